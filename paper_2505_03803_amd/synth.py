@@ -1,0 +1,167 @@
+"""Seeded synthetic workloads for the quantized-linear path.
+
+This module only draws random bytes and floats and lays them out in the
+interchange ("canonical") format; it contains none of the method's arithmetic
+(no unpacking, no dequantization, no contraction), so both the CPU oracle's
+tests and the HIP path's tests may take their inputs from it.
+
+Canonical format of one weight matrix W of shape [N, K] (N = output channels,
+K = input channels, y = x W^T):
+
+* scalar-quantized (SQ, Eq. "SQ" of Sec. 2.2): ``codes`` is uint32
+  [N, 3K/32]; row n is a little-endian bit string holding K 3-bit codes, code k
+  at bits [3k, 3k+3).  ``scales`` and ``zeros`` are fp16 bit patterns (uint16)
+  of shape [N, K/128]: one pair per group of 128 consecutive input channels.
+* vector-quantized (VQ, Eq. "VQ" of Sec. 2.2, vector dimension d = 2):
+  ``codes`` is uint32 [N, (K/2)*kbits/32]; row n holds K/2 indices of kbits
+  bits each, index j (covering columns 2j, 2j+1) at bits [kbits*j, kbits*(j+1)).
+  ``codebooks`` is fp16 bits (uint16) of shape [N/256, K/256, 2^kbits, 2]: one
+  codebook per 256 x 256 block of W.
+
+Because every 3-, 6- and 8-bit pattern is a valid code, uniformly random words
+are uniformly random codes: no packing routine is needed here.
+
+Random streams: weights of a configuration come from
+``default_rng(SeedSequence([seed, 0]))`` in matrix order (per matrix: kind
+flag, [index width], codes, scales, zeros | codebooks); activations for batch
+size M come from ``default_rng(SeedSequence([seed, 1, M]))`` in matrix order,
+so the same matrices can be paired with several batch sizes.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Iterator, Optional, Tuple
+
+import numpy as np
+
+SQ_BITS = 3
+SQ_GROUP = 128
+VQ_DIM = 2
+VQ_BLOCK = 256
+
+# name, N-as-multiple, K-as-multiple of (d, ffn): the RWKV-6 per-layer list.
+_LAYER = (
+    ("tm_receptance", "d", "d"),
+    ("tm_key", "d", "d"),
+    ("tm_value", "d", "d"),
+    ("tm_gate", "d", "d"),
+    ("tm_output", "d", "d"),
+    ("cm_key", "ffn", "d"),
+    ("cm_value", "d", "ffn"),
+    ("cm_receptance", "d", "d"),
+)
+
+
+@dataclass
+class QMatrix:
+    name: str
+    kind: str            # "sq" or "vq"
+    N: int
+    K: int
+    kbits: int           # VQ index width (6 or 8); 0 for SQ
+    codes: np.ndarray    # uint32 [N, words_per_row]
+    scales: Optional[np.ndarray] = None     # uint16 [N, K/128]  (SQ)
+    zeros: Optional[np.ndarray] = None      # uint16 [N, K/128]  (SQ)
+    codebooks: Optional[np.ndarray] = None  # uint16 [N/256, K/256, 2^kbits, 2]  (VQ)
+
+    @property
+    def packed_bytes(self) -> int:
+        """Bytes of everything that stands for W in memory."""
+        b = self.codes.nbytes
+        for a in (self.scales, self.zeros, self.codebooks):
+            if a is not None:
+                b += a.nbytes
+        return b
+
+
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    return np.asarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Nearest-even narrowing of finite float32 values to bfloat16 bit patterns."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return u.astype(np.uint16)
+
+
+def gen_sq(rng: np.random.Generator, N: int, K: int, name: str = "sq") -> QMatrix:
+    assert K % SQ_GROUP == 0 and (K * SQ_BITS) % 32 == 0
+    codes = rng.integers(0, 1 << 32, size=(N, K * SQ_BITS // 32), dtype=np.uint32)
+    scales = f32_to_f16_bits(rng.uniform(0.005, 0.02, size=(N, K // SQ_GROUP)))
+    zeros = f32_to_f16_bits(rng.uniform(0.0, 7.0, size=(N, K // SQ_GROUP)))
+    return QMatrix(name, "sq", N, K, 0, codes, scales=scales, zeros=zeros)
+
+
+def gen_vq(rng: np.random.Generator, N: int, K: int, kbits: int, name: str = "vq") -> QMatrix:
+    assert N % VQ_BLOCK == 0 and K % VQ_BLOCK == 0 and kbits in (6, 8)
+    codes = rng.integers(0, 1 << 32, size=(N, (K // VQ_DIM) * kbits // 32), dtype=np.uint32)
+    cb = rng.normal(0.0, 0.02, size=(N // VQ_BLOCK, K // VQ_BLOCK, 1 << kbits, VQ_DIM))
+    return QMatrix(name, "vq", N, K, kbits, codes, codebooks=f32_to_f16_bits(cb))
+
+
+def gen_activations(rng: np.random.Generator, M: int, K: int, dtype: str) -> np.ndarray:
+    """[M, K] standard-normal activations as fp16 or bf16 bit patterns (uint16)."""
+    a = rng.standard_normal(size=(M, K), dtype=np.float32)
+    if dtype == "f16":
+        return f32_to_f16_bits(a)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(a)
+    raise ValueError(dtype)
+
+
+def _rngs(seed: int, M: int) -> Tuple[np.random.Generator, np.random.Generator]:
+    return (np.random.default_rng(np.random.SeedSequence([seed, 0])),
+            np.random.default_rng(np.random.SeedSequence([seed, 1, M])))
+
+
+def config1(M: int = 1) -> Tuple[QMatrix, np.ndarray]:
+    """Single SQ matrix 1024 x 1024, fp16 activations, seed 0."""
+    wr, ar = _rngs(0, M)
+    return gen_sq(wr, 1024, 1024, "c1_sq"), gen_activations(ar, M, 1024, "f16")
+
+
+def config2(M: int = 1) -> Tuple[QMatrix, np.ndarray]:
+    """Single VQ matrix 4096 x 4096, 6-bit indices, fp16 activations, seed 1."""
+    wr, ar = _rngs(1, M)
+    return gen_vq(wr, 4096, 4096, 6, "c2_vq"), gen_activations(ar, M, 4096, "f16")
+
+
+STACKS = {
+    # config: (seed, d, ffn, layers, activation dtype, 8-bit-index VQ variants allowed)
+    3: (2, 4096, 14336, 32, "f16", False),
+    4: (3, 4096, 14336, 32, "bf16", False),
+    5: (4, 5120, 17920, 48, "bf16", True),
+}
+STACK_M = {3: (1,), 4: (2048,), 5: (1, 16, 4096)}
+
+
+def layer_shapes(d: int, ffn: int):
+    dims = {"d": d, "ffn": ffn}
+    return [(nm, dims[n], dims[k]) for nm, n, k in _LAYER]
+
+
+def stack(config: int, M: int, n_layers: Optional[int] = None,
+          with_activations: bool = True) -> Iterator[Tuple[QMatrix, Optional[np.ndarray]]]:
+    """Yield (matrix, activations) for the layer stack of configuration 3, 4 or 5.
+
+    Matrices come layer by layer in the fixed per-layer order; ``n_layers``
+    truncates the stack (the first layers are identical to the full stack's).
+    Each matrix is SQ or VQ with probability 1/2; in configuration 5 a VQ matrix
+    has 6- or 8-bit indices with probability 1/2 each.
+    """
+    seed, d, ffn, layers, dt, k8 = STACKS[config]
+    wr, ar = _rngs(seed, M)
+    for layer in range(layers if n_layers is None else min(n_layers, layers)):
+        for nm, N, K in layer_shapes(d, ffn):
+            name = f"L{layer}.{nm}"
+            is_sq = bool(wr.random() < 0.5)
+            if is_sq:
+                mat = gen_sq(wr, N, K, name)
+            else:
+                kbits = 6
+                if k8:
+                    kbits = 6 if wr.random() < 0.5 else 8
+                mat = gen_vq(wr, N, K, kbits, name)
+            x = gen_activations(ar, M, K, dt) if with_activations else None
+            yield mat, x
