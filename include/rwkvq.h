@@ -1,0 +1,139 @@
+/*
+ * rwkvq - weight-only-quantized linear layers of an RWKV model on one MI355X (gfx950).
+ *
+ * Every weight matrix W [N, K] (N output channels, K input channels) is stored either
+ *   - scalar-quantized (SQ): b-bit codes with one fp16 scale s and one fp16 zero point z per
+ *     group of consecutive input channels.  RWKVQuant Sec. 2.2, Eq. "SQ" defines the forward map
+ *     Q(w) = clamp(round(w/s) + z, 0, 2^b - 1); this library evaluates its inverse
+ *     Deq(q) = (q - z) * s  (one binary32 subtraction, then one binary32 multiplication), or
+ *   - vector-quantized (VQ): W viewed as (N*K/d, d) row-major vectors (d consecutive input
+ *     channels of one output row), each replaced by a k-bit index into a (2^k, d) fp16 codebook;
+ *     Deq returns the indexed codebook row.  Sec. 2.2, Eq. "VQ".
+ * Which of the two a matrix uses is the per-matrix flag phi_m of Sec. 3.1 (Eq. "optimization
+ * goal" and Eq. "multi-scale proxy"): 1 = SQ, 0 = VQ.  The library computes the linear maps
+ * y = x * Deq(W)^T that App. A.1 writes as r_t = W_r(...), k_t = W_k(...), and so on.
+ *
+ * GENERAL RULES
+ *   - Every pointer argument is a DEVICE pointer owned by the caller unless a comment says
+ *     "host".  Device pointers must be 16-byte aligned.  The library never allocates or frees
+ *     device memory and keeps no reference to a buffer after the enqueued work has finished.
+ *   - Every call validates its arguments on the host before anything is launched and returns an
+ *     rwkvq_status; on any error nothing has been enqueued.  Nothing throws or aborts.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream);
+ *     no call synchronises.
+ *   - Inputs must be finite.  Supported formats: SQ with bits = 3, group = 128; VQ with
+ *     vdim = 2, kbits = 6 or 8, block_rows = block_cols = 256.  N must be a multiple of 16 (SQ)
+ *     or of block_rows (VQ); K must be a multiple of 256.
+ *
+ * CANONICAL LAYOUT (interchange format)
+ *   A row of packed fields is an array of uint32 words read as one little-endian bit string:
+ *   bit p of the row is bit (p & 31) of word (p >> 5); field i of width b is bits [b*i, b*i+b).
+ *     SQ codes      uint32 [N][K*bits/32]        code of column k = field k of row n
+ *     SQ scales     fp16   [N][K/group]
+ *     SQ zeros      fp16   [N][K/group]
+ *     VQ indices    uint32 [N][(K/vdim)*kbits/32] index of columns (2j, 2j+1) = field j of row n
+ *     VQ codebooks  fp16   [N/block_rows][K/block_cols][2^kbits][vdim]
+ *
+ * NATIVE LAYOUT (what the fast kernels stream; produced once by rwkvq_*_prepack)
+ *   Same number of bytes as the canonical buffers, reordered into tiles of 16 rows x 256 columns
+ *   so that one wavefront reads a tile with contiguous 16-byte loads and every lane's words hold
+ *   the fields of its own matrix-core operand.  Within a tile, lane = 16*kg + r (r = row in the
+ *   tile, kg = 0..3) owns, for unit u = 0,1 and step t = 0..3, the eight columns
+ *   256*T + 128*u + 32*t + 8*kg + (0..7); its 32 fields per unit are numbered c = 8*t + j and
+ *   paired as P = c/2 (low element c even, high element c odd).
+ *     SQ codes: 384 words per tile: words [4*lane + i] (i = 0..3) then [256 + 2*lane + (i-4)]
+ *       (i = 4,5) are the lane's words L[0..5]; unit u uses L[3u .. 3u+2].  Pair P < 15 sits in
+ *       word P/5 at bits 1 + 3*(P%5) (+16 for the odd element); pair 15 is spread over bit 0
+ *       (even element) and bit 16 (odd element) of the three words, code bit b in word b.
+ *     SQ scale/zero: fp16 [N/16][K/256][16 rows][2 units][scale, zero] in one buffer.
+ *     VQ kbits = 6: same word positions; pair P < 15 is one index at bits 2 + 6*(P%5) of word
+ *       P/5; index 15 is spread over bits 0,1 of the three words, index bits 2w, 2w+1 in word w.
+ *     VQ kbits = 8: 512 words per tile: lane words L[i] = [4*lane + i] (i < 4), [256 + 4*lane
+ *       + (i-4)] (i >= 4); unit u uses L[4u .. 4u+3]; index P is byte P%4 of word P/4.
+ *     VQ codebooks are used as they are (canonical).
+ */
+#ifndef RWKVQ_H
+#define RWKVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RWKVQ_OK = 0,
+    RWKVQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    RWKVQ_ERR_SHAPE = 2,       /* M, N or K is non-positive or not a multiple of the tile/group/block size */
+    RWKVQ_ERR_UNSUPPORTED = 3, /* a format or dtype this build has no kernel for */
+    RWKVQ_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
+    RWKVQ_ERR_DEVICE = 5       /* the HIP runtime reported an error at launch */
+} rwkvq_status;
+
+typedef enum { RWKVQ_F16 = 0, RWKVQ_BF16 = 1, RWKVQ_F32 = 2 } rwkvq_dtype;
+typedef enum { RWKVQ_VQ = 0, RWKVQ_SQ = 1 } rwkvq_kind;            /* = phi_m of Sec. 3.1 */
+typedef enum { RWKVQ_CANONICAL = 0, RWKVQ_NATIVE = 1 } rwkvq_layout;
+
+/* One quantized matrix (a host struct holding device pointers). */
+typedef struct rwkvq_matrix {
+    int32_t kind;        /* rwkvq_kind */
+    int32_t layout;      /* rwkvq_layout of `codes` (and of `scales` for SQ) */
+    int32_t N, K;
+    int32_t bits, group;                            /* SQ: 3, 128 (ignored for VQ) */
+    int32_t vdim, kbits, block_rows, block_cols;    /* VQ: 2, 6|8, 256, 256 (ignored for SQ) */
+    const void* codes;     /* SQ codes or VQ indices */
+    const void* scales;    /* SQ canonical: scales; SQ native: the scale/zero buffer; VQ: NULL */
+    const void* zeros;     /* SQ canonical: zeros; otherwise NULL */
+    const void* codebooks; /* VQ: codebooks; SQ: NULL */
+} rwkvq_matrix;
+
+int rwkvq_version(void);
+const char* rwkvq_status_string(int status);
+
+/* One-time reordering canonical -> native (see the layout section above).  Output buffers have
+ * the same sizes as the inputs: codes_native K*bits/8*N bytes, sz_native 4*N*K/group bytes;
+ * indices_native (K/vdim)*kbits/8*N bytes.  Outputs must not overlap inputs. */
+int rwkvq_sq_prepack(const void* codes, const void* scales, const void* zeros, int N, int K,
+                     int bits, int group, void* codes_native, void* sz_native, void* stream);
+int rwkvq_vq_prepack(const void* indices, int N, int K, int vdim, int kbits, void* indices_native,
+                     void* stream);
+
+/* Deq(W) written out as a dense row-major [N][K] array (Sec. 2.2; "Deq" of Sec. 3.2).
+ * w_dtype = RWKVQ_F32 gives the binary32 value defined at the top of this file, bit for bit;
+ * RWKVQ_F16 / RWKVQ_BF16 give that value rounded to nearest even, which is exactly what the
+ * matrix-core path feeds its multipliers for activations of that type.  For layout =
+ * RWKVQ_NATIVE, `scales` is the scale/zero buffer and `zeros` must be NULL. */
+int rwkvq_sq_dequant(const void* codes, const void* scales, const void* zeros, int layout, int N,
+                     int K, int bits, int group, void* w_out, int w_dtype, void* stream);
+int rwkvq_vq_dequant(const void* indices, const void* codebooks, int layout, int N, int K, int vdim,
+                     int kbits, int block_rows, int block_cols, void* w_out, int w_dtype,
+                     void* stream);
+
+/* y[M][N] = x[M][K] * Deq(W)^T for one matrix (the W. products of App. A.1).
+ * x is row-major fp16 or bf16; y is row-major fp16, bf16 or fp32; products are accumulated in
+ * binary32 and y is rounded to nearest even.  The path is chosen from M and the layout:
+ *   canonical layout: a plain reference kernel (any M);
+ *   native layout, M <= 16: streaming dequant-GEMV kernels bound by HBM bandwidth;
+ *   native layout, M  > 16: tiles dequantized into LDS and multiplied on the matrix cores in
+ *                           the type of x, weights rounded to that type.
+ * x and y must not overlap. */
+int rwkvq_sq_gemm(const void* codes, const void* scales, const void* zeros, int layout,
+                  const void* x, void* y, int M, int N, int K, int bits, int group, int x_dtype,
+                  int y_dtype, void* stream);
+int rwkvq_vq_gemm(const void* indices, const void* codebooks, int layout, const void* x, void* y,
+                  int M, int N, int K, int vdim, int kbits, int block_rows, int block_cols,
+                  int x_dtype, int y_dtype, void* stream);
+
+/* The hybrid of Sec. 3.1: ys[i] = xs[i] * Deq(mats[i])^T for i < n_mats, each matrix SQ or VQ
+ * as its `kind` says, all enqueued on one stream as grouped launches (matrices share a launch;
+ * there is no ordering between matrices of one call, so no ys[i] may alias an xs[j]).
+ * `mats`, `xs` and `ys` are HOST arrays (of descriptors / device pointers) read before return.
+ * All matrices share M and the dtypes.  xs[i] is [M][mats[i].K], ys[i] is [M][mats[i].N]. */
+int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void* const* ys,
+                          int n_mats, int M, int x_dtype, int y_dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RWKVQ_H */

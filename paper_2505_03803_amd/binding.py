@@ -1,0 +1,244 @@
+"""ctypes binding of librwkvq.so: the same entry points as include/rwkvq.h, argument marshalling
+only.  PyTorch supplies device memory (tensors) and the stream; every computation runs in the
+library's HIP kernels.  There is no fallback: if the library cannot be loaded this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_int, c_int32, c_void_p
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+from . import build as _build
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_ALIGN, ERR_DEVICE = range(6)
+F16, BF16, F32 = 0, 1, 2
+VQ, SQ = 0, 1
+CANONICAL, NATIVE = 0, 1
+DTYPES = {"f16": F16, "bf16": BF16, "f32": F32}
+
+EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq_prepack",
+           "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
+           "rwkvq_linear_dispatch"]
+
+
+class rwkvq_matrix(Structure):
+    _fields_ = [("kind", c_int32), ("layout", c_int32), ("N", c_int32), ("K", c_int32),
+                ("bits", c_int32), ("group", c_int32),
+                ("vdim", c_int32), ("kbits", c_int32), ("block_rows", c_int32), ("block_cols", c_int32),
+                ("codes", c_void_p), ("scales", c_void_p), ("zeros", c_void_p), ("codebooks", c_void_p)]
+
+
+class RwkvqError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"rwkvq status {status}: {status_string(status)}")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load librwkvq.so (compiling it with hipcc only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = ctypes.CDLL(_build.LIB)
+        L.rwkvq_version.restype = c_int
+        L.rwkvq_version.argtypes = []
+        L.rwkvq_status_string.restype = c_char_p
+        L.rwkvq_status_string.argtypes = [c_int]
+        L.rwkvq_sq_prepack.restype = c_int
+        L.rwkvq_sq_prepack.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p,
+                                       c_void_p, c_void_p]
+        L.rwkvq_vq_prepack.restype = c_int
+        L.rwkvq_vq_prepack.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+        L.rwkvq_sq_dequant.restype = c_int
+        L.rwkvq_sq_dequant.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
+                                       c_void_p, c_int, c_void_p]
+        L.rwkvq_vq_dequant.restype = c_int
+        L.rwkvq_vq_dequant.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
+                                       c_void_p, c_int, c_void_p]
+        L.rwkvq_sq_gemm.restype = c_int
+        L.rwkvq_sq_gemm.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_int, c_int,
+                                    c_int, c_int, c_int, c_int, c_int, c_void_p]
+        L.rwkvq_vq_gemm.restype = c_int
+        L.rwkvq_vq_gemm.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int,
+                                    c_int, c_int, c_int, c_int, c_int, c_int, c_void_p]
+        L.rwkvq_linear_dispatch.restype = c_int
+        L.rwkvq_linear_dispatch.argtypes = [POINTER(rwkvq_matrix), POINTER(c_void_p), POINTER(c_void_p),
+                                            c_int, c_int, c_int, c_int, c_void_p]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().rwkvq_status_string(status).decode()
+
+
+def version() -> int:
+    return int(lib().rwkvq_version())
+
+
+def _check(st: int) -> None:
+    if st != OK:
+        raise RwkvqError(st)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a tensor (or pass through ints / None)."""
+    if t is None or isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+# ---- raw entry points (names as in the header); `check=False` returns the status instead --------
+
+def rwkvq_sq_prepack(codes, scales, zeros, N, K, bits, group, codes_native, sz_native, stream=None,
+                     check=True):
+    st = lib().rwkvq_sq_prepack(_ptr(codes), _ptr(scales), _ptr(zeros), N, K, bits, group,
+                                _ptr(codes_native), _ptr(sz_native), _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_vq_prepack(indices, N, K, vdim, kbits, indices_native, stream=None, check=True):
+    st = lib().rwkvq_vq_prepack(_ptr(indices), N, K, vdim, kbits, _ptr(indices_native), _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_sq_dequant(codes, scales, zeros, layout, N, K, bits, group, w_out, w_dtype, stream=None,
+                     check=True):
+    st = lib().rwkvq_sq_dequant(_ptr(codes), _ptr(scales), _ptr(zeros), layout, N, K, bits, group,
+                                _ptr(w_out), w_dtype, _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_vq_dequant(indices, codebooks, layout, N, K, vdim, kbits, block_rows, block_cols, w_out,
+                     w_dtype, stream=None, check=True):
+    st = lib().rwkvq_vq_dequant(_ptr(indices), _ptr(codebooks), layout, N, K, vdim, kbits, block_rows,
+                                block_cols, _ptr(w_out), w_dtype, _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_sq_gemm(codes, scales, zeros, layout, x, y, M, N, K, bits, group, x_dtype, y_dtype,
+                  stream=None, check=True):
+    st = lib().rwkvq_sq_gemm(_ptr(codes), _ptr(scales), _ptr(zeros), layout, _ptr(x), _ptr(y), M, N, K,
+                             bits, group, x_dtype, y_dtype, _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_vq_gemm(indices, codebooks, layout, x, y, M, N, K, vdim, kbits, block_rows, block_cols,
+                  x_dtype, y_dtype, stream=None, check=True):
+    st = lib().rwkvq_vq_gemm(_ptr(indices), _ptr(codebooks), layout, _ptr(x), _ptr(y), M, N, K, vdim,
+                             kbits, block_rows, block_cols, x_dtype, y_dtype, _stream(stream))
+    return _check(st) if check else st
+
+
+class DispatchTable:
+    """Host arrays for rwkvq_linear_dispatch, built once and reusable across calls."""
+
+    def __init__(self, descs: Sequence[rwkvq_matrix], xs: Sequence, ys: Sequence):
+        n = len(descs)
+        assert len(xs) == n and len(ys) == n
+        self.n = n
+        self.mats = (rwkvq_matrix * n)(*descs)
+        self.xs = (c_void_p * n)(*[_ptr(x) for x in xs])
+        self.ys = (c_void_p * n)(*[_ptr(y) for y in ys])
+
+
+def rwkvq_linear_dispatch(table: DispatchTable, M, x_dtype, y_dtype, stream=None, check=True):
+    st = lib().rwkvq_linear_dispatch(table.mats, table.xs, table.ys, table.n, M, x_dtype, y_dtype,
+                                     _stream(stream))
+    return _check(st) if check else st
+
+
+# ---- device-side holder of one matrix (memory plumbing for tests, smoke and bench) ---------------
+
+@dataclass
+class DeviceMatrix:
+    kind: int
+    layout: int
+    N: int
+    K: int
+    kbits: int
+    codes: object                 # torch tensors on the GPU
+    scales: object = None
+    zeros: object = None
+    codebooks: object = None
+    packed_bytes: int = 0
+
+    def desc(self) -> rwkvq_matrix:
+        d = rwkvq_matrix()
+        d.kind, d.layout, d.N, d.K = self.kind, self.layout, self.N, self.K
+        d.bits, d.group = 3, 128
+        d.vdim, d.kbits, d.block_rows, d.block_cols = 2, self.kbits, 256, 256
+        d.codes = _ptr(self.codes)
+        d.scales = _ptr(self.scales)
+        d.zeros = _ptr(self.zeros)
+        d.codebooks = _ptr(self.codebooks)
+        return d
+
+
+def upload(mat, native: bool = True, device: str = "cuda:0") -> DeviceMatrix:
+    """Copy a canonical-layout matrix record (fields kind, N, K, kbits, codes, scales, zeros,
+    codebooks as numpy arrays) to the GPU; with native=True also run the library's prepack and
+    keep only the native buffers."""
+    import numpy as np
+    import torch
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int32 if a.dtype == np.uint32 else np.int16)).to(device)
+
+    codes = dev(mat.codes)
+    if mat.kind == "sq":
+        scales, zeros = dev(mat.scales), dev(mat.zeros)
+        if not native:
+            return DeviceMatrix(SQ, CANONICAL, mat.N, mat.K, 0, codes, scales, zeros, None, mat.packed_bytes)
+        cn = torch.empty_like(codes)
+        sz = torch.empty(scales.numel() * 2, dtype=torch.int16, device=device)
+        rwkvq_sq_prepack(codes, scales, zeros, mat.N, mat.K, 3, 128, cn, sz)
+        torch.cuda.synchronize()
+        return DeviceMatrix(SQ, NATIVE, mat.N, mat.K, 0, cn, sz, None, None, mat.packed_bytes)
+    cb = dev(mat.codebooks)
+    if not native:
+        return DeviceMatrix(VQ, CANONICAL, mat.N, mat.K, mat.kbits, codes, None, None, cb, mat.packed_bytes)
+    cn = torch.empty_like(codes)
+    rwkvq_vq_prepack(codes, mat.N, mat.K, 2, mat.kbits, cn)
+    torch.cuda.synchronize()
+    return DeviceMatrix(VQ, NATIVE, mat.N, mat.K, mat.kbits, cn, None, None, cb, mat.packed_bytes)
+
+
+def dequant(dm: DeviceMatrix, w_dtype: int = F32, stream=None):
+    """Dense Deq(W) [N, K] on the GPU as a torch tensor (float32, or int16 bit patterns)."""
+    import torch
+    out = torch.empty((dm.N, dm.K), dtype=torch.float32 if w_dtype == F32 else torch.int16,
+                      device=dm.codes.device)
+    if dm.kind == SQ:
+        rwkvq_sq_dequant(dm.codes, dm.scales, dm.zeros, dm.layout, dm.N, dm.K, 3, 128, out, w_dtype, stream)
+    else:
+        rwkvq_vq_dequant(dm.codes, dm.codebooks, dm.layout, dm.N, dm.K, 2, dm.kbits, 256, 256, out, w_dtype,
+                         stream)
+    return out
+
+
+def gemm(dm: DeviceMatrix, x, M: int, x_dtype: int, y_dtype: int = F32, stream=None):
+    """y [M, N] = x [M, K] Deq(W)^T through rwkvq_sq_gemm / rwkvq_vq_gemm; x is an int16 tensor
+    of fp16 / bf16 bit patterns on the GPU."""
+    import torch
+    y = torch.empty((M, dm.N), dtype=torch.float32 if y_dtype == F32 else torch.int16, device=x.device)
+    if dm.kind == SQ:
+        rwkvq_sq_gemm(dm.codes, dm.scales, dm.zeros, dm.layout, x, y, M, dm.N, dm.K, 3, 128, x_dtype,
+                      y_dtype, stream)
+    else:
+        rwkvq_vq_gemm(dm.codes, dm.codebooks, dm.layout, x, y, M, dm.N, dm.K, 2, dm.kbits, 256, 256,
+                      x_dtype, y_dtype, stream)
+    return y

@@ -1,0 +1,184 @@
+// The C ABI of librwkvq (declared in include/rwkvq.h): argument validation on the host, then
+// the launch.  No entry point allocates device memory or synchronises.
+#include "common.h"
+#include "../../include/rwkvq.h"
+
+#include <vector>
+
+using namespace rwkvq;
+
+namespace {
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int check_dtype_x(int dt) { return (dt == RWKVQ_F16 || dt == RWKVQ_BF16) ? RWKVQ_OK : RWKVQ_ERR_UNSUPPORTED; }
+int check_dtype_y(int dt) {
+    return (dt == RWKVQ_F16 || dt == RWKVQ_BF16 || dt == RWKVQ_F32) ? RWKVQ_OK : RWKVQ_ERR_UNSUPPORTED;
+}
+
+int check_sq_format(int N, int K, int bits, int group) {
+    if (bits != 3 || group != kGroup) return RWKVQ_ERR_UNSUPPORTED;
+    if (N <= 0 || K <= 0 || N % kTileRows != 0 || K % kTileCols != 0) return RWKVQ_ERR_SHAPE;
+    return RWKVQ_OK;
+}
+int check_vq_format(int N, int K, int vdim, int kbits, int br, int bc) {
+    if (vdim != 2 || (kbits != 6 && kbits != 8) || br != kBlock || bc != kBlock) return RWKVQ_ERR_UNSUPPORTED;
+    if (N <= 0 || K <= 0 || N % kBlock != 0 || K % kBlock != 0) return RWKVQ_ERR_SHAPE;
+    return RWKVQ_OK;
+}
+int check_layout(int layout) {
+    return (layout == RWKVQ_CANONICAL || layout == RWKVQ_NATIVE) ? RWKVQ_OK : RWKVQ_ERR_UNSUPPORTED;
+}
+
+// Validate one descriptor and translate it for the kernels.
+int to_dev(const rwkvq_matrix& m, const void* x, void* y, MatDev* out) {
+    int st;
+    if ((st = check_layout(m.layout)) != RWKVQ_OK) return st;
+    if (m.kind == RWKVQ_SQ) {
+        if ((st = check_sq_format(m.N, m.K, m.bits, m.group)) != RWKVQ_OK) return st;
+        if (!m.codes || !m.scales) return RWKVQ_ERR_NULL;
+        if (m.layout == RWKVQ_CANONICAL && !m.zeros) return RWKVQ_ERR_NULL;
+        if (m.layout == RWKVQ_NATIVE && m.zeros) return RWKVQ_ERR_UNSUPPORTED;
+        if (!aligned16(m.codes) || !aligned16(m.scales) || !aligned16(m.zeros)) return RWKVQ_ERR_ALIGN;
+        *out = MatDev{(const uint32_t*)m.codes, (const uint16_t*)m.scales, (const uint16_t*)m.zeros, x, y,
+                      m.N, m.K, FMT_SQ3, m.layout};
+    } else if (m.kind == RWKVQ_VQ) {
+        if ((st = check_vq_format(m.N, m.K, m.vdim, m.kbits, m.block_rows, m.block_cols)) != RWKVQ_OK) return st;
+        if (!m.codes || !m.codebooks) return RWKVQ_ERR_NULL;
+        if (!aligned16(m.codes) || !aligned16(m.codebooks)) return RWKVQ_ERR_ALIGN;
+        *out = MatDev{(const uint32_t*)m.codes, (const uint16_t*)m.codebooks, nullptr, x, y, m.N, m.K,
+                      m.kbits == 8 ? FMT_VQ8 : FMT_VQ6, m.layout};
+    } else {
+        return RWKVQ_ERR_UNSUPPORTED;
+    }
+    return RWKVQ_OK;
+}
+
+int finish(hipError_t e) { return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE; }
+
+rwkvq_matrix sq_desc(const void* codes, const void* scales, const void* zeros, int layout, int N, int K,
+                     int bits, int group) {
+    rwkvq_matrix m{};
+    m.kind = RWKVQ_SQ; m.layout = layout; m.N = N; m.K = K; m.bits = bits; m.group = group;
+    m.codes = codes; m.scales = scales; m.zeros = zeros;
+    return m;
+}
+rwkvq_matrix vq_desc(const void* indices, const void* codebooks, int layout, int N, int K, int vdim,
+                     int kbits, int br, int bc) {
+    rwkvq_matrix m{};
+    m.kind = RWKVQ_VQ; m.layout = layout; m.N = N; m.K = K; m.vdim = vdim; m.kbits = kbits;
+    m.block_rows = br; m.block_cols = bc; m.codes = indices; m.codebooks = codebooks;
+    return m;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rwkvq_version(void) { return 100; }
+
+const char* rwkvq_status_string(int status) {
+    switch (status) {
+        case RWKVQ_OK: return "ok";
+        case RWKVQ_ERR_NULL: return "null pointer";
+        case RWKVQ_ERR_SHAPE: return "bad shape";
+        case RWKVQ_ERR_UNSUPPORTED: return "unsupported format or dtype";
+        case RWKVQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case RWKVQ_ERR_DEVICE: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+int rwkvq_sq_prepack(const void* codes, const void* scales, const void* zeros, int N, int K, int bits,
+                     int group, void* codes_native, void* sz_native, void* stream) {
+    int st = check_sq_format(N, K, bits, group);
+    if (st != RWKVQ_OK) return st;
+    if (!codes || !scales || !zeros || !codes_native || !sz_native) return RWKVQ_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(zeros) || !aligned16(codes_native) ||
+        !aligned16(sz_native))
+        return RWKVQ_ERR_ALIGN;
+    return finish(launch_sq_prepack((const uint32_t*)codes, (const uint16_t*)scales, (const uint16_t*)zeros,
+                                    N, K, (uint32_t*)codes_native, (uint16_t*)sz_native, (hipStream_t)stream));
+}
+
+int rwkvq_vq_prepack(const void* indices, int N, int K, int vdim, int kbits, void* indices_native,
+                     void* stream) {
+    int st = check_vq_format(N, K, vdim, kbits, kBlock, kBlock);
+    if (st != RWKVQ_OK) return st;
+    if (!indices || !indices_native) return RWKVQ_ERR_NULL;
+    if (!aligned16(indices) || !aligned16(indices_native)) return RWKVQ_ERR_ALIGN;
+    return finish(launch_vq_prepack((const uint32_t*)indices, N, K, kbits, (uint32_t*)indices_native,
+                                    (hipStream_t)stream));
+}
+
+int rwkvq_sq_dequant(const void* codes, const void* scales, const void* zeros, int layout, int N, int K,
+                     int bits, int group, void* w_out, int w_dtype, void* stream) {
+    MatDev d;
+    int st = to_dev(sq_desc(codes, scales, zeros, layout, N, K, bits, group), nullptr, nullptr, &d);
+    if (st != RWKVQ_OK) return st;
+    if ((st = check_dtype_y(w_dtype)) != RWKVQ_OK) return st;
+    if (!w_out) return RWKVQ_ERR_NULL;
+    if (!aligned16(w_out)) return RWKVQ_ERR_ALIGN;
+    return finish(launch_dequant(d, w_out, w_dtype, (hipStream_t)stream));
+}
+
+int rwkvq_vq_dequant(const void* indices, const void* codebooks, int layout, int N, int K, int vdim,
+                     int kbits, int block_rows, int block_cols, void* w_out, int w_dtype, void* stream) {
+    MatDev d;
+    int st = to_dev(vq_desc(indices, codebooks, layout, N, K, vdim, kbits, block_rows, block_cols), nullptr,
+                    nullptr, &d);
+    if (st != RWKVQ_OK) return st;
+    if ((st = check_dtype_y(w_dtype)) != RWKVQ_OK) return st;
+    if (!w_out) return RWKVQ_ERR_NULL;
+    if (!aligned16(w_out)) return RWKVQ_ERR_ALIGN;
+    return finish(launch_dequant(d, w_out, w_dtype, (hipStream_t)stream));
+}
+
+int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void* const* ys, int n_mats,
+                          int M, int x_dtype, int y_dtype, void* stream) {
+    if (!mats || !xs || !ys) return RWKVQ_ERR_NULL;
+    if (n_mats <= 0 || M <= 0 || M > (1 << 19)) return RWKVQ_ERR_SHAPE;
+    int st;
+    if ((st = check_dtype_x(x_dtype)) != RWKVQ_OK) return st;
+    if ((st = check_dtype_y(y_dtype)) != RWKVQ_OK) return st;
+    std::vector<MatDev> decode, prefill, ref;
+    for (int i = 0; i < n_mats; ++i) {
+        if (!xs[i] || !ys[i]) return RWKVQ_ERR_NULL;
+        if (!aligned16(xs[i]) || !aligned16(ys[i])) return RWKVQ_ERR_ALIGN;
+        MatDev d;
+        if ((st = to_dev(mats[i], xs[i], ys[i], &d)) != RWKVQ_OK) return st;
+        if (d.layout == RWKVQ_CANONICAL) ref.push_back(d);
+        else if (M <= kDecodeMaxM) decode.push_back(d);
+        else if (d.N % 256 == 0) prefill.push_back(d);
+        else ref.push_back(d);   // matrix-core tiles are 256 rows of W wide
+    }
+    hipStream_t s = (hipStream_t)stream;
+    for (const MatDev& d : ref) {
+        hipError_t e = launch_ref_gemm(d, M, x_dtype, y_dtype, s);
+        if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
+    }
+    if (!decode.empty()) {
+        hipError_t e = launch_decode(decode.data(), (int)decode.size(), M, x_dtype, y_dtype, s);
+        if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
+    }
+    if (!prefill.empty()) {
+        hipError_t e = launch_prefill(prefill.data(), (int)prefill.size(), M, x_dtype, y_dtype, s);
+        if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
+    }
+    return RWKVQ_OK;
+}
+
+int rwkvq_sq_gemm(const void* codes, const void* scales, const void* zeros, int layout, const void* x,
+                  void* y, int M, int N, int K, int bits, int group, int x_dtype, int y_dtype, void* stream) {
+    rwkvq_matrix m = sq_desc(codes, scales, zeros, layout, N, K, bits, group);
+    return rwkvq_linear_dispatch(&m, &x, &y, 1, M, x_dtype, y_dtype, stream);
+}
+
+int rwkvq_vq_gemm(const void* indices, const void* codebooks, int layout, const void* x, void* y, int M,
+                  int N, int K, int vdim, int kbits, int block_rows, int block_cols, int x_dtype,
+                  int y_dtype, void* stream) {
+    rwkvq_matrix m = vq_desc(indices, codebooks, layout, N, K, vdim, kbits, block_rows, block_cols);
+    return rwkvq_linear_dispatch(&m, &x, &y, 1, M, x_dtype, y_dtype, stream);
+}
+
+}  // extern "C"

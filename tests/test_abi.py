@@ -1,0 +1,106 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before anything is launched (so no GPU is needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_03803_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a non-null, 16-byte aligned address that is never dereferenced
+
+
+def test_exports_match_header():
+    hdr = open(os.path.join(ROOT, "include", "rwkvq.h")).read()
+    declared = sorted(set(re.findall(r"\b(rwkvq_[a-z0-9_]+)\s*\(", hdr)))
+    assert declared == sorted(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert B.version() >= 100
+
+
+def test_status_strings():
+    seen = {B.status_string(i) for i in range(6)}
+    assert len(seen) == 6 and B.status_string(0) == "ok" and B.status_string(99) == "unknown status"
+
+
+def test_matrix_struct_layout_matches_header():
+    # ten int32 then four pointers, no padding surprises
+    assert ctypes.sizeof(B.rwkvq_matrix) == 10 * 4 + 4 * 8
+    assert B.rwkvq_matrix.codes.offset == 40
+
+
+def sq_gemm(**kw):
+    a = dict(codes=FAKE, scales=FAKE, zeros=FAKE, layout=B.CANONICAL, x=FAKE, y=FAKE, M=1, N=1024, K=1024,
+             bits=3, group=128, x_dtype=B.F16, y_dtype=B.F32)
+    a.update(kw)
+    return B.lib().rwkvq_sq_gemm(a["codes"], a["scales"], a["zeros"], a["layout"], a["x"], a["y"], a["M"],
+                                 a["N"], a["K"], a["bits"], a["group"], a["x_dtype"], a["y_dtype"], None)
+
+
+def vq_gemm(**kw):
+    a = dict(indices=FAKE, codebooks=FAKE, layout=B.CANONICAL, x=FAKE, y=FAKE, M=1, N=512, K=512, vdim=2,
+             kbits=6, br=256, bc=256, x_dtype=B.F16, y_dtype=B.F32)
+    a.update(kw)
+    return B.lib().rwkvq_vq_gemm(a["indices"], a["codebooks"], a["layout"], a["x"], a["y"], a["M"], a["N"],
+                                 a["K"], a["vdim"], a["kbits"], a["br"], a["bc"], a["x_dtype"], a["y_dtype"],
+                                 None)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(codes=None), B.ERR_NULL), (dict(scales=None), B.ERR_NULL), (dict(zeros=None), B.ERR_NULL),
+    (dict(x=None), B.ERR_NULL), (dict(y=None), B.ERR_NULL),
+    (dict(M=0), B.ERR_SHAPE), (dict(N=0), B.ERR_SHAPE), (dict(N=1000), B.ERR_SHAPE),
+    (dict(K=1000), B.ERR_SHAPE), (dict(K=128), B.ERR_SHAPE), (dict(K=-256), B.ERR_SHAPE),
+    (dict(bits=4), B.ERR_UNSUPPORTED), (dict(group=64), B.ERR_UNSUPPORTED),
+    (dict(x_dtype=B.F32), B.ERR_UNSUPPORTED), (dict(y_dtype=7), B.ERR_UNSUPPORTED),
+    (dict(layout=5), B.ERR_UNSUPPORTED),
+    (dict(layout=B.NATIVE), B.ERR_UNSUPPORTED),          # native layout has no separate zeros buffer
+    (dict(codes=FAKE + 4), B.ERR_ALIGN), (dict(x=FAKE + 8), B.ERR_ALIGN), (dict(y=FAKE + 2), B.ERR_ALIGN),
+])
+def test_sq_gemm_rejects(kw, status):
+    assert sq_gemm(**kw) == status
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(indices=None), B.ERR_NULL), (dict(codebooks=None), B.ERR_NULL),
+    (dict(N=128), B.ERR_SHAPE), (dict(K=384), B.ERR_SHAPE), (dict(M=-1), B.ERR_SHAPE),
+    (dict(vdim=4), B.ERR_UNSUPPORTED), (dict(kbits=7), B.ERR_UNSUPPORTED), (dict(br=128), B.ERR_UNSUPPORTED),
+    (dict(bc=512), B.ERR_UNSUPPORTED), (dict(codebooks=FAKE + 1), B.ERR_ALIGN),
+])
+def test_vq_gemm_rejects(kw, status):
+    assert vq_gemm(**kw) == status
+
+
+def test_prepack_and_dequant_reject():
+    L = B.lib()
+    assert L.rwkvq_sq_prepack(FAKE, FAKE, FAKE, 1024, 1024, 3, 128, None, FAKE, None) == B.ERR_NULL
+    assert L.rwkvq_sq_prepack(FAKE, FAKE, FAKE, 1024, 1000, 3, 128, FAKE, FAKE, None) == B.ERR_SHAPE
+    assert L.rwkvq_sq_prepack(FAKE, FAKE, FAKE, 1024, 1024, 2, 128, FAKE, FAKE, None) == B.ERR_UNSUPPORTED
+    assert L.rwkvq_vq_prepack(FAKE, 512, 512, 2, 6, FAKE + 4, None) == B.ERR_ALIGN
+    assert L.rwkvq_vq_prepack(None, 512, 512, 2, 6, FAKE, None) == B.ERR_NULL
+    assert L.rwkvq_sq_dequant(FAKE, FAKE, FAKE, 0, 1024, 1024, 3, 128, None, B.F32, None) == B.ERR_NULL
+    assert L.rwkvq_sq_dequant(FAKE, FAKE, FAKE, 0, 1024, 1024, 3, 128, FAKE, 9, None) == B.ERR_UNSUPPORTED
+    assert L.rwkvq_vq_dequant(FAKE, FAKE, 0, 512, 512, 2, 6, 256, 256, FAKE + 8, B.F32, None) == B.ERR_ALIGN
+    assert L.rwkvq_vq_dequant(FAKE, FAKE, 0, 512, 500, 2, 6, 256, 256, FAKE, B.F32, None) == B.ERR_SHAPE
+
+
+def test_dispatch_rejects():
+    L = B.lib()
+    d = B.rwkvq_matrix()
+    d.kind, d.layout, d.N, d.K, d.bits, d.group = B.SQ, B.CANONICAL, 1024, 1024, 3, 128
+    d.codes = d.scales = d.zeros = FAKE
+    mats = (B.rwkvq_matrix * 1)(d)
+    xs = (ctypes.c_void_p * 1)(FAKE)
+    ys = (ctypes.c_void_p * 1)(FAKE)
+    assert L.rwkvq_linear_dispatch(None, xs, ys, 1, 1, B.F16, B.F32, None) == B.ERR_NULL
+    assert L.rwkvq_linear_dispatch(mats, xs, ys, 0, 1, B.F16, B.F32, None) == B.ERR_SHAPE
+    assert L.rwkvq_linear_dispatch(mats, xs, ys, 1, 0, B.F16, B.F32, None) == B.ERR_SHAPE
+    ys0 = (ctypes.c_void_p * 1)(None)
+    assert L.rwkvq_linear_dispatch(mats, xs, ys0, 1, 1, B.F16, B.F32, None) == B.ERR_NULL
+    d.kind = 3
+    mats = (B.rwkvq_matrix * 1)(d)
+    assert L.rwkvq_linear_dispatch(mats, xs, ys, 1, 1, B.F16, B.F32, None) == B.ERR_UNSUPPORTED

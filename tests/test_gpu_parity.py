@@ -1,0 +1,206 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: dequantized weights bit-exact; outputs within max relative error 2e-3 (see gpu_util)."""
+import numpy as np
+import pytest
+
+from oracle import rwkvq_oracle as orc
+from paper_2505_03803_amd import binding as B
+from paper_2505_03803_amd import synth
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def make(fmt, N, K, seed):
+    rng = np.random.default_rng(seed)
+    if fmt == "sq":
+        return synth.gen_sq(rng, N, K)
+    return synth.gen_vq(rng, N, K, 6 if fmt == "vq6" else 8)
+
+
+def acts(M, K, dtype, seed):
+    return synth.gen_activations(np.random.default_rng(seed + 99), M, K, dtype)
+
+
+SMALL = [("sq", 48, 768), ("sq", 256, 256), ("vq6", 256, 768), ("vq6", 512, 256), ("vq8", 256, 768),
+         ("vq8", 512, 512)]
+
+
+# ------------------------------------------------------------------ dequantization
+
+@pytest.mark.parametrize("fmt,N,K", SMALL)
+@pytest.mark.parametrize("native", [False, True])
+def test_dequant_bit_exact(fmt, N, K, native):
+    print(f"dequant {fmt} N={N} K={K} native={native}", flush=True)
+    mat = make(fmt, N, K, 1)
+    want = orc.dequant(mat)
+    dm = B.upload(mat, native=native)
+    got = G.gpu_dequant(dm)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    for name, code in (("bf16", B.BF16), ("f16", B.F16)):
+        got16 = G.gpu_dequant(dm, code)
+        want16 = orc.round_weights(want, name)
+        back = orc.widen(got16, name)
+        assert np.array_equal(back.view(np.uint32), want16.view(np.uint32)), name
+
+
+def test_dequant_rounding_order_cases(golden_dir):
+    # tiny zero points, where (q - z) itself rounds: the kernel must subtract, then multiply
+    import os
+    rows = [l.split() for l in open(os.path.join(golden_dir, "sq_rounding_cases.txt")) if not l.startswith("#")]
+    mat = make("sq", 16, 256, 3)
+    mat.codes[:] = 0
+    expect = {}
+    for i, (tag, q, zb, sb, a, *_rest) in enumerate(rows):
+        n = i
+        mat.scales[n, :] = int(sb, 16)
+        mat.zeros[n, :] = int(zb, 16)
+        mat.codes[n, 0] = int(q)            # code of column 0 = low 3 bits of word 0
+        expect[n] = int(a, 16)
+    for native in (False, True):
+        got = G.gpu_dequant(B.upload(mat, native=native)).view(np.uint32)
+        for n, a in expect.items():
+            assert int(got[n, 0]) == a
+    assert np.array_equal(orc.dequant(mat).view(np.uint32), got)
+
+
+# ------------------------------------------------------------------ GEMV / GEMM on small shapes
+
+@pytest.mark.parametrize("fmt,N,K", SMALL)
+@pytest.mark.parametrize("M", [1, 3, 4, 7, 16])
+@pytest.mark.parametrize("xdt", ["f16", "bf16"])
+def test_decode_small(fmt, N, K, M, xdt):
+    print(f"decode {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+    mat = make(fmt, N, K, 2)
+    x = acts(M, K, xdt, M)
+    y = G.gpu_gemm(B.upload(mat, native=True), x, xdt)
+    G.check_outputs(y, mat, x, xdt, fed=None, tight=2e-5)
+
+
+@pytest.mark.parametrize("fmt,N,K", [("sq", 256, 768), ("vq6", 256, 768), ("vq8", 512, 512)])
+@pytest.mark.parametrize("M", [17, 256, 300])
+@pytest.mark.parametrize("xdt", ["bf16", "f16"])
+def test_prefill_small(fmt, N, K, M, xdt):
+    print(f"prefill {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+    mat = make(fmt, N, K, 4)
+    x = acts(M, K, xdt, M)
+    y = G.gpu_gemm(B.upload(mat, native=True), x, xdt)
+    G.check_outputs(y, mat, x, xdt, fed=xdt, tight=2e-5)
+
+
+@pytest.mark.parametrize("fmt,N,K", SMALL)
+@pytest.mark.parametrize("M", [1, 9])
+def test_reference_kernel_canonical(fmt, N, K, M):
+    print(f"ref {fmt} N={N} K={K} M={M}", flush=True)
+    mat = make(fmt, N, K, 5)
+    x = acts(M, K, "f16", M)
+    y = G.gpu_gemm(B.upload(mat, native=False), x, "f16")
+    G.check_outputs(y, mat, x, "f16", fed=None, tight=2e-5)
+
+
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+def test_one_hot_returns_weight_column(fmt):
+    mat = make(fmt, 256, 512, 6)
+    w = orc.dequant(mat)
+    dm = B.upload(mat, native=True)
+    for k in (0, 7, 127, 128, 255, 256, 511):
+        x = np.zeros((1, 512), np.float32)
+        x[0, k] = 1.0
+        y = G.gpu_gemm(dm, synth.f32_to_f16_bits(x), "f16")[0]
+        if fmt == "sq":       # (8 + q) - (z + 8) rounds once more than q - z when z is tiny
+            assert np.allclose(y, w[:, k], rtol=1e-6, atol=0)
+        else:
+            assert np.array_equal(y, w[:, k].astype(np.float64))
+
+
+@pytest.mark.parametrize("ydt", ["f16", "bf16"])
+def test_output_rounding(ydt):
+    mat = make("sq", 256, 512, 7)
+    x = acts(2, 512, "f16", 1)
+    dm = B.upload(mat, native=True)
+    y32 = G.gpu_gemm(dm, x, "f16", B.F32)
+    y16 = G.gpu_gemm(dm, x, "f16", B.DTYPES[ydt])
+    want = orc.narrow(y32.astype(np.float32), ydt)
+    assert np.array_equal(y16, want)
+
+
+def test_dispatch_equals_single_calls():
+    torch = G.torch_()
+    mats = [make("sq", 256, 768, 10), make("vq6", 512, 256, 11), make("vq8", 256, 512, 12),
+            make("sq", 48, 256, 13), make("vq6", 256, 1024, 14)]
+    for M, xdt in ((1, "f16"), (4, "bf16"), (16, "bf16"), (40, "bf16")):
+        dms = [B.upload(m, native=True) for m in mats]
+        xs = [G.to_dev_bits(acts(M, m.K, xdt, i)) for i, m in enumerate(mats)]
+        ys = [torch.empty((M, m.N), dtype=torch.float32, device="cuda") for m in mats]
+        table = B.DispatchTable([d.desc() for d in dms], xs, ys)
+        B.rwkvq_linear_dispatch(table, M, B.DTYPES[xdt], B.F32)
+        torch.cuda.synchronize()
+        for dm, x, y in zip(dms, xs, ys):
+            single = B.gemm(dm, x, M, B.DTYPES[xdt], B.F32)
+            torch.cuda.synchronize()
+            assert torch.equal(single, y)
+
+
+# ------------------------------------------------------------------ the configurations
+
+def test_config1_full():
+    mat, x = synth.config1()
+    dm = B.upload(mat, native=True)
+    assert np.array_equal(G.gpu_dequant(dm).view(np.uint32), orc.dequant(mat).view(np.uint32))
+    y = G.gpu_gemm(dm, x, "f16")
+    print("config1", G.check_outputs(y, mat, x, "f16", tight=2e-5), flush=True)
+
+
+def test_config2_full():
+    mat, x = synth.config2()
+    dm = B.upload(mat, native=True)
+    assert np.array_equal(G.gpu_dequant(dm).view(np.uint32), orc.dequant(mat).view(np.uint32))
+    y = G.gpu_gemm(dm, x, "f16")
+    print("config2", G.check_outputs(y, mat, x, "f16", tight=2e-5), flush=True)
+
+
+def _stack_layer_check(config, M, n_layers, rows=None, fed=None, tight=None):
+    """Run the first layers of a stack through one rwkvq_linear_dispatch call and check every
+    matrix; with `rows`, only those activation rows are checked against the oracle."""
+    torch = G.torch_()
+    xdt = synth.STACKS[config][4]
+    items = list(synth.stack(config, M, n_layers=n_layers))
+    dms = [B.upload(m, native=True) for m, _ in items]
+    xs = [G.to_dev_bits(x) for _, x in items]
+    ys = [torch.empty((M, m.N), dtype=torch.float32, device="cuda") for m, _ in items]
+    table = B.DispatchTable([d.desc() for d in dms], xs, ys)
+    B.rwkvq_linear_dispatch(table, M, B.DTYPES[xdt], B.F32)
+    torch.cuda.synchronize()
+    worst = (0.0, 0.0)
+    for (mat, x), dm, y in zip(items, dms, ys):
+        got = G.gpu_dequant(dm)
+        assert np.array_equal(got.view(np.uint32), orc.dequant(mat).view(np.uint32)), mat.name
+        del got
+        yy = y.cpu().numpy().astype(np.float64)
+        if rows is not None:
+            yy, x = yy[rows], x[rows]
+        g = G.check_outputs(yy, mat, x, xdt, fed=fed, tight=tight)
+        worst = (max(worst[0], g[0]), max(worst[1], g[1]))
+        print(f"  cfg{config} M={M} {mat.name} {mat.kind}{mat.kbits or ''} g1={g[0]:.2e} g2={g[1]:.2e}", flush=True)
+    return worst
+
+
+def test_config3_decode_layers():
+    print("config3", _stack_layer_check(3, 1, n_layers=2, tight=2e-5), flush=True)
+
+
+def test_config4_prefill_layer_sampled_rows():
+    rows = np.random.default_rng(0).choice(2048, size=8, replace=False)
+    print("config4", _stack_layer_check(4, 2048, n_layers=1, rows=np.sort(rows), fed="bf16", tight=2e-5), flush=True)
+
+
+@pytest.mark.parametrize("M", [1, 16])
+def test_config5_decode_layer(M):
+    print("config5", M, _stack_layer_check(5, M, n_layers=1, tight=2e-5), flush=True)
+
+
+def test_config5_prefill_layer_sampled_rows():
+    rows = np.sort(np.random.default_rng(1).choice(4096, size=4, replace=False))
+    print("config5 prefill", _stack_layer_check(5, 4096, n_layers=1, rows=rows, fed="bf16", tight=2e-5), flush=True)
