@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-linear hot path on one MI355X.
+
+A step is one pass of the whole RWKV-6-7B-shaped layer stack (32 layers x 8 matrices, each SQ or VQ
+by a seeded coin flip) through rwkvq_linear_dispatch:
+
+  * decode leg (the headline `value`): batch 1, fp16 activations, one independent activation
+    vector per matrix; metric = packed weight bytes read per second (GB/s) and the fraction of
+    the 8 TB/s HBM peak;
+  * prefill leg (reported under "prefill"): the same matrix recipe at M = 2048 tokens, bf16
+    activations, bf16 MFMA with binary32 accumulate; metric = 2*M*N*K FLOP per second and the
+    fraction of the 2.5 PFLOP/s dense bf16 peak.
+
+All inputs are resident in HBM before the timed region.  Timing uses HIP events on the stream
+the kernels are launched on.  The CPU oracle is timed on the host cores on the same decode
+workload as a reported baseline.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+DECODE_KERNEL = "decode_kernel<1>"
+PREFILL_KERNEL = "prefill_kernel<bf16>"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_stack(config: int, M: int, n_layers, gpu_activations: bool, y_dtype):
+    """Upload the stack (native layout) and allocate activations / outputs.  Returns the dispatch
+    table and the byte / FLOP counts."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    from paper_2505_03803_amd import synth
+
+    xdt = synth.STACKS[config][4]
+    descs, xs, ys, keep = [], [], [], []
+    wbytes = 0
+    flops = 0
+    xbytes = 0
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1000 + config)
+    for mat, x in synth.stack(config, M, n_layers=n_layers, with_activations=not gpu_activations):
+        dm = B.upload(mat, native=True)
+        wbytes += mat.packed_bytes
+        flops += 2 * M * mat.N * mat.K
+        if gpu_activations:
+            xf = torch.randn((M, mat.K), device="cuda", generator=gen, dtype=torch.float32)
+            xd = xf.to(torch.bfloat16 if xdt == "bf16" else torch.float16).view(torch.int16)
+            del xf
+        else:
+            xd = torch.from_numpy(x.view(np.int16)).cuda()
+        yd = torch.empty((M, mat.N), dtype=torch.float32 if y_dtype == B.F32 else torch.int16, device="cuda")
+        xbytes += xd.numel() * 2 + yd.numel() * yd.element_size()
+        descs.append(dm.desc()); xs.append(xd); ys.append(yd); keep.append(dm)
+    table = B.DispatchTable(descs, xs, ys)
+    return dict(table=table, keep=(keep, xs, ys), wbytes=wbytes, flops=flops, xybytes=xbytes,
+                n_mats=len(descs), x_dtype=B.DTYPES[xdt])
+
+
+def time_steps(run, steps: int, warmup: int):
+    """W untimed steps, then exactly K steps bracketed by synchronize + HIP events on the current
+    stream.  Returns (total ms over K steps, per-step ms list)."""
+    import torch
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        run()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return ev[0].elapsed_time(ev[steps]), per, wall_ms
+
+
+def cpu_baseline(n_layers):
+    """The oracle as it stands on the host cores: decode (M = 1) over the first n_layers layers of
+    the same stack (all 32 by default = the whole workload)."""
+    from oracle import rwkvq_oracle as orc
+    from paper_2505_03803_amd import synth
+    nbytes, secs = 0, 0.0
+    for mat, x in synth.stack(3, 1, n_layers=n_layers):
+        xf = orc.widen(x, "f16")
+        t = time.perf_counter()
+        orc.linear(mat, xf, "f32")
+        secs += time.perf_counter() - t
+        nbytes += mat.packed_bytes
+    return {"value": nbytes / secs / 1e9, "unit": "GB/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"decode M=1, first {n_layers} of 32 layers of the RWKV-6-7B-shaped stack "
+                      f"({nbytes} packed weight bytes, {secs:.2f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32, help="layers of the stack (32 = the full workload)")
+    ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); a multi-GPU figure is not "
+                 "part of it - see DESIGN.md for how the path would shard.")
+
+    import torch
+    from paper_2505_03803_amd import binding as B
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()                                    # fails loudly if the HIP library is missing
+
+    # ---------------- decode leg: configuration 3
+    t = time.time()
+    dec = build_stack(3, 1, args.layers, gpu_activations=False, y_dtype=B.F16)
+    log(f"decode stack resident: {dec['n_mats']} matrices, {dec['wbytes'] / 1e9:.3f} GB packed, {time.time() - t:.1f} s")
+    run = lambda: B.rwkvq_linear_dispatch(dec["table"], 1, dec["x_dtype"], B.F16)
+    total_ms, per, wall_ms = time_steps(run, args.steps, args.warmup)
+    ms = total_ms / args.steps
+    gbs = dec["wbytes"] / (ms * 1e-3) / 1e9
+    launches = (dec["n_mats"] + 31) // 32
+    out = {
+        "metric": "dequant-GEMV weight GB/s (% of HBM peak) + prefill TFLOP/s, RWKV-6-7B shapes",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "configs[2]: RWKV-6-7B-shaped decode stack, %d layers x 8 matrices, "
+                               "d=4096 ffn=14336, batch 1, SQ 3-bit g128 / VQ d=2 6-bit per matrix "
+                               "(Bernoulli 0.5, seed 2), fp16 activations" % args.layers,
+                   "weight_bytes_per_step": dec["wbytes"], "matrices": dec["n_mats"],
+                   "launches_per_step": launches},
+        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "tokens_per_s": 1e3 / ms,
+        "ms_per_step_min": min(per), "ms_per_step_median": float(np.median(per)),
+        "wall_ms_per_step": wall_ms / args.steps,
+        "roofline": {"kernel": DECODE_KERNEL, "bound": "hbm",
+                     "achieved": dec["wbytes"] / launches / (ms / launches * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": dec["wbytes"] / launches,
+                     "avg_launch_ms": ms / launches},
+    }
+    del dec, run
+    torch.cuda.empty_cache()
+
+    # ---------------- prefill leg: configuration 4
+    if not args.skip_prefill:
+        t = time.time()
+        pf = build_stack(4, 2048, args.layers, gpu_activations=True, y_dtype=B.BF16)
+        log(f"prefill stack resident: {pf['n_mats']} matrices, {pf['flops'] / 1e12:.2f} TFLOP/step, {time.time() - t:.1f} s")
+        runp = lambda: B.rwkvq_linear_dispatch(pf["table"], 2048, pf["x_dtype"], B.BF16)
+        ptotal, pper, _ = time_steps(runp, args.prefill_steps, 1)
+        pms = ptotal / args.prefill_steps
+        tflops = pf["flops"] / (pms * 1e-3) / 1e12
+        out["prefill"] = {"value": tflops, "unit": "TFLOP/s", "ms_per_step": pms, "steps": args.prefill_steps,
+                          "dtype": "bf16", "tokens_per_s": 2048 * 1e3 / pms,
+                          "pct_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+                          "workload": "configs[3]: same stack recipe (seed 3), M=2048 tokens, bf16 "
+                                      "activations, %d layers" % args.layers,
+                          "flop_per_step": pf["flops"]}
+        out["roofline_prefill"] = {"kernel": PREFILL_KERNEL, "bound": "mfma", "achieved": tflops,
+                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        del pf, runp
+        torch.cuda.empty_cache()
+
+    # ---------------- CPU oracle baseline (reported, not a target)
+    if not args.skip_cpu:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_layers)
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
