@@ -136,7 +136,7 @@ def main():
     total_ms, per, wall_ms = time_steps(run, args.steps, args.warmup)
     ms = total_ms / args.steps
     gbs = dec["wbytes"] / (ms * 1e-3) / 1e9
-    launches = (dec["n_mats"] + 31) // 32
+    launches = (dec["n_mats"] + 63) // 64
     out = {
         "metric": "dequant-GEMV weight GB/s (% of HBM peak) + prefill TFLOP/s, RWKV-6-7B shapes",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -148,8 +148,8 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
         MatDev d;
         if ((st = to_dev(mats[i], xs[i], ys[i], &d)) != RWKVQ_OK) return st;
         if (d.layout == RWKVQ_CANONICAL) ref.push_back(d);
-        else if (M <= kDecodeMaxM) decode.push_back(d);
-        else if (d.N % 256 == 0) prefill.push_back(d);
+        else if (M <= kDecodeMaxM && d.K <= kDecodeMaxK) decode.push_back(d);
+        else if (M > kDecodeMaxM && d.N % 256 == 0) prefill.push_back(d);
         else ref.push_back(d);   // matrix-core tiles are 256 rows of W wide
     }
     hipStream_t s = (hipStream_t)stream;

@@ -130,5 +130,6 @@ hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, in
                           hipStream_t s);
 
 constexpr int kDecodeMaxM = 16;    // native layout: M <= this goes to the streaming kernels
+constexpr int kDecodeMaxK = 20480; // ... whose per-group activation sums for K columns fit their LDS
 
 }  // namespace rwkvq

@@ -3,20 +3,22 @@
 // Computes y = x * Deq(W)^T (the W. products of App. A.1) for several matrices in one launch,
 // each SQ or VQ as its flag says (Sec. 3.1, Eq. "optimization goal").  The work is bound by
 // reading the packed weights once from HBM, so everything else is arranged around keeping
-// 16-byte coalesced loads in flight:
+// 16-byte coalesced loads in flight while spending as few issue slots per weight as possible:
 //
-//   * One workgroup (4 wavefronts) owns one 16-row tile of one matrix; its wavefronts take the
-//     256-column tiles of that row tile round-robin and their partial sums meet in LDS.
-//   * The contraction itself runs on the matrix cores (v_mfma_f32_16x16x32_f16) with the
-//     activations as the A operand (rows = batch index) and the weights as the B operand, so
-//     the vector ALU only has to turn packed fields into fp16 pairs.  With M = 1 fifteen of the
-//     sixteen A rows are idle, which costs nothing: the matrix cores have ~5x headroom here.
-//   * SQ: a 3-bit code q is turned into the fp16 number 8 + q by one shift and one and-or
-//     (the code lands in the top mantissa bits of 0x4800).  The products sum_k (8 + q) x are
-//     accumulated per group of 128 columns together with sum_k x (a second MFMA against a
-//     constant ones operand), and the group's scale and zero point are applied in binary32:
-//         y += s * (sum (8 + q) x  -  (z + 8) * sum x)  =  s * sum (q - z) x.
-//     q, 8 + q and the products are exact; only the binary32 accumulation rounds.
+//   * One wavefront owns two adjacent 16-row tiles of one matrix and streams their 256-column
+//     tiles in order, DEPTH tiles ahead (about 3 KB per tile pair in flight).  Four such
+//     wavefronts form a workgroup (128 rows); after a short common prologue they share nothing.
+//   * The contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16) with the activations as
+//     the A operand (rows = batch index) and the weights as the B operand, so the vector ALU only
+//     has to turn packed fields into fp16 pairs.  With M = 1 fifteen of the sixteen A rows are
+//     idle, which costs nothing: the matrix cores have ~5x headroom at this arithmetic intensity.
+//     One A fragment read from LDS feeds both row tiles.
+//   * SQ: a 3-bit code q becomes the fp16 number 8 + q with one shift and one and-or (the code
+//     lands in the top mantissa bits of 0x4800).  Per group of 128 columns the accumulator starts
+//     at -8 * X (X = sum of the group's activations, computed once per workgroup in the prologue)
+//     so that it ends as sum q x exactly as an integer-weighted sum; scale and zero point are
+//     then applied in binary32:   y += s * (sum q x - z * X) = s * sum (q - z) x.
+//     q, 8 + q and the products are exact; only binary32 accumulation rounds.
 //   * VQ, 6-bit indices: the 64-entry codebook of the current 256 x 256 block is one 32-bit
 //     register across the wavefront (lane i holds entry i = two fp16 weights); ds_bpermute_b32
 //     gathers entry[index] straight into the B operand.  8-bit indices: the 256-entry codebook
@@ -27,40 +29,55 @@
 
 namespace rwkvq {
 
-constexpr int kMaxGroupMats = 32;     // matrices per grouped launch (descriptor table in kernarg)
+#ifndef RWKVQ_DECODE_MINBLOCKS
+#define RWKVQ_DECODE_MINBLOCKS 5
+#endif
+#ifndef RWKVQ_DECODE_DEPTH
+#define RWKVQ_DECODE_DEPTH 2
+#endif
+constexpr int kMaxGroupMats = 64;     // matrices per grouped launch (descriptor table in kernarg)
 constexpr int kXStride = 264;         // fp16 per staged activation row (256 + 8: bank spread)
+#ifndef RWKVQ_DECODE_RT
+#define RWKVQ_DECODE_RT 1
+#endif
+constexpr int kRT = RWKVQ_DECODE_RT;  // 16-row tiles per wavefront (1 or 2)
+constexpr int kWaveRows = 16 * kRT;
+constexpr int kWgRows = 4 * kWaveRows;
 
 struct DecodeMat {
     const uint32_t* codes;
     const uint16_t* aux;
     const void* x;
     void* y;
-    int N, K, fmt, wg_end;            // wg_end: first workgroup index after this matrix
+    int N, K, fmt, pad;
 };
-struct DecodeArgs {
+struct DecodeArgs {                   // 3344 bytes of kernel arguments
+    int wg_end[kMaxGroupMats];        // first workgroup index after matrix i (INT_MAX when unused)
     DecodeMat m[kMaxGroupMats];
-    int n_mats, M, xdt, ydt;
+    int M, xdt, ydt, pad;
 };
 
 template <int P>
-__device__ __forceinline__ uint32_t sq_pair_f16(uint32_t w0, uint32_t w1, uint32_t w2) {
-    // two 3-bit codes -> fp16x2 (8 + q_even, 8 + q_odd)
-    constexpr uint32_t kMask = 0x03800380u, kMagic = 0x48004800u;
+__device__ __forceinline__ uint32_t sq_pair_f16(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t mask,
+                                                uint32_t magic) {
+    // two 3-bit codes -> fp16x2 (8 + q_even, 8 + q_odd); mask = 0x03800380, magic = 0x48004800
     if constexpr (P < 15) {
         constexpr int p = P % 5, sh = 6 - 3 * p;
         uint32_t w = (P / 5 == 0) ? w0 : (P / 5 == 1) ? w1 : w2;
         uint32_t v = sh > 0 ? (w << (sh > 0 ? sh : 0)) : sh < 0 ? (w >> (sh < 0 ? -sh : 0)) : w;
-        return (v & kMask) | kMagic;
+        return (v & mask) | magic;
     } else {
-        uint32_t v = ((w0 & 0x00010001u) << 7) | ((w1 & 0x00010001u) << 8) | ((w2 & 0x00010001u) << 9);
-        return v | kMagic;
+        // bit b of the pair's two codes sits at bits 0 and 16 of word b
+        uint32_t v = (w0 & 0x00010001u) | ((w1 & 0x00010001u) << 1) | ((w2 & 0x00010001u) << 2);
+        return (v << 7) | magic;
     }
 }
 
 template <int T>
-__device__ __forceinline__ half8_t sq_operand(uint32_t w0, uint32_t w1, uint32_t w2) {
-    uint4_t v = {sq_pair_f16<4 * T + 0>(w0, w1, w2), sq_pair_f16<4 * T + 1>(w0, w1, w2),
-                 sq_pair_f16<4 * T + 2>(w0, w1, w2), sq_pair_f16<4 * T + 3>(w0, w1, w2)};
+__device__ __forceinline__ half8_t sq_operand(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t mask,
+                                              uint32_t magic) {
+    uint4_t v = {sq_pair_f16<4 * T + 0>(w0, w1, w2, mask, magic), sq_pair_f16<4 * T + 1>(w0, w1, w2, mask, magic),
+                 sq_pair_f16<4 * T + 2>(w0, w1, w2, mask, magic), sq_pair_f16<4 * T + 3>(w0, w1, w2, mask, magic)};
     return __builtin_bit_cast(half8_t, v);
 }
 
@@ -105,28 +122,33 @@ template <int MT>
 struct XRegs { uint2_t v[MT]; };
 
 template <int MT>
-__device__ __forceinline__ void x_load(XRegs<MT>& r, const void* x, int M, int K, int T, int lane) {
+__device__ __forceinline__ void x_load(XRegs<MT>& r, const uint16_t* x, int M, int K, int T, int lane) {
+    const uint16_t* xt = x + 256 * T;             // uniform part of the address
+    // rows beyond M repeat row M-1: every load is unconditional (see tile_pipeline)
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
-        if (m < M) r.v[m] = *(const uint2_t*)((const uint16_t*)x + (size_t)m * K + 256 * T + 4 * lane);
+    for (int m = 0; m < MT; ++m) r.v[m] = *(const uint2_t*)(xt + (size_t)(m < M ? m : M - 1) * K + 4 * lane);
 }
 
-__device__ __forceinline__ uint2_t bf16x4_to_f16x4(uint2_t v) {
-    half_t h0 = (half_t)__builtin_bit_cast(float, v.x << 16);
-    half_t h1 = (half_t)__builtin_bit_cast(float, v.x & 0xFFFF0000u);
-    half_t h2 = (half_t)__builtin_bit_cast(float, v.y << 16);
-    half_t h3 = (half_t)__builtin_bit_cast(float, v.y & 0xFFFF0000u);
-    uint2_t o;
-    o.x = (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
-    o.y = (uint32_t)__builtin_bit_cast(uint16_t, h2) | ((uint32_t)__builtin_bit_cast(uint16_t, h3) << 16);
-    return o;
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
+    half_t h0 = (half_t)__builtin_bit_cast(float, v << 16);
+    half_t h1 = (half_t)__builtin_bit_cast(float, v & 0xFFFF0000u);
+    return (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
 }
 
 template <int MT>
-__device__ __forceinline__ void x_store(const XRegs<MT>& r, half_t* xs, int M, int lane, bool bf16) {
+__device__ __forceinline__ void x_store(const XRegs<MT>& r, half_t* xs, int lane, bool bf16) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
-        if (m < M) *(uint2_t*)(xs + m * kXStride + 4 * lane) = bf16 ? bf16x4_to_f16x4(r.v[m]) : r.v[m];
+    for (int m = 0; m < MT; ++m) {
+        uint2_t v = r.v[m];
+        if (bf16) { v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y); }
+        *(uint2_t*)(xs + m * kXStride + 4 * lane) = v;
+    }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
 }
 
 // ---- per-format tile loops ------------------------------------------------------------------
@@ -134,170 +156,404 @@ template <int MT> struct Acc { static constexpr int n = MT == 1 ? 1 : 4; };
 
 #define RWKVQ_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (c), 0, 0, 0)
 
-template <int MT>
-__device__ __forceinline__ void run_sq(const DecodeMat& mt, int R, int M, bool xbf16, int wave, int lane,
-                                       half_t* xs, float4_t& out) {
-    const int KT = mt.K >> 8;
-    const uint32_t* codes = mt.codes + (size_t)R * KT * 384;
-    const uint2_t* sz = (const uint2_t*)mt.aux + (size_t)R * KT * 16 + (lane & 15);
-    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    const half8_t ones = {1, 1, 1, 1, 1, 1, 1, 1};
-    if (wave >= KT) return;
-    uint4_t a = *(const uint4_t*)(codes + (size_t)wave * 384 + 4 * lane);
-    uint2_t b = *(const uint2_t*)(codes + (size_t)wave * 384 + 256 + 2 * lane);
-    uint2_t szr = sz[(size_t)wave * 16];
-    XRegs<MT> xr;
-    x_load<MT>(xr, mt.x, M, mt.K, wave, lane);
-    for (int T = wave; T < KT; T += 4) {
-        wave_lds_sync();
-        x_store<MT>(xr, xs, M, lane, xbf16);
-        wave_lds_sync();
-        uint4_t ca = a;
-        uint2_t cb = b, csz = szr;
-        const int Tn = T + 4;
-        if (Tn < KT) {
-            a = *(const uint4_t*)(codes + (size_t)Tn * 384 + 4 * lane);
-            b = *(const uint2_t*)(codes + (size_t)Tn * 384 + 256 + 2 * lane);
-            szr = sz[(size_t)Tn * 16];
-            x_load<MT>(xr, mt.x, M, mt.K, Tn, lane);
+// Software pipeline over the column tiles T = 0 .. KT-1: DEPTH tiles are in flight from HBM
+// while one is being consumed.  Every load in the loop is unconditional, so the compiler can
+// count outstanding loads exactly and wait only for the tile about to be consumed: past the
+// end of the row the loads simply fetch tile 0 again (a few cache hits, never used).
+template <int DEPTH, class Regs, class Load, class Compute>
+__device__ __forceinline__ void tile_pipeline(int KT, Load load, Compute compute) {
+    static_assert(DEPTH == 2 || DEPTH == 3, "pipeline depth");
+    Regs r0, r1, r2;
+    load(r0, 0);
+    load(r1, 1 < KT ? 1 : 0);
+    if (DEPTH == 3) load(r2, 2 < KT ? 2 : 0);
+    for (int T = 0; T < KT; T += DEPTH) {
+        compute(r0, T);
+        load(r0, T + DEPTH < KT ? T + DEPTH : 0);
+        if (T + 1 < KT) compute(r1, T + 1);
+        load(r1, T + 1 + DEPTH < KT ? T + 1 + DEPTH : 0);
+        if (DEPTH == 3) {
+            if (T + 2 < KT) compute(r2, T + 2);
+            load(r2, T + 2 + DEPTH < KT ? T + 2 + DEPTH : 0);
         }
+    }
+}
+
+template <int MT> struct SqRegs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XRegs<MT> x; };
+template <int MT> struct Vq6Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XRegs<MT> x; };
+template <int MT> struct Vq8Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XRegs<MT> x; };
+
+// Everything a tile loop needs about its wavefront's position; R0, R1 are the two row tiles
+// (R1 == R0 when the matrix has an odd number of row tiles and this is the last wavefront).
+struct WavePos { int R[2], M, lane; bool xbf16; };
+
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, const float* xsumX,
+                                       const float* xsum8, float4_t (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
+    const uint2_t* sz[2] = {(const uint2_t*)mt.aux + (size_t)wp.R[0] * KT * 16,
+                            (const uint2_t*)mt.aux + (size_t)wp.R[1] * KT * 16};
+    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    const int mrow = MT == 16 ? 4 * (lane >> 4) : 0;      // first batch row this lane accumulates
+    // The and-or that builds 8 + q takes its mask from a VGPR and the fp16 pattern of 8.0 from an
+    // SGPR: a VOP3 instruction of this ISA takes no literal and at most one scalar operand.
+    uint32_t mask, magic;
+    asm("v_mov_b32 %0, 0x03800380" : "=v"(mask));
+    asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
+    auto load = [&](SqRegs<MT>& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
+            r.sz[rt] = (sz[rt] + (size_t)T * 16)[lane & 15];
+        }
+        x_load<MT>(r.x, (const uint16_t*)mt.x, M, mt.K, T, lane);
+    };
+    auto compute = [&](const SqRegs<MT>& r, int T) {
+        wave_lds_sync();
+        x_store<MT>(r.x, xs, lane, wp.xbf16);
+        wave_lds_sync();
+        // All LDS reads of the tile are issued first; their latency is covered by the unpack work.
+        half8_t xa[2][4];
+        float4_t c8[2], cx[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const uint32_t w0 = u == 0 ? ca.x : ca.w, w1 = u == 0 ? ca.y : cb.x, w2 = u == 0 ? ca.z : cb.y;
-            float4_t acc = {0, 0, 0, 0}, accx = {0, 0, 0, 0};
-            half8_t xa;
-            xa = *(const half8_t*)(xrow + 128 * u + 0);
-            acc = RWKVQ_MFMA(xa, sq_operand<0>(w0, w1, w2), acc);
-            accx = RWKVQ_MFMA(xa, ones, accx);
-            xa = *(const half8_t*)(xrow + 128 * u + 32);
-            acc = RWKVQ_MFMA(xa, sq_operand<1>(w0, w1, w2), acc);
-            accx = RWKVQ_MFMA(xa, ones, accx);
-            xa = *(const half8_t*)(xrow + 128 * u + 64);
-            acc = RWKVQ_MFMA(xa, sq_operand<2>(w0, w1, w2), acc);
-            accx = RWKVQ_MFMA(xa, ones, accx);
-            xa = *(const half8_t*)(xrow + 128 * u + 96);
-            acc = RWKVQ_MFMA(xa, sq_operand<3>(w0, w1, w2), acc);
-            accx = RWKVQ_MFMA(xa, ones, accx);
-            const uint32_t szw = u == 0 ? csz.x : csz.y;
-            const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
-            const float zz = f16_bits_to_f32((uint16_t)(szw >> 16)) + 8.0f;
+            const int g = 2 * T + u;
+            if (MT == 1) {
+                c8[u] = float4_t{xsum8[g], 0, 0, 0};
+                cx[u] = float4_t{xsumX[g], 0, 0, 0};
+            } else {
+                c8[u] = *(const float4_t*)(xsum8 + g * MT + mrow);
+                cx[u] = *(const float4_t*)(xsumX + g * MT + mrow);
+            }
 #pragma unroll
-            for (int i = 0; i < Acc<MT>::n; ++i) out[i] = fmaf(s, fmaf(-zz, accx[i], acc[i]), out[i]);
+            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
         }
-    }
-}
-
-template <int MT>
-__device__ __forceinline__ void run_vq6(const DecodeMat& mt, int R, int M, bool xbf16, int wave, int lane,
-                                        half_t* xs, float4_t& out) {
-    const int KT = mt.K >> 8;
-    const uint32_t* codes = mt.codes + (size_t)R * KT * 384;
-    const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(R >> 4) * KT * 64 + lane;
-    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    if (wave >= KT) return;
-    uint4_t a = *(const uint4_t*)(codes + (size_t)wave * 384 + 4 * lane);
-    uint2_t b = *(const uint2_t*)(codes + (size_t)wave * 384 + 256 + 2 * lane);
-    uint32_t cbr = cbs[(size_t)wave * 64];
-    XRegs<MT> xr;
-    x_load<MT>(xr, mt.x, M, mt.K, wave, lane);
-    for (int T = wave; T < KT; T += 4) {
-        wave_lds_sync();
-        x_store<MT>(xr, xs, M, lane, xbf16);
-        wave_lds_sync();
-        uint4_t ca = a;
-        uint2_t cb = b;
-        uint32_t ccb = cbr;
-        const int Tn = T + 4;
-        if (Tn < KT) {
-            a = *(const uint4_t*)(codes + (size_t)Tn * 384 + 4 * lane);
-            b = *(const uint2_t*)(codes + (size_t)Tn * 384 + 256 + 2 * lane);
-            cbr = cbs[(size_t)Tn * 64];
-            x_load<MT>(xr, mt.x, M, mt.K, Tn, lane);
-        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const uint32_t w0 = u == 0 ? ca.x : ca.w, w1 = u == 0 ? ca.y : cb.x, w2 = u == 0 ? ca.z : cb.y;
-            out = RWKVQ_MFMA(*(const half8_t*)(xrow + 128 * u + 0), vq6_operand<0>(w0, w1, w2, ccb), out);
-            out = RWKVQ_MFMA(*(const half8_t*)(xrow + 128 * u + 32), vq6_operand<1>(w0, w1, w2, ccb), out);
-            out = RWKVQ_MFMA(*(const half8_t*)(xrow + 128 * u + 64), vq6_operand<2>(w0, w1, w2, ccb), out);
-            out = RWKVQ_MFMA(*(const half8_t*)(xrow + 128 * u + 96), vq6_operand<3>(w0, w1, w2, ccb), out);
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                float4_t acc = c8[u];
+                acc = RWKVQ_MFMA(xa[u][0], sq_operand<0>(w0, w1, w2, mask, magic), acc);
+                acc = RWKVQ_MFMA(xa[u][1], sq_operand<1>(w0, w1, w2, mask, magic), acc);
+                acc = RWKVQ_MFMA(xa[u][2], sq_operand<2>(w0, w1, w2, mask, magic), acc);
+                acc = RWKVQ_MFMA(xa[u][3], sq_operand<3>(w0, w1, w2, mask, magic), acc);
+                const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
+                const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
+                const float z = f16_bits_to_f32((uint16_t)(szw >> 16));
+#pragma unroll
+                for (int i = 0; i < Acc<MT>::n; ++i) out[rt][i] = fmaf(s, fmaf(-z, cx[u][i], acc[i]), out[rt][i]);
+            }
         }
-    }
+    };
+    tile_pipeline<DEPTH, SqRegs<MT>>(KT, load, compute);
 }
 
-template <int MT>
-__device__ __forceinline__ void run_vq8(const DecodeMat& mt, int R, int M, bool xbf16, int wave, int lane,
-                                        half_t* xs, uint32_t* cb_lds, float4_t& out) {
-    const int KT = mt.K >> 8;
-    const uint32_t* codes = mt.codes + (size_t)R * KT * 512;
-    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(R >> 4) * KT * 64 + lane;
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float4_t (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
+    const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
     const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    if (wave >= KT) return;
-    uint4_t a = *(const uint4_t*)(codes + (size_t)wave * 512 + 4 * lane);
-    uint4_t b = *(const uint4_t*)(codes + (size_t)wave * 512 + 256 + 4 * lane);
-    uint4_t cbr = cbs[(size_t)wave * 64];
-    XRegs<MT> xr;
-    x_load<MT>(xr, mt.x, M, mt.K, wave, lane);
-    for (int T = wave; T < KT; T += 4) {
-        wave_lds_sync();
-        x_store<MT>(xr, xs, M, lane, xbf16);
-        *(uint4_t*)(cb_lds + 4 * lane) = cbr;
-        wave_lds_sync();
-        uint4_t ca = a, cb = b;
-        const int Tn = T + 4;
-        if (Tn < KT) {
-            a = *(const uint4_t*)(codes + (size_t)Tn * 512 + 4 * lane);
-            b = *(const uint4_t*)(codes + (size_t)Tn * 512 + 256 + 4 * lane);
-            cbr = cbs[(size_t)Tn * 64];
-            x_load<MT>(xr, mt.x, M, mt.K, Tn, lane);
+    auto load = [&](Vq6Regs<MT>& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
         }
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 0), vq8_operand(ca.x, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 32), vq8_operand(ca.y, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 64), vq8_operand(ca.z, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 96), vq8_operand(ca.w, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 128), vq8_operand(cb.x, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 160), vq8_operand(cb.y, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 192), vq8_operand(cb.z, cb_lds), out);
-        out = RWKVQ_MFMA(*(const half8_t*)(xrow + 224), vq8_operand(cb.w, cb_lds), out);
-    }
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        x_load<MT>(r.x, (const uint16_t*)mt.x, M, mt.K, T, lane);
+    };
+    auto compute = [&](const Vq6Regs<MT>& r, int) {
+        wave_lds_sync();
+        x_store<MT>(r.x, xs, lane, wp.xbf16);
+        wave_lds_sync();
+        half8_t xa[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                out[rt] = RWKVQ_MFMA(xa[u][0], vq6_operand<0>(w0, w1, w2, r.cb), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa[u][1], vq6_operand<1>(w0, w1, w2, r.cb), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa[u][2], vq6_operand<2>(w0, w1, w2, r.cb), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa[u][3], vq6_operand<3>(w0, w1, w2, r.cb), out[rt]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, Vq6Regs<MT>>(KT, load, compute);
 }
 
-// One workgroup = one 16-row tile of one matrix.  MT = number of activation rows carried
-// (1, 4 or 16 >= M).  D layout of the MFMA: lane holds rows 4*(lane/16) + i, column lane%16.
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+                                        float4_t (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 512, mt.codes + (size_t)wp.R[1] * KT * 512};
+    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
+    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    auto load = [&](Vq8Regs<MT>& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 512;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
+        }
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        x_load<MT>(r.x, (const uint16_t*)mt.x, M, mt.K, T, lane);
+    };
+    auto compute = [&](const Vq8Regs<MT>& r, int) {
+        wave_lds_sync();
+        x_store<MT>(r.x, xs, lane, wp.xbf16);
+        *(uint4_t*)(cb_lds + 4 * lane) = r.cb;
+        wave_lds_sync();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const half8_t xa0 = *(const half8_t*)(xrow + 128 * u + 0);
+            const half8_t xa1 = *(const half8_t*)(xrow + 128 * u + 32);
+            const half8_t xa2 = *(const half8_t*)(xrow + 128 * u + 64);
+            const half8_t xa3 = *(const half8_t*)(xrow + 128 * u + 96);
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
+                out[rt] = RWKVQ_MFMA(xa0, vq8_operand(w.x, cb_lds), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa1, vq8_operand(w.y, cb_lds), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa2, vq8_operand(w.z, cb_lds), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa3, vq8_operand(w.w, cb_lds), out[rt]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, Vq8Regs<MT>>(KT, load, compute);
+}
+
+// ------------------------------------------------------------------------------------------
+// Batch 1 (GEMV proper).  Same streaming structure and native layout, but the contraction is
+// done by the vector ALU (v_dot2c_f32_f16: two multiply-adds per lane, binary32 accumulate):
+// with a single activation row fifteen sixteenths of every MFMA would be spent on padding, and
+// on this part the matrix cores and the vector ALU of a SIMD do not run concurrently, so the
+// padded MFMA costs both issue time and power.  Lane (r, kg) accumulates the part of row r's dot
+// product that falls on its own columns; the four kg lanes of a row are summed at the end.
+//   SQ:  per group, acc starts at -8 * Xp (Xp = sum of the activations on this lane's columns of
+//        the group, from the prologue), gathers sum (8 + q) x, and y += s * (acc - z * Xp).
+//   VQ:  the codebook of the current block sits in a wavefront-private LDS region; each pair of
+//        weights is one ds_read_b32 gather feeding one dot2.
+__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {   // two fp16 pairs, scalars in
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
+}
+__device__ __forceinline__ float dot8(const uint4_t b, const half8_t xa, float acc) {
+    // (element-wise bit_cast of a vector member miscompiles with this toolchain: go through scalars)
+    const uint4_t xv = __builtin_bit_cast(uint4_t, xa);
+    const uint32_t b0 = b.x, b1 = b.y, b2 = b.z, b3 = b.w, x0 = xv.x, x1 = xv.y, x2 = xv.z, x3 = xv.w;
+    acc = dot2(b0, x0, acc);
+    acc = dot2(b1, x1, acc);
+    acc = dot2(b2, x2, acc);
+    acc = dot2(b3, x3, acc);
+    return acc;
+}
+
+template <int P>
+__device__ __forceinline__ uint32_t vq6_lds_addr(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t m, uint32_t base) {
+    // LDS byte address of codebook entry P: (index * 4) | base, base aligned to 256 bytes
+    if constexpr (P < 15) {
+        constexpr int p = P % 5;
+        uint32_t w = (P / 5 == 0) ? w0 : (P / 5 == 1) ? w1 : w2;
+        return ((w >> (6 * p)) & m) | base;
+    } else {
+        return ((w0 & 3u) << 2) | ((w1 & 3u) << 4) | ((w2 & 3u) << 6) | base;
+    }
+}
+__device__ __forceinline__ uint32_t lds_gather(uint32_t byte_addr) {
+    return *(const __attribute__((address_space(3))) uint32_t*)(uintptr_t)byte_addr;
+}
+template <int T4>
+__device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t m, uint32_t base) {
+    uint4_t v = {lds_gather(vq6_lds_addr<4 * T4 + 0>(w0, w1, w2, m, base)), lds_gather(vq6_lds_addr<4 * T4 + 1>(w0, w1, w2, m, base)),
+                 lds_gather(vq6_lds_addr<4 * T4 + 2>(w0, w1, w2, m, base)), lds_gather(vq6_lds_addr<4 * T4 + 3>(w0, w1, w2, m, base))};
+    return v;
+}
+
+template <int DEPTH>
+__device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+                                           float (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
+    const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
+    const half_t* xrow = xs + 8 * (lane >> 4);
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
+    uint32_t m;
+    asm("v_mov_b32 %0, 0xfc" : "=v"(m));
+    auto load = [&](Vq6Regs<1>& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
+        }
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        x_load<1>(r.x, (const uint16_t*)mt.x, 1, mt.K, T, lane);
+    };
+    auto compute = [&](const Vq6Regs<1>& r, int) {
+        wave_lds_sync();
+        x_store<1>(r.x, xs, lane, wp.xbf16);
+        cb_lds[lane] = r.cb;
+        wave_lds_sync();
+        half8_t xa[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                out[rt] = dot8(vq6_gather4<0>(w0, w1, w2, m, base), xa[u][0], out[rt]);
+                out[rt] = dot8(vq6_gather4<1>(w0, w1, w2, m, base), xa[u][1], out[rt]);
+                out[rt] = dot8(vq6_gather4<2>(w0, w1, w2, m, base), xa[u][2], out[rt]);
+                out[rt] = dot8(vq6_gather4<3>(w0, w1, w2, m, base), xa[u][3], out[rt]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, Vq6Regs<1>>(KT, load, compute);
+}
+
+template <int DEPTH>
+__device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+                                           float (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 512, mt.codes + (size_t)wp.R[1] * KT * 512};
+    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
+    const half_t* xrow = xs + 8 * (lane >> 4);
+    auto load = [&](Vq8Regs<1>& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 512;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
+        }
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        x_load<1>(r.x, (const uint16_t*)mt.x, 1, mt.K, T, lane);
+    };
+    auto compute = [&](const Vq8Regs<1>& r, int) {
+        wave_lds_sync();
+        x_store<1>(r.x, xs, lane, wp.xbf16);
+        *(uint4_t*)(cb_lds + 4 * lane) = r.cb;
+        wave_lds_sync();
+        half8_t xa[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
+                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.x, cb_lds)), xa[u][0], out[rt]);
+                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.y, cb_lds)), xa[u][1], out[rt]);
+                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.z, cb_lds)), xa[u][2], out[rt]);
+                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.w, cb_lds)), xa[u][3], out[rt]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, Vq8Regs<1>>(KT, load, compute);
+}
+
+// MT = number of activation rows carried (1, 4 or 16 >= M).  D layout of the MFMA: lane holds
+// rows 4*(lane/16) + i, column lane%16.  With MT = 1 the SQ matrices still use the MFMA path
+// (its unpack is the cheapest per weight) while the VQ matrices use the vector-ALU path above,
+// whose LDS gathers are cheaper than ds_bpermute.
 template <int MT>
-__global__ void __launch_bounds__(256) decode_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : 1) decode_kernel(DecodeArgs a) {
+    constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : 2;
     __shared__ __attribute__((aligned(16))) half_t xs_all[4][MT * kXStride];
-    __shared__ __attribute__((aligned(16))) uint32_t cb_all[4][256];
-    __shared__ float red[4][MT][16];
+    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[4][256];
+    __shared__ __attribute__((aligned(16))) float xsumX[kDecodeMaxK / kGroup * MT];
+    __shared__ __attribute__((aligned(16))) float xsum8[kDecodeMaxK / kGroup * MT];
 
+    // Which matrix does this workgroup belong to?  Lane i compares against the end of matrix i
+    // (one load per wavefront from the argument block); the count of matrices that end at or
+    // before this workgroup is its matrix index.
     const int wg = blockIdx.x;
-    int mi = 0;
-    while (mi + 1 < a.n_mats && wg >= a.m[mi].wg_end) ++mi;
+    static_assert(kMaxGroupMats == 64, "one table entry per lane");
+    const int mi = __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[threadIdx.x & 63]));
     const DecodeMat mt = a.m[mi];
-    const int R = wg - (mi ? a.m[mi - 1].wg_end : 0);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int M = a.M;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool xbf16 = a.xdt == DT_BF16;
 
-    float4_t out = {0, 0, 0, 0};
-    if (mt.fmt == FMT_SQ3) run_sq<MT>(mt, R, M, xbf16, wave, lane, xs_all[wave], out);
-    else if (mt.fmt == FMT_VQ6) run_vq6<MT>(mt, R, M, xbf16, wave, lane, xs_all[wave], out);
-    else run_vq8<MT>(mt, R, M, xbf16, wave, lane, xs_all[wave], cb_all[wave], out);
-
-    if (MT == 16) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) red[wave][(4 * (lane >> 4) + i) % MT][lane & 15] = out[i];
-    } else if (lane < 16) {
-#pragma unroll
-        for (int i = 0; i < Acc<MT>::n; ++i) red[wave][i % MT][lane] = out[i];
+    if (mt.fmt == FMT_SQ3) {
+        // Prologue: X[g][m] = sum of the activations of group g (as the fp16 values the MFMA
+        // will see), and -8 X, for every group of the matrix; wavefronts take groups round-robin.
+        const int G = mt.K / kGroup;
+        for (int g = wave; g < G; g += 4)
+            for (int m = 0; m < M; ++m) {
+                uint32_t v = *(const uint32_t*)((const uint16_t*)mt.x + (size_t)m * mt.K + kGroup * g + 2 * lane);
+                if (xbf16) v = bf16x2_to_f16x2(v);
+                half2_t h = __builtin_bit_cast(half2_t, v);
+                float sum = wave_sum((float)h.x + (float)h.y);
+                if (lane == 0) { xsumX[g * MT + m] = sum; xsum8[g * MT + m] = -8.0f * sum; }
+            }
+        __syncthreads();
     }
-    __syncthreads();
-    const int t = threadIdx.x;
-    if (t < MT * 16) {
-        const int m = t >> 4, n = t & 15;
-        if (m < M) {
-            float v = (red[0][m][n] + red[1][m][n]) + (red[2][m][n] + red[3][m][n]);
-            store_from_f32(mt.y, (size_t)m * mt.N + 16 * R + n, a.ydt, v);
+
+    const int NR = mt.N >> 4;
+    WavePos wp;
+    wp.R[0] = kRT * (4 * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
+    if (wp.R[0] >= NR) return;                     // rows beyond N (N not a multiple of kWgRows)
+    wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
+    wp.M = M; wp.lane = lane; wp.xbf16 = xbf16;
+
+    if (MT == 1 && mt.fmt != FMT_SQ3) {
+        float part[kRT];
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) part[rt] = 0.f;
+        if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH>(mt, wp, xs_all[wave], cb_all[wave], part);
+        else run_vq8_m1<DEPTH>(mt, wp, xs_all[wave], cb_all[wave], part);
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            if (rt == 1 && wp.R[1] == wp.R[0]) break;
+            float v = part[rt];                    // sum the four column groups of each row
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (lane < 16) store_from_f32(mt.y, (size_t)16 * wp.R[rt] + lane, a.ydt, v);
+        }
+        return;
+    }
+
+    float4_t out[kRT];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) out[rt] = float4_t{0, 0, 0, 0};
+    if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH>(mt, wp, xs_all[wave], xsumX, xsum8, out);
+    else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH>(mt, wp, xs_all[wave], out);
+    else run_vq8<MT, DEPTH>(mt, wp, xs_all[wave], cb_all[wave], out);
+
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) {
+        if (rt == 1 && wp.R[1] == wp.R[0]) break;
+        const int n = 16 * wp.R[rt] + (lane & 15);
+        if (MT == 16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = 4 * (lane >> 4) + i;
+                if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, out[rt][i]);
+            }
+        } else if (lane < 16) {
+#pragma unroll
+            for (int i = 0; i < Acc<MT>::n; ++i)
+                if (i < M) store_from_f32(mt.y, (size_t)i * mt.N + n, a.ydt, out[rt][i]);
         }
     }
 }
@@ -309,11 +565,15 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[base + i];
-            wgs += m.N / 16;
-            a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, wgs};
+            wgs += (m.N + kWgRows - 1) / kWgRows;
+            a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, 0};
+            a.wg_end[i] = wgs;
         }
-        for (int i = cnt; i < kMaxGroupMats; ++i) a.m[i] = DecodeMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, wgs};
-        a.n_mats = cnt; a.M = M; a.xdt = x_dtype; a.ydt = y_dtype;
+        for (int i = cnt; i < kMaxGroupMats; ++i) {
+            a.m[i] = DecodeMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+            a.wg_end[i] = 0x7FFFFFFF;
+        }
+        a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
         if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
         else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
         else hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(256), 0, s, a);
