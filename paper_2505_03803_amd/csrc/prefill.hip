@@ -7,12 +7,16 @@
 // binary32; VQ: the fp16 codebook entry) rounded once, to nearest even, to the type of x.
 //
 // Tiling: workgroup = 256 threads = 2 x 2 wavefronts, block tile 256 (m) x 256 (n) x 64 (k),
-// wavefront tile 128 x 128 = 8 x 8 MFMA tiles (256 accumulator registers).  Both operands live
-// in LDS as [row][64 k] with rows padded to 144 bytes, which makes the 16-byte fragment reads and
-// the 16-byte tile writes bank-conflict free.  Two LDS buffers: while the matrix cores work on
-// k-step i, the activations of step i+1 are in flight from global memory and the weights of step
-// i+1 are being unpacked by the vector ALU from packed words that were fetched once per 256
-// columns.  One workgroup barrier per k-step.
+// wavefront tile 128 x 128 = 8 x 8 MFMA tiles (256 accumulator registers).  Both operand tiles
+// live in LDS as 256 rows of 128 bytes (64 k), with the eight 16-byte chunks of a row stored at
+// chunk ^ ((row >> 1) & 7): any 16 consecutive rows read the same logical chunk from 16 distinct
+// bank groups, so fragment reads and tile writes are conflict free without padding.
+//   * activations: copied global -> LDS by the load unit itself (global_load_lds_dwordx4), no
+//     registers and no vector-ALU work; each lane fetches the chunk that belongs at its slot;
+//   * weights: packed words are fetched once per 256 columns, unpacked by the vector ALU one
+//     k-step ahead of the matrix cores, and written with 16-byte LDS stores.
+// Two LDS buffers per operand; one workgroup barrier per k-step; waits on the load counter are
+// placed by hand (the activations of step i+1 are in flight during the MFMAs of step i).
 //
 // Workgroup -> tile order: the m-tile index runs fastest, so workgroups that are dispatched
 // round-robin over the 8 XCDs keep one slice of x (256 rows) per XCD L2 when there are 8 m-tiles.
@@ -20,10 +24,10 @@
 
 namespace rwkvq {
 
-constexpr int kPfMaxMats = 32;
-constexpr int BM = 256, BN = 256;        // block tile; the k-step is 64 columns
-constexpr int kRowBytes = 144;                 // 64 k * 2 B + 16 B pad
-constexpr int kTileBytes = 256 * kRowBytes;    // one operand tile
+constexpr int kPfMaxMats = 64;
+constexpr int BM = 256, BN = 256;              // block tile; the k-step is 64 columns
+constexpr int kRowBytes = 128;                 // 64 k * 2 B
+constexpr int kTileBytes = 256 * kRowBytes;    // one operand tile (32 KB)
 constexpr int kCb8Bytes = 1024;                // converted 8-bit-index codebook
 constexpr int kPfLds = 4 * kTileBytes + 2 * kCb8Bytes;
 
@@ -32,12 +36,19 @@ struct PfMat {
     const uint16_t* aux;
     const void* x;
     void* y;
-    int N, K, fmt, wg_end;
+    int N, K, fmt, pad;
 };
 struct PfArgs {
+    int wg_end[kPfMaxMats];
     PfMat m[kPfMaxMats];
-    int n_mats, M, ydt, m_tiles;
+    int M, ydt, m_tiles, pad;
 };
+
+// s_waitcnt immediates (gfx9 encoding): only the named counter is waited for.
+#define RWKVQ_WAIT_VM0_LGKM0() __builtin_amdgcn_s_waitcnt(0x0070)   /* vmcnt(0) lgkmcnt(0) */
+// Publish LDS writes (ds_write and load-unit copies) to the workgroup: the caller has waited for
+// its own writes; the barrier orders them against the other wavefronts' reads.
+#define RWKVQ_BARRIER() asm volatile("s_barrier" ::: "memory")
 
 template <bool BF16> struct Elem;
 template <> struct Elem<true> {
@@ -114,118 +125,116 @@ __device__ __forceinline__ uint4_t vq8_chunk(uint32_t w, const uint32_t* cb) {
 }
 
 // Packed words of one 256-column tile for the 4 row tiles (of 16 rows) a thread unpacks.
-struct WRegs {
-    uint4_t a[4];     // words 0..3 of the lane
-    uint4_t b[4];     // SQ / VQ6: words 4,5 in .x,.y ; VQ8: words 4..7
-    uint2_t sz[4];    // SQ: (scale,zero) of unit 0 and unit 1 for the lane's row
-    uint32_t cb;      // VQ6: converted codebook entry `lane`
-    uint4_t cb8;      // VQ8: 4 raw codebook entries (4*lane .. 4*lane+3)
+template <int FMT> struct WRegs;
+template <> struct WRegs<FMT_SQ3> { uint4_t a[4]; uint2_t b[4]; uint2_t sz[4]; };   // sz: (scale,zero) x 2 units
+template <> struct WRegs<FMT_VQ6> { uint4_t a[4]; uint2_t b[4]; uint32_t cb; };     // cb: codebook entry `lane`
+template <> struct WRegs<FMT_VQ8> { uint4_t a[4]; uint4_t b[4]; uint4_t cb8; };     // cb8: entries 4*lane..+3
+
+// Where a wavefront finds its packed words: uniform tile pointers for its 4 row tiles.
+struct WSrc {
+    const uint32_t* rows[4];   // start of row tile R0 + 4*wave + i (advance by tile words per T)
+    const uint16_t* aux;       // SQ: scale/zero of row tile R0 + 4*wave (16 uint2 per tile and T); VQ: codebooks of the block row
+    int KT;
 };
 
-__device__ __forceinline__ void w_load(WRegs& r, const PfMat& mt, int R0, int T, int wave, int lane) {
-    const int KT = mt.K >> 8;
-    if (mt.fmt == FMT_VQ8) {
+template <int FMT>
+__device__ __forceinline__ void w_load(WRegs<FMT>& r, const WSrc& src, int T, int lane) {
+    constexpr int tw = FMT == FMT_VQ8 ? 512 : 384;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t* tile = mt.codes + ((size_t)(R0 + 4 * wave + i) * KT + T) * 512;
-            r.a[i] = *(const uint4_t*)(tile + 4 * lane);
-            r.b[i] = *(const uint4_t*)(tile + 256 + 4 * lane);
-        }
-        r.cb8 = ((const uint4_t*)mt.aux)[((size_t)(R0 >> 4) * KT + T) * 64 + lane];
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t* tile = src.rows[i] + (size_t)T * tw;
+        r.a[i] = *(const uint4_t*)(tile + 4 * lane);
+        if constexpr (FMT == FMT_VQ8) r.b[i] = *(const uint4_t*)(tile + 256 + 4 * lane);
+        else r.b[i] = *(const uint2_t*)(tile + 256 + 2 * lane);
+    }
+    if constexpr (FMT == FMT_SQ3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            r.sz[i] = ((const uint2_t*)src.aux + ((size_t)i * src.KT + T) * 16)[lane & 15];
+    } else if constexpr (FMT == FMT_VQ6) {
+        r.cb = ((const uint32_t*)src.aux + (size_t)T * 64)[lane];
     } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t* tile = mt.codes + ((size_t)(R0 + 4 * wave + i) * KT + T) * 384;
-            r.a[i] = *(const uint4_t*)(tile + 4 * lane);
-            uint2_t b = *(const uint2_t*)(tile + 256 + 2 * lane);
-            r.b[i].x = b.x; r.b[i].y = b.y;
-        }
-        if (mt.fmt == FMT_SQ3) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                r.sz[i] = ((const uint2_t*)mt.aux)[((size_t)(R0 + 4 * wave + i) * KT + T) * 16 + (lane & 15)];
-        } else {
-            r.cb = ((const uint32_t*)mt.aux)[((size_t)(R0 >> 4) * KT + T) * 64 + lane];
-        }
+        r.cb8 = ((const uint4_t*)src.aux + (size_t)T * 64)[lane];
     }
 }
 
+// LDS byte offset, inside a tile, of logical 16-byte chunk c (0..7) of row `row`.
+__device__ __forceinline__ int tile_off(int row, int c) { return row * kRowBytes + ((c ^ ((row >> 1) & 7)) << 4); }
+
 // Unpack k-step KQ (0..3: 64 columns) of the tile held in r and write it to the W tile in LDS.
-template <bool BF16, int KQ>
-__device__ __forceinline__ void w_unpack(const WRegs& r, int fmt, char* wt, uint32_t* cb8, int wave, int lane) {
+template <bool BF16, int FMT, int KQ>
+__device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const uint32_t* cb8, int wave, int lane) {
     constexpr int u = KQ >> 1, t0 = 2 * (KQ & 1);
-    char* dst = wt + (64 * wave + (lane & 15)) * kRowBytes + 16 * (lane >> 4);
-    if (fmt == FMT_SQ3) {
+    const int row0 = 64 * wave + (lane & 15), kg = lane >> 4;
+    // rows row0 + 16 i share (row >> 1) & 7, so the two chunk offsets are the same for all four
+    char* d0 = wt + tile_off(row0, kg);
+    char* d1 = wt + tile_off(row0, 4 + kg);
+    if constexpr (FMT == FMT_SQ3) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t w0 = u == 0 ? r.a[i].x : r.a[i].w, w1 = u == 0 ? r.a[i].y : r.b[i].x,
                            w2 = u == 0 ? r.a[i].z : r.b[i].y;
             const uint32_t szw = u == 0 ? r.sz[i].x : r.sz[i].y;
             const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu)), z = f16_bits_to_f32((uint16_t)(szw >> 16));
-            *(uint4_t*)(dst + 16 * i * kRowBytes) = sq_chunk<BF16, t0>(w0, w1, w2, s, z);
-            *(uint4_t*)(dst + 16 * i * kRowBytes + 64) = sq_chunk<BF16, t0 + 1>(w0, w1, w2, s, z);
+            *(uint4_t*)(d0 + 16 * i * kRowBytes) = sq_chunk<BF16, t0>(w0, w1, w2, s, z);
+            *(uint4_t*)(d1 + 16 * i * kRowBytes) = sq_chunk<BF16, t0 + 1>(w0, w1, w2, s, z);
         }
-    } else if (fmt == FMT_VQ6) {
+    } else if constexpr (FMT == FMT_VQ6) {
         const uint32_t cb = Elem<BF16>::from_f16x2(r.cb);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t w0 = u == 0 ? r.a[i].x : r.a[i].w, w1 = u == 0 ? r.a[i].y : r.b[i].x,
                            w2 = u == 0 ? r.a[i].z : r.b[i].y;
-            *(uint4_t*)(dst + 16 * i * kRowBytes) = vq6_chunk<t0>(w0, w1, w2, cb);
-            *(uint4_t*)(dst + 16 * i * kRowBytes + 64) = vq6_chunk<t0 + 1>(w0, w1, w2, cb);
+            *(uint4_t*)(d0 + 16 * i * kRowBytes) = vq6_chunk<t0>(w0, w1, w2, cb);
+            *(uint4_t*)(d1 + 16 * i * kRowBytes) = vq6_chunk<t0 + 1>(w0, w1, w2, cb);
         }
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t wa = u == 0 ? (t0 == 0 ? r.a[i].x : r.a[i].z) : (t0 == 0 ? r.b[i].x : r.b[i].z);
             const uint32_t wb = u == 0 ? (t0 == 0 ? r.a[i].y : r.a[i].w) : (t0 == 0 ? r.b[i].y : r.b[i].w);
-            *(uint4_t*)(dst + 16 * i * kRowBytes) = vq8_chunk(wa, cb8);
-            *(uint4_t*)(dst + 16 * i * kRowBytes + 64) = vq8_chunk(wb, cb8);
+            *(uint4_t*)(d0 + 16 * i * kRowBytes) = vq8_chunk(wa, cb8);
+            *(uint4_t*)(d1 + 16 * i * kRowBytes) = vq8_chunk(wb, cb8);
         }
     }
 }
 
-struct XTile { uint4_t v[8]; };
-
-__device__ __forceinline__ void x_tile_load(XTile& r, const uint16_t* x, int M, int K, int m0, int k0, int tid) {
+// Copy the activation tile, columns k0..k0+63 of the block's 256 rows, into an LDS tile, 16 bytes
+// per lane and instruction, the load unit writing LDS directly.  LDS slot p (16 bytes) = row
+// p/8, position p%8; the lane that owns slot p fetches the logical chunk the swizzle stores there.
+// xoff[i] is the lane's byte offset (row * K * 2 + chunk * 16) from the tile's first row, computed
+// once; xk = activations of the tile's first row at column k0 (uniform).
+__device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff)[8], char* xt, int wave) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int c = tid + 256 * i, row = c >> 3, col = c & 7;
-        int m = m0 + row;
-        m = m < M ? m : M - 1;
-        r.v[i] = *(const uint4_t*)(x + (size_t)m * K + k0 + 8 * col);
-    }
-}
-__device__ __forceinline__ void x_tile_store(const XTile& r, char* xt, int tid) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int c = tid + 256 * i, row = c >> 3, col = c & 7;
-        *(uint4_t*)(xt + row * kRowBytes + 16 * col) = r.v[i];
-    }
+    for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xk + xoff[i]),
+                                         (__attribute__((address_space(3))) void*)(xt + (256 * i + 64 * wave) * 16),
+                                         16, 0, 0);
 }
 
 template <bool BF16>
 __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm, int wn, int lane,
                                          float4_t (&acc)[8][8]) {
-    const char* xa = xt + (128 * wm + (lane & 15)) * kRowBytes + 16 * (lane >> 4);
-    const char* wb = wt + (128 * wn + (lane & 15)) * kRowBytes + 16 * (lane >> 4);
+    const int r = lane & 15, kg = lane >> 4;
 #pragma unroll
     for (int k32 = 0; k32 < 2; ++k32) {
+        const char* xa = xt + tile_off(128 * wm + r, 4 * k32 + kg);
+        const char* wb = wt + tile_off(128 * wn + r, 4 * k32 + kg);
         uint4_t b[8];
 #pragma unroll
-        for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb + 16 * ni * kRowBytes + 64 * k32);
+        for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb + 16 * ni * kRowBytes);
 #pragma unroll
         for (int mi = 0; mi < 8; ++mi) {
-            uint4_t a = *(const uint4_t*)(xa + 16 * mi * kRowBytes + 64 * k32);
+            uint4_t a = *(const uint4_t*)(xa + 16 * mi * kRowBytes);
 #pragma unroll
             for (int ni = 0; ni < 8; ++ni) acc[mi][ni] = Elem<BF16>::mfma(a, b[ni], acc[mi][ni]);
         }
     }
 }
 
-// Convert and stage the 8-bit-index codebook of the current tile (256 entries) into LDS.
+// Convert and stage the 8-bit-index codebook of a tile (256 entries) into LDS.
 template <bool BF16>
-__device__ __forceinline__ void cb8_store(const WRegs& r, uint32_t* cb8, int wave, int lane) {
+__device__ __forceinline__ void cb8_store(const WRegs<FMT_VQ8>& r, uint32_t* cb8, int wave, int lane) {
     if (wave == 0) {
         uint4_t c = {Elem<BF16>::from_f16x2(r.cb8.x), Elem<BF16>::from_f16x2(r.cb8.y),
                      Elem<BF16>::from_f16x2(r.cb8.z), Elem<BF16>::from_f16x2(r.cb8.w)};
@@ -233,9 +242,11 @@ __device__ __forceinline__ void cb8_store(const WRegs& r, uint32_t* cb8, int wav
     }
 }
 
-template <bool BF16>
+// All matrices of one launch have the format FMT.  The k loop has no conditionals: past the last
+// column tile the prefetches simply fetch the last tile again (never used).
+template <bool BF16, int FMT>
 __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
     char* const xt0 = lds;
     char* const xt1 = lds + kTileBytes;
     char* const wt0 = lds + 2 * kTileBytes;
@@ -244,15 +255,34 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 #define CB8(i) (cb8base + ((i) & 1) * (kCb8Bytes / 4))
 
     const int wg = blockIdx.x;
-    int mi_ = 0;
-    while (mi_ + 1 < a.n_mats && wg >= a.m[mi_].wg_end) ++mi_;
+    static_assert(kPfMaxMats == 64, "one table entry per lane");
+    const int mi_ = __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[threadIdx.x & 63]));
     const PfMat mt = a.m[mi_];
-    const int local = wg - (mi_ ? a.m[mi_ - 1].wg_end : 0);
+    const int local = wg - (mi_ ? a.wg_end[mi_ - 1] : 0);
     const int m0 = (local % a.m_tiles) * BM, n0 = (local / a.m_tiles) * BN;
     const int M = a.M, K = mt.K, KT = K >> 8, R0 = n0 >> 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-    const uint16_t* x = (const uint16_t*)mt.x;
-    const int fmt = mt.fmt;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
+
+    // per-lane activation offsets (rows past M repeat row M - 1)
+    uint32_t xoff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int p = 256 * i + 64 * wave + lane;
+        const int row = p >> 3, c = (p & 7) ^ ((row >> 1) & 7);
+        const int rr = m0 + row < M ? row : M - 1 - m0;
+        xoff[i] = (uint32_t)rr * (uint32_t)K * 2u + 16u * c;
+    }
+    const char* xrow0 = (const char*)mt.x + (size_t)m0 * K * 2;
+
+    WSrc src;
+    constexpr int tw = FMT == FMT_VQ8 ? 512 : 384;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) src.rows[i] = mt.codes + (size_t)(R0 + 4 * wave + i) * KT * tw;
+    src.KT = KT;
+    if constexpr (FMT == FMT_SQ3) src.aux = (const uint16_t*)((const uint2_t*)mt.aux + (size_t)(R0 + 4 * wave) * KT * 16);
+    else if constexpr (FMT == FMT_VQ6) src.aux = (const uint16_t*)((const uint32_t*)mt.aux + (size_t)(R0 >> 4) * KT * 64);
+    else src.aux = (const uint16_t*)((const uint4_t*)mt.aux + (size_t)(R0 >> 4) * KT * 64);
 
     float4_t acc[8][8];
 #pragma unroll
@@ -261,50 +291,49 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
         for (int j = 0; j < 8; ++j) acc[i][j] = float4_t{0, 0, 0, 0};
 
     // prologue: tile 0, k-step 0 into buffer 0
-    WRegs wr;
-    XTile xr;
-    w_load(wr, mt, R0, 0, wave, lane);
-    x_tile_load(xr, x, M, K, m0, 0, tid);
-    if (fmt == FMT_VQ8) {
+    WRegs<FMT> wr;
+    w_load<FMT>(wr, src, 0, lane);
+    x_tile_dma(xrow0, xoff, xt0, wave);
+    if constexpr (FMT == FMT_VQ8) {
         cb8_store<BF16>(wr, CB8(0), wave, lane);
-        __syncthreads();
+        RWKVQ_WAIT_VM0_LGKM0();
+        RWKVQ_BARRIER();
     }
-    w_unpack<BF16, 0>(wr, fmt, wt0, CB8(0), wave, lane);
-    x_tile_store(xr, xt0, tid);
-    __syncthreads();
+    w_unpack<BF16, FMT, 0>(wr, wt0, CB8(0), wave, lane);
+    RWKVQ_WAIT_VM0_LGKM0();
+    RWKVQ_BARRIER();
 
     for (int T = 0; T < KT; ++T) {
-        const bool last = T + 1 == KT;
-        // k-steps 0..2 of this tile: next step comes from the same packed words
-        x_tile_load(xr, x, M, K, m0, 256 * T + 64, tid);
+        const int Tn = T + 1 < KT ? T + 1 : T;
+        const char* xk = xrow0 + (size_t)T * 512;
+        // k-step 0 of the tile is in buffer 0; steps 1..3 come from the same packed words.
+        x_tile_dma(xk + 128, xoff, xt1, wave);
         mma_step<BF16>(xt0, wt0, wm, wn, lane, acc);
-        w_unpack<BF16, 1>(wr, fmt, wt1, CB8(T), wave, lane);
-        x_tile_store(xr, xt1, tid);
-        __syncthreads();
+        w_unpack<BF16, FMT, 1>(wr, wt1, CB8(T), wave, lane);
+        RWKVQ_WAIT_VM0_LGKM0();
+        RWKVQ_BARRIER();
 
-        x_tile_load(xr, x, M, K, m0, 256 * T + 128, tid);
+        x_tile_dma(xk + 256, xoff, xt0, wave);
         mma_step<BF16>(xt1, wt1, wm, wn, lane, acc);
-        w_unpack<BF16, 2>(wr, fmt, wt0, CB8(T), wave, lane);
-        x_tile_store(xr, xt0, tid);
-        __syncthreads();
+        w_unpack<BF16, FMT, 2>(wr, wt0, CB8(T), wave, lane);
+        RWKVQ_WAIT_VM0_LGKM0();
+        RWKVQ_BARRIER();
 
-        x_tile_load(xr, x, M, K, m0, 256 * T + 192, tid);
-        WRegs wn_;
-        if (!last) w_load(wn_, mt, R0, T + 1, wave, lane);
+        WRegs<FMT> wnext;
+        w_load<FMT>(wnext, src, Tn, lane);                   // has a whole MFMA step to arrive
+        x_tile_dma(xk + 384, xoff, xt1, wave);
         mma_step<BF16>(xt0, wt0, wm, wn, lane, acc);
-        w_unpack<BF16, 3>(wr, fmt, wt1, CB8(T), wave, lane);
-        x_tile_store(xr, xt1, tid);
-        if (!last && fmt == FMT_VQ8) cb8_store<BF16>(wn_, CB8(T + 1), wave, lane);
-        __syncthreads();
+        w_unpack<BF16, FMT, 3>(wr, wt1, CB8(T), wave, lane);
+        if constexpr (FMT == FMT_VQ8) cb8_store<BF16>(wnext, CB8(T + 1), wave, lane);
+        RWKVQ_WAIT_VM0_LGKM0();
+        RWKVQ_BARRIER();
 
-        if (!last) x_tile_load(xr, x, M, K, m0, 256 * T + 256, tid);
+        x_tile_dma(xrow0 + (size_t)Tn * 512, xoff, xt0, wave);
         mma_step<BF16>(xt1, wt1, wm, wn, lane, acc);
-        if (!last) {
-            wr = wn_;
-            w_unpack<BF16, 0>(wr, fmt, wt0, CB8(T + 1), wave, lane);
-            x_tile_store(xr, xt0, tid);
-        }
-        __syncthreads();
+        wr = wnext;
+        w_unpack<BF16, FMT, 0>(wr, wt0, CB8(T + 1), wave, lane);
+        RWKVQ_WAIT_VM0_LGKM0();
+        RWKVQ_BARRIER();
     }
 
     // epilogue: lane holds rows 4*(lane/16) + i, column lane%16 of every 16 x 16 tile
@@ -325,33 +354,48 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 #undef CB8
 }
 
-hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
+template <bool BF16, int FMT>
+static hipError_t launch_fmt(const PfArgs& a, int wgs, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<true>,
+        hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<BF16, FMT>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)prefill_kernel<false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    hipLaunchKernelGGL((prefill_kernel<BF16, FMT>), dim3(wgs), dim3(256), kPfLds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
     const int m_tiles = (M + BM - 1) / BM;
-    for (int base = 0; base < n_mats; base += kPfMaxMats) {
-        PfArgs a;
-        int cnt = n_mats - base < kPfMaxMats ? n_mats - base : kPfMaxMats;
-        int wgs = 0;
-        for (int i = 0; i < cnt; ++i) {
-            const MatDev& m = mats[base + i];
-            wgs += m_tiles * (m.N / BN);
-            a.m[i] = PfMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, wgs};
+    // one grouped launch per format and per 64 matrices
+    for (int fmt = 0; fmt < 3; ++fmt) {
+        int i = 0;
+        while (i < n_mats) {
+            PfArgs a;
+            int cnt = 0, wgs = 0;
+            for (; i < n_mats && cnt < kPfMaxMats; ++i) {
+                const MatDev& m = mats[i];
+                if (m.fmt != fmt) continue;
+                wgs += m_tiles * (m.N / BN);
+                a.m[cnt] = PfMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, 0};
+                a.wg_end[cnt] = wgs;
+                ++cnt;
+            }
+            if (cnt == 0) break;
+            for (int j = cnt; j < kPfMaxMats; ++j) {
+                a.m[j] = PfMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+                a.wg_end[j] = 0x7FFFFFFF;
+            }
+            a.M = M; a.ydt = y_dtype; a.m_tiles = m_tiles; a.pad = 0;
+            hipError_t e;
+            const bool bf = x_dtype == DT_BF16;
+            if (fmt == FMT_SQ3) e = bf ? launch_fmt<true, FMT_SQ3>(a, wgs, s) : launch_fmt<false, FMT_SQ3>(a, wgs, s);
+            else if (fmt == FMT_VQ6) e = bf ? launch_fmt<true, FMT_VQ6>(a, wgs, s) : launch_fmt<false, FMT_VQ6>(a, wgs, s);
+            else e = bf ? launch_fmt<true, FMT_VQ8>(a, wgs, s) : launch_fmt<false, FMT_VQ8>(a, wgs, s);
+            if (e != hipSuccess) return e;
         }
-        for (int i = cnt; i < kPfMaxMats; ++i) a.m[i] = PfMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, wgs};
-        a.n_mats = cnt; a.M = M; a.ydt = y_dtype; a.m_tiles = m_tiles;
-        if (x_dtype == DT_BF16) hipLaunchKernelGGL(prefill_kernel<true>, dim3(wgs), dim3(256), kPfLds, s, a);
-        else hipLaunchKernelGGL(prefill_kernel<false>, dim3(wgs), dim3(256), kPfLds, s, a);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
