@@ -52,9 +52,10 @@ struct PfArgs {
 
 template <bool BF16> struct Elem;
 template <> struct Elem<true> {
-    static __device__ __forceinline__ float4_t mfma(uint4_t a, uint4_t b, float4_t c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    // accumulate in place; the "a" constraint pins the accumulator to the AGPR half of the
+    // register file (left to itself the allocator starts it in VGPRs and shuffles it all loop long)
+    static __device__ __forceinline__ void mfma(uint4_t a, uint4_t b, float4_t& c) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) {   // v_cvt_pk_bf16_f32
         typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
@@ -67,9 +68,8 @@ template <> struct Elem<true> {
     }
 };
 template <> struct Elem<false> {
-    static __device__ __forceinline__ float4_t mfma(uint4_t a, uint4_t b, float4_t c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
-                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    static __device__ __forceinline__ void mfma(uint4_t a, uint4_t b, float4_t& c) {
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
         half2_t v = {(half_t)lo, (half_t)hi};
@@ -212,6 +212,10 @@ __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff
                                          16, 0, 0);
 }
 
+// One k-step (64 columns) of the wavefront tile: per 32 columns, the eight W fragments stay in
+// registers while the eight x fragments stream through, one ahead of the MFMAs that use it.  The
+// scheduling barriers keep the compiler from hoisting every LDS read to the top (which costs more
+// registers than there are).
 template <bool BF16>
 __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm, int wn, int lane,
                                          float4_t (&acc)[8][8]) {
@@ -223,11 +227,14 @@ __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm,
         uint4_t b[8];
 #pragma unroll
         for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb + 16 * ni * kRowBytes);
+        uint4_t a = *(const uint4_t*)xa;
 #pragma unroll
         for (int mi = 0; mi < 8; ++mi) {
-            uint4_t a = *(const uint4_t*)(xa + 16 * mi * kRowBytes);
+            uint4_t an = a;
+            if (mi < 7) an = *(const uint4_t*)(xa + 16 * (mi + 1) * kRowBytes);
 #pragma unroll
-            for (int ni = 0; ni < 8; ++ni) acc[mi][ni] = Elem<BF16>::mfma(a, b[ni], acc[mi][ni]);
+            for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(a, b[ni], acc[mi][ni]);
+            a = an;
         }
     }
 }
@@ -319,22 +326,30 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
         RWKVQ_WAIT_VM0_LGKM0();
         RWKVQ_BARRIER();
 
-        WRegs<FMT> wnext;
-        w_load<FMT>(wnext, src, Tn, lane);                   // has a whole MFMA step to arrive
         x_tile_dma(xk + 384, xoff, xt1, wave);
         mma_step<BF16>(xt0, wt0, wm, wn, lane, acc);
         w_unpack<BF16, FMT, 3>(wr, wt1, CB8(T), wave, lane);
-        if constexpr (FMT == FMT_VQ8) cb8_store<BF16>(wnext, CB8(T + 1), wave, lane);
         RWKVQ_WAIT_VM0_LGKM0();
         RWKVQ_BARRIER();
 
+        // the packed words of this tile are spent: fetch the next tile's into the same registers;
+        // they have a whole MFMA step to arrive
+        w_load<FMT>(wr, src, Tn, lane);
         x_tile_dma(xrow0 + (size_t)Tn * 512, xoff, xt0, wave);
         mma_step<BF16>(xt1, wt1, wm, wn, lane, acc);
-        wr = wnext;
+        if constexpr (FMT == FMT_VQ8) {
+            cb8_store<BF16>(wr, CB8(T + 1), wave, lane);
+            RWKVQ_WAIT_VM0_LGKM0();
+            RWKVQ_BARRIER();
+        }
         w_unpack<BF16, FMT, 0>(wr, wt0, CB8(T + 1), wave, lane);
         RWKVQ_WAIT_VM0_LGKM0();
         RWKVQ_BARRIER();
     }
+
+    // The MFMAs are opaque to the compiler's hazard checks: let the last ones drain before the
+    // accumulators are read (the longest MFMA-to-read hazard is well under 32 cycles).
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
     // epilogue: lane holds rows 4*(lane/16) + i, column lane%16 of every 16 x 16 tile
     const int N = mt.N;
