@@ -9,8 +9,9 @@
 // Tiling: workgroup = 256 threads = 2 x 2 wavefronts, block tile 256 (m) x 256 (n) x 64 (k),
 // wavefront tile 128 x 128 = 8 x 8 MFMA tiles (256 accumulator registers).  Both operand tiles
 // live in LDS as 256 rows of 128 bytes (64 k), with the eight 16-byte chunks of a row stored at
-// chunk ^ ((row >> 1) & 7): any 16 consecutive rows read the same logical chunk from 16 distinct
-// bank groups, so fragment reads and tile writes are conflict free without padding.
+// chunk ^ (row & 7): a row is exactly one pass over the 32 LDS banks, so any 8 consecutive rows
+// read the same logical chunk from 8 distinct bank groups - fragment reads (eight lanes of 16
+// bytes per cycle) and tile writes are conflict free without padding.
 //   * activations: copied global -> LDS by the load unit itself (global_load_lds_dwordx4), no
 //     registers and no vector-ALU work; each lane fetches the chunk that belongs at its slot;
 //   * weights: packed words are fetched once per 256 columns, unpacked by the vector ALU one
@@ -21,6 +22,9 @@
 // Workgroup -> tile order: the m-tile index runs fastest, so workgroups that are dispatched
 // round-robin over the 8 XCDs keep one slice of x (256 rows) per XCD L2 when there are 8 m-tiles.
 #include "common.h"
+
+#include <algorithm>
+#include <vector>
 
 namespace rwkvq {
 
@@ -48,14 +52,25 @@ struct PfArgs {
 #define RWKVQ_WAIT_VM0_LGKM0() __builtin_amdgcn_s_waitcnt(0x0070)   /* vmcnt(0) lgkmcnt(0) */
 // Publish LDS writes (ds_write and load-unit copies) to the workgroup: the caller has waited for
 // its own writes; the barrier orders them against the other wavefronts' reads.
+#ifndef RWKVQ_EXP_PF
+#define RWKVQ_EXP_PF 0      /* experiment builds only: 1 no x copy, 2 no unpack, 4 no MFMA, 8 no barrier */
+#endif
+#if RWKVQ_EXP_PF & 8
+#define RWKVQ_BARRIER() asm volatile("" ::: "memory")
+#else
 #define RWKVQ_BARRIER() asm volatile("s_barrier" ::: "memory")
+#endif
 
 template <bool BF16> struct Elem;
 template <> struct Elem<true> {
     // accumulate in place; the "a" constraint pins the accumulator to the AGPR half of the
     // register file (left to itself the allocator starts it in VGPRs and shuffles it all loop long)
     static __device__ __forceinline__ void mfma(uint4_t a, uint4_t b, float4_t& c) {
+#if RWKVQ_EXP_PF & 4
+        asm volatile("v_accvgpr_write_b32 %0, %1" : "+a"(c) : "v"(a.x ^ b.x));
+#else
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+#endif
     }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) {   // v_cvt_pk_bf16_f32
         typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
@@ -159,19 +174,24 @@ __device__ __forceinline__ void w_load(WRegs<FMT>& r, const WSrc& src, int T, in
 }
 
 // LDS byte offset, inside a tile, of logical 16-byte chunk c (0..7) of row `row`.
-__device__ __forceinline__ int tile_off(int row, int c) { return row * kRowBytes + ((c ^ ((row >> 1) & 7)) << 4); }
+__device__ __forceinline__ int tile_off(int row, int c) { return row * kRowBytes + ((c ^ (row & 7)) << 4); }
 
 // Unpack k-step KQ (0..3: 64 columns) of the tile held in r and write it to the W tile in LDS.
-template <bool BF16, int FMT, int KQ>
+// Row tiles I0 .. I1-1 of the thread's four (so that the work can be spread over a k-step).
+template <bool BF16, int FMT, int KQ, int I0 = 0, int I1 = 4>
 __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const uint32_t* cb8, int wave, int lane) {
+#if RWKVQ_EXP_PF & 2
+    if (I0 == 0) *(uint4_t*)(wt + 16 * lane) = r.a[0] ^ r.a[1] ^ r.a[2] ^ r.a[3];
+    return;
+#endif
     constexpr int u = KQ >> 1, t0 = 2 * (KQ & 1);
     const int row0 = 64 * wave + (lane & 15), kg = lane >> 4;
-    // rows row0 + 16 i share (row >> 1) & 7, so the two chunk offsets are the same for all four
+    // rows row0 + 16 i share row & 7, so the two chunk offsets are the same for all four
     char* d0 = wt + tile_off(row0, kg);
     char* d1 = wt + tile_off(row0, 4 + kg);
     if constexpr (FMT == FMT_SQ3) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = I0; i < I1; ++i) {
             const uint32_t w0 = u == 0 ? r.a[i].x : r.a[i].w, w1 = u == 0 ? r.a[i].y : r.b[i].x,
                            w2 = u == 0 ? r.a[i].z : r.b[i].y;
             const uint32_t szw = u == 0 ? r.sz[i].x : r.sz[i].y;
@@ -182,7 +202,7 @@ __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const ui
     } else if constexpr (FMT == FMT_VQ6) {
         const uint32_t cb = Elem<BF16>::from_f16x2(r.cb);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = I0; i < I1; ++i) {
             const uint32_t w0 = u == 0 ? r.a[i].x : r.a[i].w, w1 = u == 0 ? r.a[i].y : r.b[i].x,
                            w2 = u == 0 ? r.a[i].z : r.b[i].y;
             *(uint4_t*)(d0 + 16 * i * kRowBytes) = vq6_chunk<t0>(w0, w1, w2, cb);
@@ -190,7 +210,7 @@ __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const ui
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = I0; i < I1; ++i) {
             const uint32_t wa = u == 0 ? (t0 == 0 ? r.a[i].x : r.a[i].z) : (t0 == 0 ? r.b[i].x : r.b[i].z);
             const uint32_t wb = u == 0 ? (t0 == 0 ? r.a[i].y : r.a[i].w) : (t0 == 0 ? r.b[i].y : r.b[i].w);
             *(uint4_t*)(d0 + 16 * i * kRowBytes) = vq8_chunk(wa, cb8);
@@ -205,6 +225,9 @@ __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const ui
 // xoff[i] is the lane's byte offset (row * K * 2 + chunk * 16) from the tile's first row, computed
 // once; xk = activations of the tile's first row at column k0 (uniform).
 __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff)[8], char* xt, int wave) {
+#if RWKVQ_EXP_PF & 1
+    return;
+#endif
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xk + xoff[i]),
@@ -212,30 +235,44 @@ __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff
                                          16, 0, 0);
 }
 
-// One k-step (64 columns) of the wavefront tile: per 32 columns, the eight W fragments stay in
-// registers while the eight x fragments stream through, one ahead of the MFMAs that use it.  The
-// scheduling barriers keep the compiler from hoisting every LDS read to the top (which costs more
-// registers than there are).
-template <bool BF16>
+// One k-step (64 columns) of the wavefront tile = 16 rows of 8 MFMAs: x fragment f (f = 0..15:
+// m-subtile f%8 of column half f/8) against the eight W fragments of that half.  x fragments are
+// read kAhead rows ahead of their use and the W fragments of the second half during rows 4..7,
+// so that an LDS round trip is hidden behind several rows of MFMAs.  `early` runs right after
+// the first LDS reads have been issued and `mid` between the halves: vector-ALU work placed
+// there (unpacking the next k-step) covers more latency.
+constexpr int kAhead = 3;
+template <bool BF16, class F0, class F1>
 __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm, int wn, int lane,
-                                         float4_t (&acc)[8][8]) {
+                                         float4_t (&acc)[8][8], F0 early, F1 mid) {
     const int r = lane & 15, kg = lane >> 4;
+    const char* xa[2] = {xt + tile_off(128 * wm + r, kg), xt + tile_off(128 * wm + r, 4 + kg)};
+    const char* wb0 = wt + tile_off(128 * wn + r, kg);
+    const char* wb1 = wt + tile_off(128 * wn + r, 4 + kg);
+    uint4_t b[8], b1[8], a[kAhead + 1];
 #pragma unroll
-    for (int k32 = 0; k32 < 2; ++k32) {
-        const char* xa = xt + tile_off(128 * wm + r, 4 * k32 + kg);
-        const char* wb = wt + tile_off(128 * wn + r, 4 * k32 + kg);
-        uint4_t b[8];
+    for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb0 + 16 * ni * kRowBytes);
 #pragma unroll
-        for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb + 16 * ni * kRowBytes);
-        uint4_t a = *(const uint4_t*)xa;
+    for (int f = 0; f < kAhead; ++f) a[f] = *(const uint4_t*)(xa[0] + 16 * f * kRowBytes);
+    early();
 #pragma unroll
-        for (int mi = 0; mi < 8; ++mi) {
-            uint4_t an = a;
-            if (mi < 7) an = *(const uint4_t*)(xa + 16 * (mi + 1) * kRowBytes);
-#pragma unroll
-            for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(a, b[ni], acc[mi][ni]);
-            a = an;
+    for (int f = 0; f < 16; ++f) {
+        if (f == 8) mid();
+        if (f + kAhead < 16)
+            a[(f + kAhead) % (kAhead + 1)] = *(const uint4_t*)(xa[(f + kAhead) >> 3] + 16 * ((f + kAhead) & 7) * kRowBytes);
+        if (f >= 4 && f < 8) {
+            b1[2 * (f - 4)] = *(const uint4_t*)(wb1 + 16 * (2 * (f - 4)) * kRowBytes);
+            b1[2 * (f - 4) + 1] = *(const uint4_t*)(wb1 + 16 * (2 * (f - 4) + 1) * kRowBytes);
         }
+#if RWKVQ_EXP_PF & 16
+        const uint4_t af = {0x3c003c00u + f, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(af, af, acc[f & 7][ni]);
+#else
+        const uint4_t af = a[f % (kAhead + 1)];
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(f < 8 ? b[ni] : b1[ni], af, acc[f & 7][ni]);
+#endif
     }
 }
 
@@ -276,7 +313,7 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int p = 256 * i + 64 * wave + lane;
-        const int row = p >> 3, c = (p & 7) ^ ((row >> 1) & 7);
+        const int row = p >> 3, c = (p & 7) ^ (row & 7);
         const int rr = m0 + row < M ? row : M - 1 - m0;
         xoff[i] = (uint32_t)rr * (uint32_t)K * 2u + 16u * c;
     }
@@ -315,20 +352,23 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
         const char* xk = xrow0 + (size_t)T * 512;
         // k-step 0 of the tile is in buffer 0; steps 1..3 come from the same packed words.
         x_tile_dma(xk + 128, xoff, xt1, wave);
-        mma_step<BF16>(xt0, wt0, wm, wn, lane, acc);
-        w_unpack<BF16, FMT, 1>(wr, wt1, CB8(T), wave, lane);
+        mma_step<BF16>(xt0, wt0, wm, wn, lane, acc,
+                       [&] { w_unpack<BF16, FMT, 1, 0, 2>(wr, wt1, CB8(T), wave, lane); },
+                       [&] { w_unpack<BF16, FMT, 1, 2, 4>(wr, wt1, CB8(T), wave, lane); });
         RWKVQ_WAIT_VM0_LGKM0();
         RWKVQ_BARRIER();
 
         x_tile_dma(xk + 256, xoff, xt0, wave);
-        mma_step<BF16>(xt1, wt1, wm, wn, lane, acc);
-        w_unpack<BF16, FMT, 2>(wr, wt0, CB8(T), wave, lane);
+        mma_step<BF16>(xt1, wt1, wm, wn, lane, acc,
+                       [&] { w_unpack<BF16, FMT, 2, 0, 2>(wr, wt0, CB8(T), wave, lane); },
+                       [&] { w_unpack<BF16, FMT, 2, 2, 4>(wr, wt0, CB8(T), wave, lane); });
         RWKVQ_WAIT_VM0_LGKM0();
         RWKVQ_BARRIER();
 
         x_tile_dma(xk + 384, xoff, xt1, wave);
-        mma_step<BF16>(xt0, wt0, wm, wn, lane, acc);
-        w_unpack<BF16, FMT, 3>(wr, wt1, CB8(T), wave, lane);
+        mma_step<BF16>(xt0, wt0, wm, wn, lane, acc,
+                       [&] { w_unpack<BF16, FMT, 3, 0, 2>(wr, wt1, CB8(T), wave, lane); },
+                       [&] { w_unpack<BF16, FMT, 3, 2, 4>(wr, wt1, CB8(T), wave, lane); });
         RWKVQ_WAIT_VM0_LGKM0();
         RWKVQ_BARRIER();
 
@@ -336,7 +376,7 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
         // they have a whole MFMA step to arrive
         w_load<FMT>(wr, src, Tn, lane);
         x_tile_dma(xrow0 + (size_t)Tn * 512, xoff, xt0, wave);
-        mma_step<BF16>(xt1, wt1, wm, wn, lane, acc);
+        mma_step<BF16>(xt1, wt1, wm, wn, lane, acc, [] {}, [] {});
         if constexpr (FMT == FMT_VQ8) {
             cb8_store<BF16>(wr, CB8(T + 1), wave, lane);
             RWKVQ_WAIT_VM0_LGKM0();
@@ -351,21 +391,29 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     // accumulators are read (the longest MFMA-to-read hazard is well under 32 cycles).
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
-    // epilogue: lane holds rows 4*(lane/16) + i, column lane%16 of every 16 x 16 tile
+    // epilogue: the W fragment is the A operand of the MFMA, so a lane holds, for every 16 x 16
+    // tile, output row m = lane%16 and the four consecutive columns n = 4*(lane/16) + 0..3:
+    // one 8-byte (or 16-byte for fp32) store per tile.
     const int N = mt.N;
 #pragma unroll
-    for (int mi = 0; mi < 8; ++mi)
+    for (int mi = 0; mi < 8; ++mi) {
+        const int m = m0 + 128 * wm + 16 * mi + (lane & 15);
+        if (m < M) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = m0 + 128 * wm + 16 * mi + 4 * (lane >> 4) + i;
-            if (m < M) {
-#pragma unroll
-                for (int ni = 0; ni < 8; ++ni) {
-                    const int n = n0 + 128 * wn + 16 * ni + (lane & 15);
-                    store_from_f32(mt.y, (size_t)m * N + n, a.ydt, acc[mi][ni][i]);
+            for (int ni = 0; ni < 8; ++ni) {
+                const size_t o = (size_t)m * N + n0 + 128 * wn + 16 * ni + 4 * (lane >> 4);
+                const float4_t v = acc[mi][ni];
+                if (a.ydt == DT_F32) {
+                    *(float4_t*)((float*)mt.y + o) = v;
+                } else {
+                    uint2_t pk;
+                    if (a.ydt == DT_BF16) { pk.x = Elem<true>::pack(v[0], v[1]); pk.y = Elem<true>::pack(v[2], v[3]); }
+                    else { pk.x = Elem<false>::pack(v[0], v[1]); pk.y = Elem<false>::pack(v[2], v[3]); }
+                    *(uint2_t*)((uint16_t*)mt.y + o) = pk;
                 }
             }
         }
+    }
 #undef CB8
 }
 
@@ -382,8 +430,13 @@ static hipError_t launch_fmt(const PfArgs& a, int wgs, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
+hipError_t launch_prefill(const MatDev* mats_in, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
     const int m_tiles = (M + BM - 1) / BM;
+    // Workgroups of a matrix with a long K run long: put those matrices first so that the end of
+    // a launch is filled by short workgroups.
+    std::vector<MatDev> sorted(mats_in, mats_in + n_mats);
+    std::stable_sort(sorted.begin(), sorted.end(), [](const MatDev& a, const MatDev& b) { return a.K > b.K; });
+    const MatDev* mats = sorted.data();
     // one grouped launch per format and per 64 matrices
     for (int fmt = 0; fmt < 3; ++fmt) {
         int i = 0;
