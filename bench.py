@@ -31,8 +31,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-DECODE_KERNEL = "decode_kernel<1>"
-PREFILL_KERNEL = "prefill_kernel<bf16>"
+DECODE_KERNEL = "rwkvq::decode_kernel<1>"
+PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT>"   # bf16; one instantiation per weight format
+DECODE_MATS_PER_LAUNCH = 64
+# HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
+# scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic.txt.
+DECODE_TRAFFIC_BYTES_PER_LAUNCH = 704.0e6
 
 
 def log(*a):
@@ -90,21 +94,24 @@ def time_steps(run, steps: int, warmup: int):
     return ev[0].elapsed_time(ev[steps]), per, wall_ms
 
 
-def cpu_baseline(n_layers):
+def cpu_baseline(n_layers, min_seconds=10.0, max_passes=8):
     """The oracle as it stands on the host cores: decode (M = 1) over the first n_layers layers of
-    the same stack (all 32 by default = the whole workload)."""
+    the same stack (all 32 by default = the whole workload), repeated until about min_seconds of
+    oracle time have been measured."""
     from oracle import rwkvq_oracle as orc
     from paper_2505_03803_amd import synth
-    nbytes, secs = 0, 0.0
-    for mat, x in synth.stack(3, 1, n_layers=n_layers):
-        xf = orc.widen(x, "f16")
-        t = time.perf_counter()
-        orc.linear(mat, xf, "f32")
-        secs += time.perf_counter() - t
-        nbytes += mat.packed_bytes
+    nbytes, secs, passes = 0, 0.0, 0
+    while secs < min_seconds and passes < max_passes:
+        for mat, x in synth.stack(3, 1, n_layers=n_layers):
+            xf = orc.widen(x, "f16")
+            t = time.perf_counter()
+            orc.linear(mat, xf, "f32")
+            secs += time.perf_counter() - t
+            nbytes += mat.packed_bytes
+        passes += 1
     return {"value": nbytes / secs / 1e9, "unit": "GB/s", "cores": orc.threads(), "kind": "oracle",
-            "sample": f"decode M=1, first {n_layers} of 32 layers of the RWKV-6-7B-shaped stack "
-                      f"({nbytes} packed weight bytes, {secs:.2f} s)"}
+            "sample": f"decode M=1, {passes} pass(es) over the first {n_layers} of 32 layers of the "
+                      f"RWKV-6-7B-shaped stack ({nbytes} packed weight bytes in {secs:.2f} s of oracle time)"}
 
 
 def main():
@@ -117,6 +124,8 @@ def main():
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=32)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); a multi-GPU figure is not "
@@ -128,6 +137,14 @@ def main():
         sys.exit("bench.py needs a GPU")
     B.lib()                                    # fails loudly if the HIP library is missing
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     # ---------------- decode leg: configuration 3
     t = time.time()
     dec = build_stack(3, 1, args.layers, gpu_activations=False, y_dtype=B.F16)
@@ -136,7 +153,7 @@ def main():
     total_ms, per, wall_ms = time_steps(run, args.steps, args.warmup)
     ms = total_ms / args.steps
     gbs = dec["wbytes"] / (ms * 1e-3) / 1e9
-    launches = (dec["n_mats"] + 63) // 64
+    launches = (dec["n_mats"] + DECODE_MATS_PER_LAUNCH - 1) // DECODE_MATS_PER_LAUNCH
     out = {
         "metric": "dequant-GEMV weight GB/s (% of HBM peak) + prefill TFLOP/s, RWKV-6-7B shapes",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -154,7 +171,7 @@ def main():
         "roofline": {"kernel": DECODE_KERNEL, "bound": "hbm",
                      "achieved": dec["wbytes"] / launches / (ms / launches * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": DECODE_TRAFFIC_BYTES_PER_LAUNCH,
                      "algorithmic_bytes_per_launch": dec["wbytes"] / launches,
                      "avg_launch_ms": ms / launches},
     }

@@ -159,22 +159,23 @@ template <int MT> struct Acc { static constexpr int n = MT == 1 ? 1 : 4; };
 // Software pipeline over the column tiles T = 0 .. KT-1: DEPTH tiles are in flight from HBM
 // while one is being consumed.  Every load in the loop is unconditional, so the compiler can
 // count outstanding loads exactly and wait only for the tile about to be consumed: past the
-// end of the row the loads simply fetch tile 0 again (a few cache hits, never used).
+// end of the row the loads simply fetch the last tile again (cache hits, never used).
 template <int DEPTH, class Regs, class Load, class Compute>
 __device__ __forceinline__ void tile_pipeline(int KT, Load load, Compute compute) {
     static_assert(DEPTH == 2 || DEPTH == 3, "pipeline depth");
+    const int last = KT - 1;
     Regs r0, r1, r2;
     load(r0, 0);
-    load(r1, 1 < KT ? 1 : 0);
-    if (DEPTH == 3) load(r2, 2 < KT ? 2 : 0);
+    load(r1, 1 < KT ? 1 : last);
+    if (DEPTH == 3) load(r2, 2 < KT ? 2 : last);
     for (int T = 0; T < KT; T += DEPTH) {
         compute(r0, T);
-        load(r0, T + DEPTH < KT ? T + DEPTH : 0);
+        load(r0, T + DEPTH < KT ? T + DEPTH : last);
         if (T + 1 < KT) compute(r1, T + 1);
-        load(r1, T + 1 + DEPTH < KT ? T + 1 + DEPTH : 0);
+        load(r1, T + 1 + DEPTH < KT ? T + 1 + DEPTH : last);
         if (DEPTH == 3) {
             if (T + 2 < KT) compute(r2, T + 2);
-            load(r2, T + 2 + DEPTH < KT ? T + 2 + DEPTH : 0);
+            load(r2, T + 2 + DEPTH < KT ? T + 2 + DEPTH : last);
         }
     }
 }
