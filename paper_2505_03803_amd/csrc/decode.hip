@@ -145,6 +145,36 @@ __device__ __forceinline__ void x_store(const XRegs<MT>& r, half_t* xs, int lane
     }
 }
 
+// v_dot2_f32_f16 on two packed fp16 pairs.
+__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {   // two fp16 pairs, scalars in
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
+}
+
+// v + (v of the lane that the DPP control selects); lanes the control leaves out add zero.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF);
+    return v + __builtin_bit_cast(float, o);
+}
+
+// Sums of the two 128-column groups of a 256-column activation tile held four columns per lane
+// (lanes 0-31: group 0, lanes 32-63: group 1), as wavefront-uniform values.  Lane-crossing adds
+// stay inside the vector ALU: two quad permutes and two mirrors give every lane the sum of its
+// row of 16, a row broadcast adds the row below to rows 1 and 3.
+__device__ __forceinline__ void tile_group_sums(uint2_t x, float& X0, float& X1) {
+    const uint32_t ones = 0x3C003C00u;
+    const uint32_t lo = x.x, hi = x.y;   // scalars first: a bit_cast of a vector member goes wrong
+    float v = dot2(lo, ones, 0.f);
+    v = dot2(hi, ones, v);
+    v = dpp_add<0xB1>(v);            // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);            // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);           // row_half_mirror
+    v = dpp_add<0x140>(v);           // row_mirror
+    v = dpp_add<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
+    X0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    X1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -156,26 +186,46 @@ template <int MT> struct Acc { static constexpr int n = MT == 1 ? 1 : 4; };
 
 #define RWKVQ_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (c), 0, 0, 0)
 
-// Software pipeline over the column tiles T = 0 .. KT-1: DEPTH tiles are in flight from HBM
-// while one is being consumed.  Every load in the loop is unconditional, so the compiler can
-// count outstanding loads exactly and wait only for the tile about to be consumed: past the
-// end of the row the loads simply fetch the last tile again (cache hits, never used).
+// Software pipeline over the column tiles T = 0 .. KT-1 with DEPTH tiles in flight from HBM
+// *while* a tile is being consumed: there is one register set more than the depth, and the load
+// of tile T + DEPTH is issued before tile T is computed (a wavefront that only reloaded a set
+// after consuming it would have one tile fewer in flight for the whole of its compute phase,
+// which is what bounds a latency-limited stream).  Every load is unconditional, so the compiler
+// counts outstanding loads exactly and waits only for the tile about to be consumed: past the
+// end of the row the loads fetch the last tile again (cache hits, never used).
 template <int DEPTH, class Regs, class Load, class Compute>
 __device__ __forceinline__ void tile_pipeline(int KT, Load load, Compute compute) {
     static_assert(DEPTH == 2 || DEPTH == 3, "pipeline depth");
     const int last = KT - 1;
-    Regs r0, r1, r2;
-    load(r0, 0);
-    load(r1, 1 < KT ? 1 : last);
-    if (DEPTH == 3) load(r2, 2 < KT ? 2 : last);
-    for (int T = 0; T < KT; T += DEPTH) {
-        compute(r0, T);
-        load(r0, T + DEPTH < KT ? T + DEPTH : last);
-        if (T + 1 < KT) compute(r1, T + 1);
-        load(r1, T + 1 + DEPTH < KT ? T + 1 + DEPTH : last);
-        if (DEPTH == 3) {
+    auto c = [&](int T) { return T < KT ? T : last; };
+    Regs r0, r1, r2, r3;
+    // The fences keep each tile's loads together and in program order, in the prologue too: the
+    // wait the compiler derives for a tile then lets all younger tiles stay in flight.
+    auto issue = [&](Regs& r, int T) {
+        load(r, c(T));
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    __builtin_amdgcn_sched_barrier(0);
+    issue(r0, 0);
+    issue(r1, 1);
+    if (DEPTH == 3) issue(r2, 2);
+    for (int T = 0; T < KT; T += DEPTH + 1) {
+        if (DEPTH == 2) {
+            issue(r2, T + 2);
+            compute(r0, T);
+            issue(r0, T + 3);
+            if (T + 1 < KT) compute(r1, T + 1);
+            issue(r1, T + 4);
             if (T + 2 < KT) compute(r2, T + 2);
-            load(r2, T + 2 + DEPTH < KT ? T + 2 + DEPTH : last);
+        } else {
+            issue(r3, T + 3);
+            compute(r0, T);
+            issue(r0, T + 4);
+            if (T + 1 < KT) compute(r1, T + 1);
+            issue(r1, T + 5);
+            if (T + 2 < KT) compute(r2, T + 2);
+            issue(r2, T + 6);
+            if (T + 3 < KT) compute(r3, T + 3);
         }
     }
 }
@@ -219,13 +269,21 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
         // All LDS reads of the tile are issued first; their latency is covered by the unpack work.
         half8_t xa[2][4];
         float4_t c8[2], cx[2];
+        if (MT == 1) {
+            // batch 1: the group sums come from the tile's own activations (as the fp16 values
+            // the MFMA sees); the constant 8 of the codes is folded into the zero point below
+            uint2_t xv = r.x.v[0];
+            if (wp.xbf16) { xv.x = bf16x2_to_f16x2(xv.x); xv.y = bf16x2_to_f16x2(xv.y); }
+            float X0, X1;
+            tile_group_sums(xv, X0, X1);
+            c8[0] = c8[1] = float4_t{0, 0, 0, 0};
+            cx[0] = float4_t{X0, 0, 0, 0};
+            cx[1] = float4_t{X1, 0, 0, 0};
+        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int g = 2 * T + u;
-            if (MT == 1) {
-                c8[u] = float4_t{xsum8[g], 0, 0, 0};
-                cx[u] = float4_t{xsumX[g], 0, 0, 0};
-            } else {
+            if (MT != 1) {
                 c8[u] = *(const float4_t*)(xsum8 + g * MT + mrow);
                 cx[u] = *(const float4_t*)(xsumX + g * MT + mrow);
             }
@@ -246,7 +304,8 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
                 acc = RWKVQ_MFMA(xa[u][3], sq_operand<3>(w0, w1, w2, mask, magic), acc);
                 const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
                 const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
-                const float z = f16_bits_to_f32((uint16_t)(szw >> 16));
+                float z = f16_bits_to_f32((uint16_t)(szw >> 16));
+                if (MT == 1) z += 8.0f;            // the codes enter the MFMA as 8 + q
 #pragma unroll
                 for (int i = 0; i < Acc<MT>::n; ++i) out[rt][i] = fmaf(s, fmaf(-z, cx[u][i], acc[i]), out[rt][i]);
             }
@@ -348,9 +407,6 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
 //        the group, from the prologue), gathers sum (8 + q) x, and y += s * (acc - z * Xp).
 //   VQ:  the codebook of the current block sits in a wavefront-private LDS region; each pair of
 //        weights is one ds_read_b32 gather feeding one dot2.
-__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {   // two fp16 pairs, scalars in
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
-}
 __device__ __forceinline__ float dot8(const uint4_t b, const half8_t xa, float acc) {
     // (element-wise bit_cast of a vector member miscompiles with this toolchain: go through scalars)
     const uint4_t xv = __builtin_bit_cast(uint4_t, xa);
@@ -495,8 +551,8 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     const int M = a.M;
     const bool xbf16 = a.xdt == DT_BF16;
 
-    if (mt.fmt == FMT_SQ3) {
-        // Prologue: X[g][m] = sum of the activations of group g (as the fp16 values the MFMA
+    if (MT != 1 && mt.fmt == FMT_SQ3) {
+        // Prologue (batch > 1): X[g][m] = sum of the activations of group g (as the fp16 values the MFMA
         // will see), and -8 X, for every group of the matrix; wavefronts take groups round-robin.
         const int G = mt.K / kGroup;
         for (int g = wave; g < G; g += 4)

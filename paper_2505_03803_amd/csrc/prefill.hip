@@ -52,25 +52,14 @@ struct PfArgs {
 #define RWKVQ_WAIT_VM0_LGKM0() __builtin_amdgcn_s_waitcnt(0x0070)   /* vmcnt(0) lgkmcnt(0) */
 // Publish LDS writes (ds_write and load-unit copies) to the workgroup: the caller has waited for
 // its own writes; the barrier orders them against the other wavefronts' reads.
-#ifndef RWKVQ_EXP_PF
-#define RWKVQ_EXP_PF 0      /* experiment builds only: 1 no x copy, 2 no unpack, 4 no MFMA, 8 no barrier */
-#endif
-#if RWKVQ_EXP_PF & 8
-#define RWKVQ_BARRIER() asm volatile("" ::: "memory")
-#else
 #define RWKVQ_BARRIER() asm volatile("s_barrier" ::: "memory")
-#endif
 
 template <bool BF16> struct Elem;
 template <> struct Elem<true> {
     // accumulate in place; the "a" constraint pins the accumulator to the AGPR half of the
     // register file (left to itself the allocator starts it in VGPRs and shuffles it all loop long)
     static __device__ __forceinline__ void mfma(uint4_t a, uint4_t b, float4_t& c) {
-#if RWKVQ_EXP_PF & 4
-        asm volatile("v_accvgpr_write_b32 %0, %1" : "+a"(c) : "v"(a.x ^ b.x));
-#else
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-#endif
     }
     static __device__ __forceinline__ uint32_t pack(float lo, float hi) {   // v_cvt_pk_bf16_f32
         typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
@@ -180,10 +169,6 @@ __device__ __forceinline__ int tile_off(int row, int c) { return row * kRowBytes
 // Row tiles I0 .. I1-1 of the thread's four (so that the work can be spread over a k-step).
 template <bool BF16, int FMT, int KQ, int I0 = 0, int I1 = 4>
 __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const uint32_t* cb8, int wave, int lane) {
-#if RWKVQ_EXP_PF & 2
-    if (I0 == 0) *(uint4_t*)(wt + 16 * lane) = r.a[0] ^ r.a[1] ^ r.a[2] ^ r.a[3];
-    return;
-#endif
     constexpr int u = KQ >> 1, t0 = 2 * (KQ & 1);
     const int row0 = 64 * wave + (lane & 15), kg = lane >> 4;
     // rows row0 + 16 i share row & 7, so the two chunk offsets are the same for all four
@@ -225,9 +210,6 @@ __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const ui
 // xoff[i] is the lane's byte offset (row * K * 2 + chunk * 16) from the tile's first row, computed
 // once; xk = activations of the tile's first row at column k0 (uniform).
 __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff)[8], char* xt, int wave) {
-#if RWKVQ_EXP_PF & 1
-    return;
-#endif
 #pragma unroll
     for (int i = 0; i < 8; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xk + xoff[i]),
@@ -264,15 +246,9 @@ __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm,
             b1[2 * (f - 4)] = *(const uint4_t*)(wb1 + 16 * (2 * (f - 4)) * kRowBytes);
             b1[2 * (f - 4) + 1] = *(const uint4_t*)(wb1 + 16 * (2 * (f - 4) + 1) * kRowBytes);
         }
-#if RWKVQ_EXP_PF & 16
-        const uint4_t af = {0x3c003c00u + f, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-#pragma unroll
-        for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(af, af, acc[f & 7][ni]);
-#else
         const uint4_t af = a[f % (kAhead + 1)];
 #pragma unroll
         for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(f < 8 ? b[ni] : b1[ni], af, acc[f & 7][ni]);
-#endif
     }
 }
 
