@@ -439,17 +439,47 @@ __device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_
     return v;
 }
 
+// acc += w . x, where x is the fp16 pair that lane N of the 16-lane row holds in xp (DPP
+// row_newbcast): the sixteen rows' lanes of a column group all multiply by the same activations,
+// which therefore need neither LDS nor a copy per lane.
+template <int N>
+__device__ __forceinline__ float dot2_row_bcast(float acc, uint32_t xp, uint32_t w) {
+    asm("v_dot2c_f32_f16_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xp), "v"(w), "n"(N));
+    return acc;
+}
+template <int T>
+__device__ __forceinline__ float dot8_row_bcast(float acc, uint32_t xp, const uint4_t b) {
+    const uint32_t b0 = b.x, b1 = b.y, b2 = b.z, b3 = b.w;
+    acc = dot2_row_bcast<4 * T + 0>(acc, xp, b0);
+    acc = dot2_row_bcast<4 * T + 1>(acc, xp, b1);
+    acc = dot2_row_bcast<4 * T + 2>(acc, xp, b2);
+    acc = dot2_row_bcast<4 * T + 3>(acc, xp, b3);
+    return acc;
+}
+
+// Activations of a tile for the row-broadcast dot products: lane (kg, i) holds, for unit u, the
+// pair of columns 128 u + 32 (i / 4) + 8 kg + 2 (i % 4) + {0, 1}, i.e. pair i of the sixteen
+// that the lanes of column group kg multiply in that unit, in MFMA-step order.
+struct XPairs { uint32_t p[2]; };
+__device__ __forceinline__ void xpairs_load(XPairs& r, const uint16_t* x, int T, int lane) {
+    const int i = lane & 15, kg = lane >> 4;
+    const uint16_t* xt = x + 256 * T + 32 * (i >> 2) + 8 * kg + 2 * (i & 3);
+    r.p[0] = *(const uint32_t*)xt;
+    r.p[1] = *(const uint32_t*)(xt + 128);
+}
+
+struct Vq6M1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XPairs x; };
+
 template <int DEPTH>
-__device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                           float (&out)[kRT]) {
+__device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     const int KT = mt.K >> 8, lane = wp.lane;
     const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
     const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
-    const half_t* xrow = xs + 8 * (lane >> 4);
     const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
     uint32_t m;
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
-    auto load = [&](Vq6Regs<1>& r, int T) {
+    float acc1 = 0.f;                      // second accumulation chain, folded in at the end
+    auto load = [&](Vq6M1Regs& r, int T) {
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 384;
@@ -457,32 +487,43 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
             r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
         }
         r.cb = (cbs + (size_t)T * 64)[lane];
-        x_load<1>(r.x, (const uint16_t*)mt.x, 1, mt.K, T, lane);
+        xpairs_load(r.x, (const uint16_t*)mt.x, T, lane);
     };
-    auto compute = [&](const Vq6Regs<1>& r, int) {
+    auto compute = [&](const Vq6M1Regs& r, int) {
         wave_lds_sync();
-        x_store<1>(r.x, xs, lane, wp.xbf16);
         cb_lds[lane] = r.cb;
         wave_lds_sync();
-        half8_t xa[2][4];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+        uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
+        if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
+        // a DPP read needs two wait states after a vector-ALU write of the register
+        asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));
+        // All sixteen gathers of a unit are issued before its dot products, and the second
+        // unit's before the first unit's dot products, so the LDS latency is paid once per tile.
+        static_assert(kRT == 1, "one row tile per wavefront");
+        uint4_t g[2][4];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
-                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
-                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
-                out[rt] = dot8(vq6_gather4<0>(w0, w1, w2, m, base), xa[u][0], out[rt]);
-                out[rt] = dot8(vq6_gather4<1>(w0, w1, w2, m, base), xa[u][1], out[rt]);
-                out[rt] = dot8(vq6_gather4<2>(w0, w1, w2, m, base), xa[u][2], out[rt]);
-                out[rt] = dot8(vq6_gather4<3>(w0, w1, w2, m, base), xa[u][3], out[rt]);
-            }
+            const uint32_t w0 = u == 0 ? r.a[0].x : r.a[0].w, w1 = u == 0 ? r.a[0].y : r.b[0].x,
+                           w2 = u == 0 ? r.a[0].z : r.b[0].y;
+            g[u][0] = vq6_gather4<0>(w0, w1, w2, m, base);
+            g[u][1] = vq6_gather4<1>(w0, w1, w2, m, base);
+            g[u][2] = vq6_gather4<2>(w0, w1, w2, m, base);
+            g[u][3] = vq6_gather4<3>(w0, w1, w2, m, base);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // two accumulation chains (one per unit), interleaved, so that a dot product never waits
+        // for the one issued just before it
+        acc1 = dot8_row_bcast<0>(acc1, x1, g[1][0]);
+        out[0] = dot8_row_bcast<0>(out[0], x0, g[0][0]);
+        acc1 = dot8_row_bcast<1>(acc1, x1, g[1][1]);
+        out[0] = dot8_row_bcast<1>(out[0], x0, g[0][1]);
+        acc1 = dot8_row_bcast<2>(acc1, x1, g[1][2]);
+        out[0] = dot8_row_bcast<2>(out[0], x0, g[0][2]);
+        acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
+        out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
     };
-    tile_pipeline<DEPTH, Vq6Regs<1>>(KT, load, compute);
+    tile_pipeline<DEPTH, Vq6M1Regs>(KT, load, compute);
+    out[0] += acc1;
 }
 
 template <int DEPTH>
@@ -577,7 +618,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
         float part[kRT];
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) part[rt] = 0.f;
-        if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH>(mt, wp, xs_all[wave], cb_all[wave], part);
+        if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH>(mt, wp, cb_all[wave], part);
         else run_vq8_m1<DEPTH>(mt, wp, xs_all[wave], cb_all[wave], part);
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
