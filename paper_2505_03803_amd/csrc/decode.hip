@@ -157,24 +157,6 @@ __device__ __forceinline__ float dpp_add(float v) {
     return v + __builtin_bit_cast(float, o);
 }
 
-// Sums of the two 128-column groups of a 256-column activation tile held four columns per lane
-// (lanes 0-31: group 0, lanes 32-63: group 1), as wavefront-uniform values.  Lane-crossing adds
-// stay inside the vector ALU: two quad permutes and two mirrors give every lane the sum of its
-// row of 16, a row broadcast adds the row below to rows 1 and 3.
-__device__ __forceinline__ void tile_group_sums(uint2_t x, float& X0, float& X1) {
-    const uint32_t ones = 0x3C003C00u;
-    const uint32_t lo = x.x, hi = x.y;   // scalars first: a bit_cast of a vector member goes wrong
-    float v = dot2(lo, ones, 0.f);
-    v = dot2(hi, ones, v);
-    v = dpp_add<0xB1>(v);            // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E>(v);            // quad_perm [2,3,0,1]
-    v = dpp_add<0x141>(v);           // row_half_mirror
-    v = dpp_add<0x140>(v);           // row_mirror
-    v = dpp_add<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
-    X0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-    X1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-}
-
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -269,24 +251,11 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
         // All LDS reads of the tile are issued first; their latency is covered by the unpack work.
         half8_t xa[2][4];
         float4_t c8[2], cx[2];
-        if (MT == 1) {
-            // batch 1: the group sums come from the tile's own activations (as the fp16 values
-            // the MFMA sees); the constant 8 of the codes is folded into the zero point below
-            uint2_t xv = r.x.v[0];
-            if (wp.xbf16) { xv.x = bf16x2_to_f16x2(xv.x); xv.y = bf16x2_to_f16x2(xv.y); }
-            float X0, X1;
-            tile_group_sums(xv, X0, X1);
-            c8[0] = c8[1] = float4_t{0, 0, 0, 0};
-            cx[0] = float4_t{X0, 0, 0, 0};
-            cx[1] = float4_t{X1, 0, 0, 0};
-        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int g = 2 * T + u;
-            if (MT != 1) {
-                c8[u] = *(const float4_t*)(xsum8 + g * MT + mrow);
-                cx[u] = *(const float4_t*)(xsumX + g * MT + mrow);
-            }
+            c8[u] = *(const float4_t*)(xsum8 + g * MT + mrow);
+            cx[u] = *(const float4_t*)(xsumX + g * MT + mrow);
 #pragma unroll
             for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
         }
@@ -304,8 +273,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
                 acc = RWKVQ_MFMA(xa[u][3], sq_operand<3>(w0, w1, w2, mask, magic), acc);
                 const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
                 const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
-                float z = f16_bits_to_f32((uint16_t)(szw >> 16));
-                if (MT == 1) z += 8.0f;            // the codes enter the MFMA as 8 + q
+                const float z = f16_bits_to_f32((uint16_t)(szw >> 16));
 #pragma unroll
                 for (int i = 0; i < Acc<MT>::n; ++i) out[rt][i] = fmaf(s, fmaf(-z, cx[u][i], acc[i]), out[rt][i]);
             }
@@ -400,23 +368,15 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
 // Batch 1 (GEMV proper).  Same streaming structure and native layout, but the contraction is
 // done by the vector ALU (v_dot2c_f32_f16: two multiply-adds per lane, binary32 accumulate):
 // with a single activation row fifteen sixteenths of every MFMA would be spent on padding, and
-// on this part the matrix cores and the vector ALU of a SIMD do not run concurrently, so the
-// padded MFMA costs both issue time and power.  Lane (r, kg) accumulates the part of row r's dot
-// product that falls on its own columns; the four kg lanes of a row are summed at the end.
-//   SQ:  per group, acc starts at -8 * Xp (Xp = sum of the activations on this lane's columns of
-//        the group, from the prologue), gathers sum (8 + q) x, and y += s * (acc - z * Xp).
+// the padded MFMA costs the same issue time as the dot products.  Lane (r, kg) accumulates the part
+// of row r's dot product that falls on its own columns; the four kg lanes of a row are summed at
+// the end.  The activations are not staged in LDS: lane (kg, i) loads pair i of the sixteen
+// column pairs that column group kg multiplies in a unit, and each dot product names the lane of
+// its row that holds its pair (DPP row broadcast).
+//   SQ:  the codes are multiplied in place as fp16 subnormals; per group
+//        y += s * (sum q x - z * Xp), Xp = the sum of the lane's own activations of the group.
 //   VQ:  the codebook of the current block sits in a wavefront-private LDS region; each pair of
 //        weights is one ds_read_b32 gather feeding one dot2.
-__device__ __forceinline__ float dot8(const uint4_t b, const half8_t xa, float acc) {
-    // (element-wise bit_cast of a vector member miscompiles with this toolchain: go through scalars)
-    const uint4_t xv = __builtin_bit_cast(uint4_t, xa);
-    const uint32_t b0 = b.x, b1 = b.y, b2 = b.z, b3 = b.w, x0 = xv.x, x1 = xv.y, x2 = xv.z, x3 = xv.w;
-    acc = dot2(b0, x0, acc);
-    acc = dot2(b1, x1, acc);
-    acc = dot2(b2, x2, acc);
-    acc = dot2(b3, x3, acc);
-    return acc;
-}
 
 template <int P>
 __device__ __forceinline__ uint32_t vq6_lds_addr(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t m, uint32_t base) {
@@ -447,6 +407,12 @@ __device__ __forceinline__ float dot2_row_bcast(float acc, uint32_t xp, uint32_t
     asm("v_dot2c_f32_f16_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(xp), "v"(w), "n"(N));
     return acc;
 }
+// The dot products above are opaque to the compiler's hazard checks.  On this ISA the result of
+// a dot instruction may be read (or overwritten) by a different vector-ALU instruction only
+// three wait states later; accumulating dot products of the same kind need none.  Call this
+// between the last dot product into an accumulator and any other use of it.
+#define RWKVQ_DOT_RESULT_FENCE(...) asm volatile("s_nop 2" : __VA_ARGS__)
+
 template <int T>
 __device__ __forceinline__ float dot8_row_bcast(float acc, uint32_t xp, const uint4_t b) {
     const uint32_t b0 = b.x, b1 = b.y, b2 = b.z, b3 = b.w;
@@ -523,49 +489,134 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
         out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
     };
     tile_pipeline<DEPTH, Vq6M1Regs>(KT, load, compute);
+    RWKVQ_DOT_RESULT_FENCE("+v"(out[0]), "+v"(acc1));
     out[0] += acc1;
 }
 
+// Batch-1 SQ on the vector ALU.  The codes are multiplied as they are, with no 8 + q pattern: a
+// 3-bit code left at mantissa bits b..b+2 of an fp16 half is the subnormal q * 2^(b-24), which
+// v_dot2c_f32_f16 multiplies exactly.  A pair of codes therefore costs one AND (codes at bits 1, 4
+// or 7 of the halves) or a share of one shift by 9 that brings the codes at bits 10 and 13 down
+// to bits 1 and 4.  Products of different bit positions go to different accumulators (acc[0..2] for
+// bits 1, 4, 7), which are combined with exact powers of two once per group.
+struct SqM1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XPairs x; };
+
+template <int P>
+__device__ __forceinline__ void sq_dot_pair(float (&acc)[3], uint32_t xp, uint32_t w0, uint32_t w1, uint32_t w2,
+                                            uint32_t s0, uint32_t s1, uint32_t s2) {
+    // s0..s2 = w0..w2 >> 9
+    if constexpr (P < 15) {
+        constexpr int p = P % 5;
+        const uint32_t w = (P / 5 == 0) ? w0 : (P / 5 == 1) ? w1 : w2;
+        const uint32_t sh = (P / 5 == 0) ? s0 : (P / 5 == 1) ? s1 : s2;
+        if constexpr (p == 0) acc[0] = dot2_row_bcast<P>(acc[0], xp, w & 0x000E000Eu);
+        else if constexpr (p == 1) acc[1] = dot2_row_bcast<P>(acc[1], xp, w & 0x00700070u);
+        else if constexpr (p == 2) acc[2] = dot2_row_bcast<P>(acc[2], xp, w & 0x03800380u);
+        else if constexpr (p == 3) acc[0] = dot2_row_bcast<P>(acc[0], xp, sh & 0x000E000Eu);
+        else acc[1] = dot2_row_bcast<P>(acc[1], xp, sh & 0x00700070u);
+    } else {
+        // bit b of the pair's two codes sits at bits 0 and 16 of word b; assembled at bits 1..3
+        const uint32_t t = (((w2 & 0x00010001u) << 1) | (w1 & 0x00010001u)) << 1 | (w0 & 0x00010001u);
+        acc[0] = dot2_row_bcast<15>(acc[0], xp, t << 1);
+    }
+}
+
+template <int... P>
+__device__ __forceinline__ void sq_dot_pairs(float (&acc)[3], uint32_t xp, uint32_t w0, uint32_t w1, uint32_t w2,
+                                             uint32_t s0, uint32_t s1, uint32_t s2) {
+    (sq_dot_pair<P>(acc, xp, w0, w1, w2, s0, s1, s2), ...);
+}
+
 template <int DEPTH>
-__device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                           float (&out)[kRT]) {
+__device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp, float (&out)[kRT]) {
+    static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 512, mt.codes + (size_t)wp.R[1] * KT * 512};
-    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
-    const half_t* xrow = xs + 8 * (lane >> 4);
-    auto load = [&](Vq8Regs<1>& r, int T) {
-#pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 512;
-            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
-            r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
-        }
-        r.cb = (cbs + (size_t)T * 64)[lane];
-        x_load<1>(r.x, (const uint16_t*)mt.x, 1, mt.K, T, lane);
+    const uint32_t* codes = mt.codes + (size_t)wp.R[0] * KT * 384;
+    const uint2_t* sz = (const uint2_t*)mt.aux + (size_t)wp.R[0] * KT * 16;
+    auto load = [&](SqM1Regs& r, int T) {
+        const uint32_t* t = codes + (size_t)T * 384;
+        r.a[0] = *(const uint4_t*)(t + 4 * lane);
+        r.b[0] = *(const uint2_t*)(t + 256 + 2 * lane);
+        r.sz[0] = (sz + (size_t)T * 16)[lane & 15];
+        xpairs_load(r.x, (const uint16_t*)mt.x, T, lane);
     };
-    auto compute = [&](const Vq8Regs<1>& r, int) {
-        wave_lds_sync();
-        x_store<1>(r.x, xs, lane, wp.xbf16);
-        *(uint4_t*)(cb_lds + 4 * lane) = r.cb;
-        wave_lds_sync();
-        half8_t xa[2][4];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+    auto compute = [&](const SqM1Regs& r, int) {
+        uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
+        if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
+        asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));     // vector-ALU write -> DPP read
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
-                const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
-                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.x, cb_lds)), xa[u][0], out[rt]);
-                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.y, cb_lds)), xa[u][1], out[rt]);
-                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.z, cb_lds)), xa[u][2], out[rt]);
-                out[rt] = dot8(__builtin_bit_cast(uint4_t, vq8_operand(w.w, cb_lds)), xa[u][3], out[rt]);
-            }
+            const uint32_t xp = u == 0 ? x0 : x1;
+            const uint32_t w0 = u == 0 ? r.a[0].x : r.a[0].w, w1 = u == 0 ? r.a[0].y : r.b[0].x,
+                           w2 = u == 0 ? r.a[0].z : r.b[0].y;
+            // Xp = 2^-17 times the sum of the activations this lane's column group multiplies in the
+            // unit: the sixteen lanes of the row hold one pair each
+            float Xp = dot2(xp, 0x00800080u, 0.f);         // 2^-17 (x_lo + x_hi): fp16 0x0080 = 2^-17
+            Xp = dpp_add<0xB1>(Xp);
+            Xp = dpp_add<0x4E>(Xp);
+            Xp = dpp_add<0x141>(Xp);
+            Xp = dpp_add<0x140>(Xp);
+            float acc[3] = {0.f, 0.f, 0.f};
+            sq_dot_pairs<0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15>(acc, xp, w0, w1, w2, w0 >> 9, w1 >> 9, w2 >> 9);
+            RWKVQ_DOT_RESULT_FENCE("+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]));
+            // sum x q = 2^17 S with S = 64 acc0 + 8 acc1 + acc2; Xp carries the same 2^-17, and so
+            // does the running output, which is scaled back once at the end
+            const float S = fmaf(acc[0], 64.f, fmaf(acc[1], 8.f, acc[2]));
+            const uint32_t szw = u == 0 ? r.sz[0].x : r.sz[0].y;
+            const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
+            const float z = f16_bits_to_f32((uint16_t)(szw >> 16));
+            out[0] = fmaf(s, fmaf(-z, Xp, S), out[0]);
         }
     };
-    tile_pipeline<DEPTH, Vq8Regs<1>>(KT, load, compute);
+    tile_pipeline<DEPTH, SqM1Regs>(KT, load, compute);
+    out[0] *= 131072.f;
+}
+
+struct Vq8M1Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XPairs x; };
+
+template <int DEPTH>
+__device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
+    static_assert(kRT == 1, "one row tile per wavefront");
+    const int KT = mt.K >> 8, lane = wp.lane;
+    const uint32_t* codes = mt.codes + (size_t)wp.R[0] * KT * 512;
+    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
+    float acc1 = 0.f;
+    auto load = [&](Vq8M1Regs& r, int T) {
+        const uint32_t* t = codes + (size_t)T * 512;
+        r.a[0] = *(const uint4_t*)(t + 4 * lane);
+        r.b[0] = *(const uint4_t*)(t + 256 + 4 * lane);
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        xpairs_load(r.x, (const uint16_t*)mt.x, T, lane);
+    };
+    auto compute = [&](const Vq8M1Regs& r, int) {
+        wave_lds_sync();
+        *(uint4_t*)(cb_lds + 4 * lane) = r.cb;
+        wave_lds_sync();
+        uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
+        if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
+        asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));     // vector-ALU write -> DPP read
+        uint4_t g[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint4_t w = u == 0 ? r.a[0] : r.b[0];
+            g[u][0] = __builtin_bit_cast(uint4_t, vq8_operand(w.x, cb_lds));
+            g[u][1] = __builtin_bit_cast(uint4_t, vq8_operand(w.y, cb_lds));
+            g[u][2] = __builtin_bit_cast(uint4_t, vq8_operand(w.z, cb_lds));
+            g[u][3] = __builtin_bit_cast(uint4_t, vq8_operand(w.w, cb_lds));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        acc1 = dot8_row_bcast<0>(acc1, x1, g[1][0]);
+        out[0] = dot8_row_bcast<0>(out[0], x0, g[0][0]);
+        acc1 = dot8_row_bcast<1>(acc1, x1, g[1][1]);
+        out[0] = dot8_row_bcast<1>(out[0], x0, g[0][1]);
+        acc1 = dot8_row_bcast<2>(acc1, x1, g[1][2]);
+        out[0] = dot8_row_bcast<2>(out[0], x0, g[0][2]);
+        acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
+        out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
+    };
+    tile_pipeline<DEPTH, Vq8M1Regs>(KT, load, compute);
+    RWKVQ_DOT_RESULT_FENCE("+v"(out[0]), "+v"(acc1));
+    out[0] += acc1;
 }
 
 // MT = number of activation rows carried (1, 4 or 16 >= M).  D layout of the MFMA: lane holds
@@ -593,7 +644,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     const bool xbf16 = a.xdt == DT_BF16;
 
     if (MT != 1 && mt.fmt == FMT_SQ3) {
-        // Prologue (batch > 1): X[g][m] = sum of the activations of group g (as the fp16 values the MFMA
+        // Prologue: X[g][m] = sum of the activations of group g (as the fp16 values the MFMA
         // will see), and -8 X, for every group of the matrix; wavefronts take groups round-robin.
         const int G = mt.K / kGroup;
         for (int g = wave; g < G; g += 4)
@@ -614,12 +665,13 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
     wp.M = M; wp.lane = lane; wp.xbf16 = xbf16;
 
-    if (MT == 1 && mt.fmt != FMT_SQ3) {
+    if constexpr (MT == 1) {
         float part[kRT];
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) part[rt] = 0.f;
-        if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH>(mt, wp, cb_all[wave], part);
-        else run_vq8_m1<DEPTH>(mt, wp, xs_all[wave], cb_all[wave], part);
+        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH>(mt, wp, part);
+        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH>(mt, wp, cb_all[wave], part);
+        else run_vq8_m1<DEPTH>(mt, wp, cb_all[wave], part);
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
             if (rt == 1 && wp.R[1] == wp.R[0]) break;
@@ -629,7 +681,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
             if (lane < 16) store_from_f32(mt.y, (size_t)16 * wp.R[rt] + lane, a.ydt, v);
         }
         return;
-    }
+    } else {
 
     float4_t out[kRT];
 #pragma unroll
@@ -654,6 +706,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
                 if (i < M) store_from_f32(mt.y, (size_t)i * mt.N + n, a.ydt, out[rt][i]);
         }
     }
+    }   // MT > 1
 }
 
 hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
