@@ -26,6 +26,7 @@
 //   * Activations are staged per wavefront and per column tile in LDS (fp16; bf16 inputs are
 //     converted, exact for |x| in [2^-14, 65504]) and read back in A-operand order.
 #include "common.h"
+#include <algorithm>
 
 namespace rwkvq {
 
@@ -713,9 +714,15 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
     for (int base = 0; base < n_mats; base += kMaxGroupMats) {
         DecodeArgs a;
         int cnt = n_mats - base < kMaxGroupMats ? n_mats - base : kMaxGroupMats;
+        // Workgroups are handed out in index order and a workgroup's running time grows with K:
+        // the matrices of a launch go longest rows first, so that the launch does not end on a
+        // few long workgroups (the outputs are independent, the order is free).
+        int order[kMaxGroupMats];
+        for (int i = 0; i < cnt; ++i) order[i] = base + i;
+        std::stable_sort(order, order + cnt, [&](int p, int q) { return mats[p].K > mats[q].K; });
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
-            const MatDev& m = mats[base + i];
+            const MatDev& m = mats[order[i]];
             wgs += (m.N + kWgRows - 1) / kWgRows;
             a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, 0};
             a.wg_end[i] = wgs;

@@ -102,17 +102,36 @@ def test_reference_kernel_canonical(fmt, N, K, M):
 
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
 def test_one_hot_returns_weight_column(fmt):
+    """Batch 1 with a one-hot activation vector returns one column of Deq(W), bit for bit (every
+    product but one is an exact zero), for every column of two tiles: each column goes through its
+    own unpack position and its own lane of the activation broadcast."""
     mat = make(fmt, 256, 512, 6)
     w = orc.dequant(mat)
     dm = B.upload(mat, native=True)
-    for k in (0, 7, 127, 128, 255, 256, 511):
+    for k in range(512):
         x = np.zeros((1, 512), np.float32)
         x[0, k] = 1.0
         y = G.gpu_gemm(dm, synth.f32_to_f16_bits(x), "f16")[0]
-        if fmt == "sq":       # (8 + q) - (z + 8) rounds once more than q - z when z is tiny
-            assert np.allclose(y, w[:, k], rtol=1e-6, atol=0)
+        assert np.array_equal(y, w[:, k].astype(np.float64)), f"column {k}"
+
+
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+def test_one_hot_batch4(fmt):
+    """The same through the matrix-core path (batch 4): row m selects column 37 m + 3.  The SQ
+    codes enter the MFMA as 8 + q, so (8 + q) - (z + 8) can round once more than q - z."""
+    mat = make(fmt, 256, 512, 6)
+    w = orc.dequant(mat)
+    dm = B.upload(mat, native=True)
+    x = np.zeros((4, 512), np.float32)
+    cols = [37 * m + 3 for m in range(4)]
+    for m, k in enumerate(cols):
+        x[m, k] = 1.0
+    y = G.gpu_gemm(dm, synth.f32_to_f16_bits(x), "f16")
+    for m, k in enumerate(cols):
+        if fmt == "sq":
+            assert np.allclose(y[m], w[:, k], rtol=1e-6, atol=0)
         else:
-            assert np.array_equal(y, w[:, k].astype(np.float64))
+            assert np.array_equal(y[m], w[:, k].astype(np.float64))
 
 
 @pytest.mark.parametrize("ydt", ["f16", "bf16"])
