@@ -104,14 +104,43 @@ __device__ __forceinline__ uint32_t vq6_byteaddr(uint32_t w0, uint32_t w1, uint3
     }
 }
 
+// The two weights of pair P of a native SQ unit, dequantised as Sec. 2.2 Eq. "SQ" prescribes
+// (q - z rounded, times s rounded).  The codes are not extracted: masked in place, a 3-bit code at
+// mantissa bits b..b+2 of an fp16 half is the subnormal q * 2^(b-24); a mixed-precision FMA reads
+// the half, multiplies by 2^(24-b) (exact) and subtracts z with the single rounding of q - z.  The
+// codes at bits 10 and 13 of the halves come down to bits 1 and 4 with one shift by 9 per word.
+template <int P>
+__device__ __forceinline__ void sq_pair_deq(uint32_t w0, uint32_t w1, uint32_t w2, float s, float z, float& lo,
+                                            float& hi) {
+    uint32_t m;
+    float c;
+    if constexpr (P < 15) {
+        constexpr int p = P % 5;
+        const uint32_t w = (P / 5 == 0) ? w0 : (P / 5 == 1) ? w1 : w2;
+        if constexpr (p == 0) { m = w & 0x000E000Eu; c = 8388608.f; }
+        else if constexpr (p == 1) { m = w & 0x00700070u; c = 1048576.f; }
+        else if constexpr (p == 2) { m = w & 0x03800380u; c = 131072.f; }
+        else if constexpr (p == 3) { m = (w >> 9) & 0x000E000Eu; c = 8388608.f; }
+        else { m = (w >> 9) & 0x00700070u; c = 1048576.f; }
+    } else {
+        // bit b of the pair's two codes sits at bits 0 and 16 of word b
+        m = (w0 & 0x00010001u) | ((w1 & 0x00010001u) << 1) | ((w2 & 0x00010001u) << 2);
+        c = 16777216.f;
+    }
+    const half2_t h = __builtin_bit_cast(half2_t, m);
+    lo = __fmul_rn(fmaf((float)h.x, c, -z), s);
+    hi = __fmul_rn(fmaf((float)h.y, c, -z), s);
+}
+
 // Eight consecutive-k weights (step T4 of a unit) of one lane, as four packed pairs.
 template <bool BF16, int T4>
 __device__ __forceinline__ uint4_t sq_chunk(uint32_t w0, uint32_t w1, uint32_t w2, float s, float z) {
     uint4_t o;
-    o.x = Elem<BF16>::pack(sq_deq(sq_code<8 * T4 + 0>(w0, w1, w2), s, z), sq_deq(sq_code<8 * T4 + 1>(w0, w1, w2), s, z));
-    o.y = Elem<BF16>::pack(sq_deq(sq_code<8 * T4 + 2>(w0, w1, w2), s, z), sq_deq(sq_code<8 * T4 + 3>(w0, w1, w2), s, z));
-    o.z = Elem<BF16>::pack(sq_deq(sq_code<8 * T4 + 4>(w0, w1, w2), s, z), sq_deq(sq_code<8 * T4 + 5>(w0, w1, w2), s, z));
-    o.w = Elem<BF16>::pack(sq_deq(sq_code<8 * T4 + 6>(w0, w1, w2), s, z), sq_deq(sq_code<8 * T4 + 7>(w0, w1, w2), s, z));
+    float a, b;
+    sq_pair_deq<4 * T4 + 0>(w0, w1, w2, s, z, a, b); o.x = Elem<BF16>::pack(a, b);
+    sq_pair_deq<4 * T4 + 1>(w0, w1, w2, s, z, a, b); o.y = Elem<BF16>::pack(a, b);
+    sq_pair_deq<4 * T4 + 2>(w0, w1, w2, s, z, a, b); o.z = Elem<BF16>::pack(a, b);
+    sq_pair_deq<4 * T4 + 3>(w0, w1, w2, s, z, a, b); o.w = Elem<BF16>::pack(a, b);
     return o;
 }
 template <int T4>
