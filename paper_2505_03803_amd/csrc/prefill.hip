@@ -33,7 +33,11 @@ constexpr int BM = 256, BN = 256;              // block tile; the k-step is 64 c
 constexpr int kRowBytes = 128;                 // 64 k * 2 B
 constexpr int kTileBytes = 256 * kRowBytes;    // one operand tile (32 KB)
 constexpr int kCb8Bytes = 1024;                // converted 8-bit-index codebook
-constexpr int kPfLds = 4 * kTileBytes + 2 * kCb8Bytes;
+// Activation tiles in LDS: three (the copy of a k-step is issued two k-steps ahead of its use, so
+// that its round trip to the cache hides behind a whole k-step of MFMAs) except with 8-bit VQ,
+// whose converted codebooks take the room of the third.
+constexpr int x_buffers(int fmt) { return fmt == FMT_VQ8 ? 2 : 3; }
+constexpr int pf_lds_bytes(int fmt) { return (2 + x_buffers(fmt)) * kTileBytes + (fmt == FMT_VQ8 ? 2 * kCb8Bytes : 0); }
 
 struct PfMat {
     const uint32_t* codes;
@@ -50,6 +54,7 @@ struct PfArgs {
 
 // s_waitcnt immediates (gfx9 encoding): only the named counter is waited for.
 #define RWKVQ_WAIT_VM0_LGKM0() __builtin_amdgcn_s_waitcnt(0x0070)   /* vmcnt(0) lgkmcnt(0) */
+#define RWKVQ_WAIT_VM8_LGKM0() __builtin_amdgcn_s_waitcnt(0x0078)   /* vmcnt(8) lgkmcnt(0) */
 // Publish LDS writes (ds_write and load-unit copies) to the workgroup: the caller has waited for
 // its own writes; the barrier orders them against the other wavefronts' reads.
 #define RWKVQ_BARRIER() asm volatile("s_barrier" ::: "memory")
@@ -296,11 +301,11 @@ __device__ __forceinline__ void cb8_store(const WRegs<FMT_VQ8>& r, uint32_t* cb8
 template <bool BF16, int FMT>
 __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    char* const xt0 = lds;
-    char* const xt1 = lds + kTileBytes;
-    char* const wt0 = lds + 2 * kTileBytes;
-    char* const wt1 = lds + 3 * kTileBytes;
-    uint32_t* const cb8base = (uint32_t*)(lds + 4 * kTileBytes);
+    constexpr int XB = x_buffers(FMT), LA = XB - 1;       // LA = k-steps between a copy and its use
+    char* const wt0 = lds;
+    char* const wt1 = lds + kTileBytes;
+    char* const xbase = lds + 2 * kTileBytes;
+    uint32_t* const cb8base = (uint32_t*)(lds + (2 + XB) * kTileBytes);
 #define CB8(i) (cb8base + ((i) & 1) * (kCb8Bytes / 4))
 
     const int wg = blockIdx.x;
@@ -339,10 +344,21 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = float4_t{0, 0, 0, 0};
 
-    // prologue: tile 0, k-step 0 into buffer 0
+    // The activation buffers form a ring (byte offsets from xbase): x0 holds the k-step being
+    // multiplied, x1 the next one, x2 (three buffers) the one after.  A k-step's copy is issued LA
+    // k-steps ahead; eight copy instructions per thread and k-step, so "all but the newest eight
+    // memory operations done" is the wait that lets the newest copy stay in flight.
+    int x0 = 0, x1 = kTileBytes, x2 = 2 * kTileBytes;
+    const int hmax = 4 * KT - 1;                           // last k-step
+    auto xk = [&](int h) { return xrow0 + (size_t)(h < hmax ? h : hmax) * kRowBytes; };
+    auto rotate = [&] { if (XB == 3) { const int t = x0; x0 = x1; x1 = x2; x2 = t; } else { const int t = x0; x0 = x1; x1 = t; } };
+    auto wait_step = [&] { if (LA == 2) RWKVQ_WAIT_VM8_LGKM0(); else RWKVQ_WAIT_VM0_LGKM0(); };
+
+    // prologue: packed words of tile 0, k-step 0 (and 1) of the activations, k-step 0 of W
     WRegs<FMT> wr;
     w_load<FMT>(wr, src, 0, lane);
-    x_tile_dma(xrow0, xoff, xt0, wave);
+    x_tile_dma(xk(0), xoff, xbase + x0, wave);
+    if (LA == 2) x_tile_dma(xk(1), xoff, xbase + x1, wave);
     if constexpr (FMT == FMT_VQ8) {
         cb8_store<BF16>(wr, CB8(0), wave, lane);
         RWKVQ_WAIT_VM0_LGKM0();
@@ -354,42 +370,49 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 
     for (int T = 0; T < KT; ++T) {
         const int Tn = T + 1 < KT ? T + 1 : T;
-        const char* xk = xrow0 + (size_t)T * 512;
-        // k-step 0 of the tile is in buffer 0; steps 1..3 come from the same packed words.
-        x_tile_dma(xk + 128, xoff, xt1, wave);
-        mma_step<BF16>(xt0, wt0, wm, wn, lane, acc,
+        const int g = 4 * T;                               // k-step index of the tile's first step
+        // k-step 0 of the tile is in W buffer 0; steps 1..3 come from the same packed words.
+        x_tile_dma(xk(g + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
+        mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc,
                        [&] { w_unpack<BF16, FMT, 1, 0, 2>(wr, wt1, CB8(T), wave, lane); },
                        [&] { w_unpack<BF16, FMT, 1, 2, 4>(wr, wt1, CB8(T), wave, lane); });
-        RWKVQ_WAIT_VM0_LGKM0();
+        wait_step();
         RWKVQ_BARRIER();
+        rotate();
 
-        x_tile_dma(xk + 256, xoff, xt0, wave);
-        mma_step<BF16>(xt1, wt1, wm, wn, lane, acc,
+        x_tile_dma(xk(g + 1 + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
+        mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc,
                        [&] { w_unpack<BF16, FMT, 2, 0, 2>(wr, wt0, CB8(T), wave, lane); },
                        [&] { w_unpack<BF16, FMT, 2, 2, 4>(wr, wt0, CB8(T), wave, lane); });
-        RWKVQ_WAIT_VM0_LGKM0();
+        wait_step();
         RWKVQ_BARRIER();
+        rotate();
 
-        x_tile_dma(xk + 384, xoff, xt1, wave);
-        mma_step<BF16>(xt0, wt0, wm, wn, lane, acc,
+        x_tile_dma(xk(g + 2 + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
+        mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc,
                        [&] { w_unpack<BF16, FMT, 3, 0, 2>(wr, wt1, CB8(T), wave, lane); },
                        [&] { w_unpack<BF16, FMT, 3, 2, 4>(wr, wt1, CB8(T), wave, lane); });
-        RWKVQ_WAIT_VM0_LGKM0();
+        wait_step();
         RWKVQ_BARRIER();
+        rotate();
 
-        // the packed words of this tile are spent: fetch the next tile's into the same registers;
-        // they have a whole MFMA step to arrive
+        // the packed words of this tile are spent: fetch the next tile's into the same registers
+        // (before the activation copy, so that waiting for them leaves the copy in flight); they
+        // have a whole MFMA step to arrive
         w_load<FMT>(wr, src, Tn, lane);
-        x_tile_dma(xrow0 + (size_t)Tn * 512, xoff, xt0, wave);
-        mma_step<BF16>(xt1, wt1, wm, wn, lane, acc, [] {}, [] {});
+        x_tile_dma(xk(g + 3 + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
+        mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc, [] {}, [] {});
         if constexpr (FMT == FMT_VQ8) {
             cb8_store<BF16>(wr, CB8(T + 1), wave, lane);
             RWKVQ_WAIT_VM0_LGKM0();
             RWKVQ_BARRIER();
+        } else {
+            wait_step();                                   // the packed words have landed
         }
         w_unpack<BF16, FMT, 0>(wr, wt0, CB8(T + 1), wave, lane);
-        RWKVQ_WAIT_VM0_LGKM0();
+        wait_step();
         RWKVQ_BARRIER();
+        rotate();
     }
 
     // The MFMAs are opaque to the compiler's hazard checks: let the last ones drain before the
@@ -427,11 +450,11 @@ static hipError_t launch_fmt(const PfArgs& a, int wgs, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<BF16, FMT>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kPfLds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, pf_lds_bytes(FMT));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_kernel<BF16, FMT>), dim3(wgs), dim3(256), kPfLds, s, a);
+    hipLaunchKernelGGL((prefill_kernel<BF16, FMT>), dim3(wgs), dim3(256), pf_lds_bytes(FMT), s, a);
     return hipGetLastError();
 }
 
