@@ -35,8 +35,8 @@ DECODE_KERNEL = "rwkvq::decode_kernel<1>"
 PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT>"   # bf16; one instantiation per weight format
 DECODE_MATS_PER_LAUNCH = 64
 # HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
-# scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic.txt.
-DECODE_TRAFFIC_BYTES_PER_LAUNCH = 704.0e6
+# scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic_config3.txt.
+DECODE_TRAFFIC_BYTES_PER_LAUNCH = 701.9e6
 
 
 def log(*a):
