@@ -6,7 +6,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, Structure, c_char_p, c_int, c_int32, c_void_p
+from ctypes import POINTER, Structure, c_char_p, c_double, c_int, c_int32, c_size_t, c_void_p
 from dataclasses import dataclass
 from typing import Optional, Sequence
 
@@ -20,7 +20,7 @@ DTYPES = {"f16": F16, "bf16": BF16, "f32": F32}
 
 EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq_prepack",
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
-           "rwkvq_linear_dispatch"]
+           "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy"]
 
 
 class rwkvq_matrix(Structure):
@@ -70,6 +70,11 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_linear_dispatch.restype = c_int
         L.rwkvq_linear_dispatch.argtypes = [POINTER(rwkvq_matrix), POINTER(c_void_p), POINTER(c_void_p),
                                             c_int, c_int, c_int, c_int, c_void_p]
+        L.rwkvq_proxy_workspace_bytes.restype = c_size_t
+        L.rwkvq_proxy_workspace_bytes.argtypes = []
+        L.rwkvq_proxy.restype = c_int
+        L.rwkvq_proxy.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_double, c_double, c_void_p,
+                                  c_void_p, c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -140,6 +145,16 @@ def rwkvq_vq_gemm(indices, codebooks, layout, x, y, M, N, K, vdim, kbits, block_
                   x_dtype, y_dtype, stream=None, check=True):
     st = lib().rwkvq_vq_gemm(_ptr(indices), _ptr(codebooks), layout, _ptr(x), _ptr(y), M, N, K, vdim,
                              kbits, block_rows, block_cols, x_dtype, y_dtype, _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_proxy_workspace_bytes() -> int:
+    return int(lib().rwkvq_proxy_workspace_bytes())
+
+
+def rwkvq_proxy(w, w_dtype, N, K, terms, tau_c, tau_f, workspace, proxies, phi, stream=None, check=True):
+    st = lib().rwkvq_proxy(_ptr(w), w_dtype, N, K, terms, tau_c, tau_f, _ptr(workspace), _ptr(proxies),
+                           _ptr(phi), _stream(stream))
     return _check(st) if check else st
 
 
@@ -242,3 +257,18 @@ def gemm(dm: DeviceMatrix, x, M: int, x_dtype: int, y_dtype: int = F32, stream=N
         rwkvq_vq_gemm(dm.codes, dm.codebooks, dm.layout, x, y, M, dm.N, dm.K, 2, dm.kbits, 256, 256,
                       x_dtype, y_dtype, stream)
     return y
+
+
+def proxy(w, w_dtype: int, terms: int = 5, tau_c: float = 1.5, tau_f: float = 50.0, workspace=None, stream=None):
+    """(P_c, P_f, phi) of a dense weight matrix through rwkvq_proxy; w is a 2-D int16 tensor of
+    fp16 / bf16 bit patterns on the GPU.  Synchronises to read the three numbers back."""
+    import torch
+    N, K = w.shape
+    if workspace is None:
+        workspace = torch.empty(rwkvq_proxy_workspace_bytes() // 4, dtype=torch.int32, device=w.device)
+    out = torch.empty(2, dtype=torch.float64, device=w.device)
+    flag = torch.empty(4, dtype=torch.int32, device=w.device)
+    rwkvq_proxy(w, w_dtype, N, K, terms, tau_c, tau_f, workspace, out, flag, stream)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    return float(o[0]), float(o[1]), int(flag[0].item())

@@ -181,4 +181,21 @@ int rwkvq_vq_gemm(const void* indices, const void* codebooks, int layout, const 
     return rwkvq_linear_dispatch(&m, &x, &y, 1, M, x_dtype, y_dtype, stream);
 }
 
+size_t rwkvq_proxy_workspace_bytes(void) { return 65536 * sizeof(uint32_t); }
+
+int rwkvq_proxy(const void* w, int w_dtype, int N, int K, int terms, double tau_c, double tau_f,
+                void* workspace, double* proxies, int32_t* phi, void* stream) {
+    if (!w || !workspace || !proxies || !phi) return RWKVQ_ERR_NULL;
+    if (w_dtype != RWKVQ_F16 && w_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    if (terms < 2 || terms > 8) return RWKVQ_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1) return RWKVQ_ERR_SHAPE;
+    const unsigned long long count = (unsigned long long)N * (unsigned long long)K;
+    if (count < 2ull || count > 0xFFFFFFFFull) return RWKVQ_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(workspace) || !aligned16(proxies) || ((uintptr_t)phi & 3u))
+        return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_proxy(w, w_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, count, terms, tau_c, tau_f,
+                                (uint32_t*)workspace, proxies, phi, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
 }  // extern "C"

@@ -104,3 +104,30 @@ def test_dispatch_rejects():
     d.kind = 3
     mats = (B.rwkvq_matrix * 1)(d)
     assert L.rwkvq_linear_dispatch(mats, xs, ys, 1, 1, B.F16, B.F32, None) == B.ERR_UNSUPPORTED
+
+
+def test_proxy_rejects():
+    L = B.lib()
+    assert L.rwkvq_proxy_workspace_bytes() == 65536 * 4
+    ok = (FAKE, B.BF16, 256, 256, 5, 1.5, 50.0, FAKE, FAKE, FAKE, None)
+
+    def call(**kw):
+        names = ["w", "dt", "N", "K", "terms", "tc", "tf", "ws", "out", "phi", "stream"]
+        args = list(ok)
+        for k, v in kw.items():
+            args[names.index(k)] = v
+        return L.rwkvq_proxy(*args)
+
+    assert call(w=None) == B.ERR_NULL
+    assert call(ws=None) == B.ERR_NULL
+    assert call(out=None) == B.ERR_NULL
+    assert call(phi=None) == B.ERR_NULL
+    assert call(dt=B.F32) == B.ERR_UNSUPPORTED
+    assert call(terms=1) == B.ERR_UNSUPPORTED
+    assert call(terms=9) == B.ERR_UNSUPPORTED
+    assert call(N=0) == B.ERR_SHAPE
+    assert call(N=1, K=1) == B.ERR_SHAPE                 # fewer than two weights: no interval
+    assert call(N=65536, K=65536) == B.ERR_SHAPE          # more than 2^32 - 1 weights
+    assert call(w=FAKE + 2) == B.ERR_ALIGN
+    assert call(ws=FAKE + 8) == B.ERR_ALIGN
+    assert call(phi=FAKE + 2) == B.ERR_ALIGN

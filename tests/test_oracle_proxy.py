@@ -34,7 +34,8 @@ def two_level(p, a, q, b):
     return Pc, Pf
 
 
-@pytest.mark.parametrize("p,a,q,b", [(100, 1.0, 100, 3.0), (999, 0.5, 1, 200.0), (7, 2.0, 50, 0.125)])
+@pytest.mark.parametrize("p,a,q,b", [(100, 1.0, 100, 3.0), (999, 0.5, 1, 200.0), (7, 2.0, 50, 0.125),
+                                     (100, 3.0, 5, 0.01)])   # the last one has negative odd moments
 def test_two_valued_intervals_closed_form(p, a, q, b):
     gaps = np.array([a] * p + [b] * q)
     np.random.default_rng(1).shuffle(gaps)          # order of the intervals is irrelevant
