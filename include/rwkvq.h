@@ -135,25 +135,29 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
 
 /* ---- the SQ / VQ decision (Sec. 3.1, "Coarse-grained Proxy" and "Fine-grained Proxy") ----------
  *
- * For one dense weight matrix w[N][K] (DEVICE pointer, row-major, fp16 or bf16 bit patterns, finite
- * values) compute
+ * For each of n_mats dense weight matrices ws[i] (DEVICE pointers in a HOST array; matrix i is
+ * Ns[i] x Ks[i], row-major, fp16 or bf16 bit patterns, finite values; Ns and Ks are HOST arrays)
+ * compute
  *   P_c = H(uniform) - H(G')                       Eq. "coarse_proxy", natural logarithm
  *   P_f = sum_{k=2}^{terms} v_k |M_k|              Eq. "fine_proxy", K = terms in [2, 8]
  *   phi = 1 (RWKVQ_SQ) if P_c < tau_c and P_f < tau_f, else 0 (RWKVQ_VQ)    Eq. "multi_scale_proxy"
  * where G' are the normalised intervals between neighbours of the sorted, flattened weights
  * (Eqs. "interval", "interval_norm"), 0 ln 0 := 0 for the zero intervals between equal weights, and
- * a constant matrix gives P_c = P_f = 0.  All arithmetic after the counting pass is binary64.
+ * a constant matrix gives P_c = P_f = 0.  All arithmetic after the pass over the weights is
+ * binary64 in a fixed order.
  *
- * proxies: DEVICE pointer to two doubles (P_c, P_f); phi: DEVICE pointer to one int32.
- * workspace: DEVICE pointer to rwkvq_proxy_workspace_bytes() bytes of scratch owned by the caller
- * (contents irrelevant on entry, undefined on exit); all pointers 16-byte aligned.  The call is
+ * proxies: DEVICE pointer to 2 n_mats doubles (P_c, P_f per matrix); phi: DEVICE pointer to n_mats
+ * int32.  workspace: DEVICE pointer to rwkvq_proxy_workspace_bytes(n_mats) bytes of scratch owned
+ * by the caller (contents irrelevant on entry, undefined on exit).  workspace, proxies and every
+ * ws[i] 16-byte aligned, phi 4-byte aligned.  The host arrays are read before return; the call is
  * asynchronous on `stream`; calls that share a workspace must be ordered by the stream.
- * Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_ALIGN, RWKVQ_ERR_SHAPE (N, K < 1, fewer than two weights or
- * more than 2^32 - 1), RWKVQ_ERR_UNSUPPORTED (w_dtype other than fp16 / bf16, terms outside
- * [2, 8]), RWKVQ_ERR_DEVICE. */
-size_t rwkvq_proxy_workspace_bytes(void);
-int rwkvq_proxy(const void* w, int w_dtype, int N, int K, int terms, double tau_c, double tau_f,
-                void* workspace, double* proxies, int32_t* phi, void* stream);
+ * Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_ALIGN, RWKVQ_ERR_SHAPE (n_mats < 1, N or K < 1, a matrix of
+ * fewer than two weights or more than 2^32 - 1), RWKVQ_ERR_UNSUPPORTED (w_dtype other than
+ * fp16 / bf16, terms outside [2, 8]), RWKVQ_ERR_DEVICE. */
+size_t rwkvq_proxy_workspace_bytes(int n_mats);
+int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
+                double tau_c, double tau_f, void* workspace, double* proxies, int32_t* phi,
+                void* stream);
 
 #ifdef __cplusplus
 }

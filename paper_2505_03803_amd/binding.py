@@ -71,10 +71,10 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_linear_dispatch.argtypes = [POINTER(rwkvq_matrix), POINTER(c_void_p), POINTER(c_void_p),
                                             c_int, c_int, c_int, c_int, c_void_p]
         L.rwkvq_proxy_workspace_bytes.restype = c_size_t
-        L.rwkvq_proxy_workspace_bytes.argtypes = []
+        L.rwkvq_proxy_workspace_bytes.argtypes = [c_int]
         L.rwkvq_proxy.restype = c_int
-        L.rwkvq_proxy.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_double, c_double, c_void_p,
-                                  c_void_p, c_void_p, c_void_p]
+        L.rwkvq_proxy.argtypes = [POINTER(c_void_p), POINTER(c_int), POINTER(c_int), c_int, c_int, c_int,
+                                  c_double, c_double, c_void_p, c_void_p, c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -148,13 +148,26 @@ def rwkvq_vq_gemm(indices, codebooks, layout, x, y, M, N, K, vdim, kbits, block_
     return _check(st) if check else st
 
 
-def rwkvq_proxy_workspace_bytes() -> int:
-    return int(lib().rwkvq_proxy_workspace_bytes())
+def rwkvq_proxy_workspace_bytes(n_mats: int) -> int:
+    return int(lib().rwkvq_proxy_workspace_bytes(n_mats))
 
 
-def rwkvq_proxy(w, w_dtype, N, K, terms, tau_c, tau_f, workspace, proxies, phi, stream=None, check=True):
-    st = lib().rwkvq_proxy(_ptr(w), w_dtype, N, K, terms, tau_c, tau_f, _ptr(workspace), _ptr(proxies),
-                           _ptr(phi), _stream(stream))
+class ProxyTable:
+    """Host arrays for rwkvq_proxy (device pointers and shapes of the matrices), reusable."""
+
+    def __init__(self, ws: Sequence, shapes: Sequence):
+        n = len(ws)
+        assert len(shapes) == n
+        self.n = n
+        self.ws = (c_void_p * n)(*[_ptr(w) for w in ws])
+        self.Ns = (c_int * n)(*[int(s[0]) for s in shapes])
+        self.Ks = (c_int * n)(*[int(s[1]) for s in shapes])
+
+
+def rwkvq_proxy(table: ProxyTable, w_dtype, terms, tau_c, tau_f, workspace, proxies, phi, stream=None,
+                check=True):
+    st = lib().rwkvq_proxy(table.ws, table.Ns, table.Ks, table.n, w_dtype, terms, tau_c, tau_f,
+                           _ptr(workspace), _ptr(proxies), _ptr(phi), _stream(stream))
     return _check(st) if check else st
 
 
@@ -259,16 +272,17 @@ def gemm(dm: DeviceMatrix, x, M: int, x_dtype: int, y_dtype: int = F32, stream=N
     return y
 
 
-def proxy(w, w_dtype: int, terms: int = 5, tau_c: float = 1.5, tau_f: float = 50.0, workspace=None, stream=None):
-    """(P_c, P_f, phi) of a dense weight matrix through rwkvq_proxy; w is a 2-D int16 tensor of
-    fp16 / bf16 bit patterns on the GPU.  Synchronises to read the three numbers back."""
+def proxy(ws, w_dtype: int, terms: int = 5, tau_c: float = 1.5, tau_f: float = 50.0, stream=None):
+    """[(P_c, P_f, phi)] of dense weight matrices through one rwkvq_proxy call; ws is a list of 2-D
+    int16 tensors of fp16 / bf16 bit patterns on the GPU.  Synchronises to read the results back."""
     import torch
-    N, K = w.shape
-    if workspace is None:
-        workspace = torch.empty(rwkvq_proxy_workspace_bytes() // 4, dtype=torch.int32, device=w.device)
-    out = torch.empty(2, dtype=torch.float64, device=w.device)
-    flag = torch.empty(4, dtype=torch.int32, device=w.device)
-    rwkvq_proxy(w, w_dtype, N, K, terms, tau_c, tau_f, workspace, out, flag, stream)
+    dev = ws[0].device
+    table = ProxyTable(ws, [tuple(w.shape) for w in ws])
+    workspace = torch.empty(rwkvq_proxy_workspace_bytes(table.n) // 4, dtype=torch.int32, device=dev)
+    out = torch.empty(2 * table.n, dtype=torch.float64, device=dev)
+    flag = torch.empty(table.n + 3, dtype=torch.int32, device=dev)
+    rwkvq_proxy(table, w_dtype, terms, tau_c, tau_f, workspace, out, flag, stream)
     torch.cuda.synchronize()
     o = out.cpu().numpy()
-    return float(o[0]), float(o[1]), int(flag[0].item())
+    f = flag.cpu().numpy()
+    return [(float(o[2 * i]), float(o[2 * i + 1]), int(f[i])) for i in range(table.n)]

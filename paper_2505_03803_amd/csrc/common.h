@@ -129,8 +129,9 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
 hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype,
                           hipStream_t s);
 
-hipError_t launch_proxy(const void* w, int dtype, unsigned long long count, int terms, double tau_c,
-                        double tau_f, uint32_t* hist, double* out, int32_t* phi, hipStream_t s);
+hipError_t launch_proxy(const void* const* ws, const unsigned long long* counts, int n_mats, int dtype,
+                        int terms, double tau_c, double tau_f, uint32_t* bitmaps, double* out, int32_t* phi,
+                        hipStream_t s);
 
 constexpr int kDecodeMaxM = 16;    // native layout: M <= this goes to the streaming kernels
 constexpr int kDecodeMaxK = 20480; // ... whose per-group activation sums for K columns fit their LDS

@@ -2,10 +2,11 @@
 // matrices stored as fp16 or bf16.
 //
 // The paper sorts the flattened weights and works on the intervals between neighbours.  Sixteen-bit
-// weights take at most 65 536 distinct values, so the sorted sequence is fully described by how
-// often each value occurs: one pass over the matrix builds that histogram (HBM-bound, the only
-// part that touches the matrix), and everything else is a sum over at most 65 535 non-zero
-// intervals plus a closed-form term for the intervals of length zero between equal weights:
+// weights take at most 65 536 distinct values, and the sums below depend only on WHICH values occur
+// (equal weights contribute intervals of length zero, whose number is oc*ic minus the number of
+// distinct values).  One pass over the matrix therefore only records the set of occurring bit
+// patterns (HBM-bound, the only part that touches the matrix); the rest is a sum over at most
+// 65 535 non-zero intervals plus a closed-form term for the zero ones:
 //
 //   n = oc*ic - 1 intervals, sum(G) = max - min, t_i = G_i / (sum(G) / n) = n G'_i
 //   P_c = ln n - H(G')           = (1/n) sum_i t_i ln t_i                 (0 ln 0 := 0)
@@ -18,11 +19,22 @@
 
 namespace rwkvq {
 
-constexpr int kProxyBins = 65536;
-constexpr int kHistThreads = 512;
-constexpr int kHistChunk = 61440;       // elements between two flushes: < 65 536, so the 16-bit
-                                        // counters packed two per LDS word cannot overflow
-static_assert(kHistChunk % (8 * kHistThreads) == 0, "whole 16-byte loads per thread");
+constexpr int kProxyKeys = 65536;
+constexpr int kBitmapWords = kProxyKeys / 32;     // the workspace: one bit per 16-bit pattern
+constexpr int kSetThreads = 1024;                 // two workgroups of 64 KB LDS fit a CU
+constexpr int kSetMaxWgs = 128;                   // workgroups per matrix
+constexpr int kProxyMaxMats = 64;                 // matrices per launch (one table entry per lane)
+
+struct ProxyArgs {
+    int wg_end[kProxyMaxMats];                    // running sum of workgroups per matrix
+    const uint16_t* w[kProxyMaxMats];
+    unsigned long long count[kProxyMaxMats];
+    uint32_t* bitmaps;                            // kBitmapWords words per matrix
+    double* out;                                  // two doubles per matrix
+    int32_t* phi;                                 // one flag per matrix
+    int n_mats, dtype, terms, pad;
+    double tau_c, tau_f;
+};
 
 // Order-preserving map of a sign-magnitude 16-bit float pattern to an unsigned key.
 __device__ __forceinline__ uint32_t sort_key(uint32_t bits) {
@@ -36,55 +48,55 @@ __device__ __forceinline__ double key_value(uint32_t key, int dtype) {
     return dtype == DT_F16 ? (double)f16_bits_to_f32(b) : (double)bf16_bits_to_f32(b);
 }
 
-__global__ void __launch_bounds__(256) proxy_clear_kernel(uint32_t* hist) {
-    hist[blockIdx.x * 256 + threadIdx.x] = 0u;
+__global__ void __launch_bounds__(256) proxy_clear_kernel(uint32_t* bitmap) {
+    bitmap[blockIdx.x * 256 + threadIdx.x] = 0u;
 }
 
-// Histogram of the 16-bit patterns of w[0 .. count).  Each workgroup counts chunks of kHistChunk
-// elements in LDS (ds_add_u32 on counters packed two per word) and adds the non-zero counters of
-// a chunk to the global histogram before the next chunk.
-__global__ void __launch_bounds__(kHistThreads, 1)
-proxy_hist_kernel(const uint16_t* __restrict__ w, unsigned long long count, uint32_t* __restrict__ hist) {
-    __shared__ uint32_t cnt[kProxyBins / 2];
+// Set of the 16-bit patterns in w[0 .. count): every workgroup marks the keys of its share in a
+// byte-per-key table in LDS (plain byte stores: lanes that store the same flag do not need to be
+// ordered), packs the table to bits and ORs its non-zero words into the global bitmap.
+__global__ void __launch_bounds__(kSetThreads, 2) proxy_set_kernel(ProxyArgs a) {
+    __shared__ uint32_t flags[kProxyKeys / 4];
     const int tid = threadIdx.x;
-    for (int i = tid; i < kProxyBins / 2; i += kHistThreads) cnt[i] = 0u;
+    const int wg = blockIdx.x;
+    const int mi = __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[tid & 63]));
+    const int wg0 = mi ? a.wg_end[mi - 1] : 0;
+    const int local = wg - wg0, nwg = a.wg_end[mi] - wg0;        // this matrix's workgroups
+    const uint16_t* __restrict__ w = a.w[mi];
+    const unsigned long long count = a.count[mi];
+    uint32_t* __restrict__ bitmap = a.bitmaps + (size_t)mi * kBitmapWords;
+    for (int i = tid; i < kProxyKeys / 4; i += kSetThreads) flags[i] = 0u;
     __syncthreads();
-    const unsigned long long nchunks = (count + kHistChunk - 1) / kHistChunk;
-    for (unsigned long long c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        const unsigned long long base = c * kHistChunk;
-        const unsigned long long end = base + kHistChunk < count ? base + kHistChunk : count;
-        auto add = [&](uint32_t bits) {
-            const uint32_t k = sort_key(bits);
-            atomicAdd(&cnt[k >> 1], (k & 1u) ? 0x10000u : 1u);
-        };
-        if (end - base == kHistChunk) {
-            const uint4_t* src = (const uint4_t*)(w + base);
-#pragma unroll 5
-            for (int i = 0; i < kHistChunk / (8 * kHistThreads); ++i) {
-                const uint4_t v = src[i * kHistThreads + tid];
-                const uint32_t a = v.x, b = v.y, cc = v.z, d = v.w;
-                add(a & 0xFFFFu); add(a >> 16); add(b & 0xFFFFu); add(b >> 16);
-                add(cc & 0xFFFFu); add(cc >> 16); add(d & 0xFFFFu); add(d >> 16);
-            }
-        } else {                                     // the ragged last chunk, element by element
-            for (unsigned long long i = base + tid; i < end; i += kHistThreads) add(w[i]);
-        }
-        __syncthreads();
-        for (int i = tid; i < kProxyBins / 2; i += kHistThreads) {
-            const uint32_t v = cnt[i];
-            if (v) {
-                cnt[i] = 0u;
-                if (v & 0xFFFFu) atomicAdd(&hist[2 * i], v & 0xFFFFu);
-                if (v >> 16) atomicAdd(&hist[2 * i + 1], v >> 16);
-            }
-        }
-        __syncthreads();
+    volatile uint8_t* flag = (volatile uint8_t*)flags;
+    const unsigned long long nvec = count / 8;                 // whole 16-byte groups of 8 weights
+    const uint4_t* src = (const uint4_t*)w;
+    for (unsigned long long i = (unsigned long long)local * kSetThreads + tid; i < nvec;
+         i += (unsigned long long)nwg * kSetThreads) {
+        const uint4_t v = src[i];
+        const uint32_t a = v.x, b = v.y, c = v.z, d = v.w;
+        flag[sort_key(a & 0xFFFFu)] = 1; flag[sort_key(a >> 16)] = 1;
+        flag[sort_key(b & 0xFFFFu)] = 1; flag[sort_key(b >> 16)] = 1;
+        flag[sort_key(c & 0xFFFFu)] = 1; flag[sort_key(c >> 16)] = 1;
+        flag[sort_key(d & 0xFFFFu)] = 1; flag[sort_key(d >> 16)] = 1;
+    }
+    if (local == 0 && (unsigned long long)tid < count - 8 * nvec)        // the ragged tail
+        flag[sort_key(w[8 * nvec + tid])] = 1;
+    __syncthreads();
+    // 32 flags -> one bitmap word; the walk starts at a different word in every workgroup so that
+    // the workgroups do not all hit the same global words at the same time
+    for (int j = tid; j < kBitmapWords; j += kSetThreads) {
+        const int i = (j + 37 * local) & (kBitmapWords - 1);
+        uint32_t m = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)      // four flag bytes (0 or 1) -> four bits: one multiply
+            m |= ((((flags[8 * i + q] & 0x01010101u) * 0x01020408u) >> 24) & 0xFu) << (4 * q);
+        if (m) atomicOr(&bitmap[i], m);
     }
 }
 
-constexpr int kFinalThreads = 1024;
-constexpr int kKeysPerThread = kProxyBins / kFinalThreads;     // 64 consecutive keys per thread
+constexpr int kFinalThreads = 1024;               // one thread per 64 consecutive keys
 constexpr int kMaxTerms = 8;
+static_assert(kFinalThreads * 64 == kProxyKeys, "one 64-bit presence word per thread");
 
 // Fixed-order sum over the workgroup (binary64): lanes of a wavefront first, then the wavefronts.
 __device__ __forceinline__ double block_sum(double v, double* scratch) {
@@ -99,39 +111,44 @@ __device__ __forceinline__ double block_sum(double v, double* scratch) {
     return s;
 }
 
-// out[0] = P_c, out[1] = P_f, *phi = 1 (SQ) iff P_c < tau_c and P_f < tau_f.
-__global__ void __launch_bounds__(kFinalThreads, 1)
-proxy_final_kernel(const uint32_t* __restrict__ hist, int dtype, unsigned long long count, int terms,
-                   double tau_c, double tau_f, double* __restrict__ out, int32_t* __restrict__ phi) {
-    __shared__ int last_present[kFinalThreads];      // largest present key of a thread's range, or -1
-    __shared__ int first_present[kFinalThreads];
+// One workgroup per matrix: out[0] = P_c, out[1] = P_f, *phi = 1 (SQ) iff P_c < tau_c and
+// P_f < tau_f.  Thread t first owns presence word t (keys 64 t .. 64 t + 63); running sums over the words give
+// the rank of every present key, and each thread then walks an equal share of the ranks (the
+// present keys of near-Gaussian weights crowd into a few words: a thread per word would leave
+// most threads idle while a few evaluate 64 logarithms each).
+__global__ void __launch_bounds__(kFinalThreads, 1) proxy_final_kernel(ProxyArgs a) {
+    const int mat = blockIdx.x;                      // one workgroup per matrix
+    const uint32_t* __restrict__ bitmap = a.bitmaps + (size_t)mat * kBitmapWords;
+    const unsigned long long count = a.count[mat];
+    const int dtype = a.dtype, terms = a.terms;
+    const double tau_c = a.tau_c, tau_f = a.tau_f;
+    double* __restrict__ out = a.out + 2 * mat;
+    int32_t* __restrict__ phi = a.phi + mat;
+    __shared__ unsigned long long present[kFinalThreads];
+    __shared__ int before[kFinalThreads + 1];        // number of present keys below word t
+    __shared__ int last_present[kFinalThreads];      // largest present key up to and including word t
     __shared__ double scratch[kFinalThreads / 64];
-    const int tid = threadIdx.x, k0 = tid * kKeysPerThread;
+    const int tid = threadIdx.x;
 
-    int first = -1, last = -1, distinct = 0;
-    for (int i = 0; i < kKeysPerThread; ++i)
-        if (hist[k0 + i]) {
-            if (first < 0) first = k0 + i;
-            last = k0 + i;
-            ++distinct;
-        }
-    last_present[tid] = last;
-    first_present[tid] = first;
+    const unsigned long long mine = ((const unsigned long long*)bitmap)[tid];
+    present[tid] = mine;
+    before[tid + 1] = __builtin_popcountll(mine);
+    last_present[tid] = mine ? 64 * tid + 63 - __builtin_clzll(mine) : -1;
+    if (tid == 0) before[0] = 0;
     __syncthreads();
-    // inclusive running maximum of last_present over the threads (ten doubling steps)
-    for (int off = 1; off < kFinalThreads; off <<= 1) {
+    for (int off = 1; off < kFinalThreads; off <<= 1) {          // inclusive running sum / maximum
+        const int add = tid >= off ? before[tid + 1 - off] : 0;
         const int other = tid >= off ? last_present[tid - off] : -1;
         __syncthreads();
+        before[tid + 1] += add;
         if (other > last_present[tid]) last_present[tid] = other;
         __syncthreads();
     }
-    const int prev_before = tid ? last_present[tid - 1] : -1;   // last present key below k0
+    const int D = before[kFinalThreads];                         // distinct values (>= 1)
     const int kmax = last_present[kFinalThreads - 1];
-    // smallest present key: the first thread whose range holds one
-    int kmin = -1;
-    for (int i = 0; i < kFinalThreads; ++i)
-        if (first_present[i] >= 0) { kmin = first_present[i]; break; }
-    const double D = block_sum((double)distinct, scratch);
+    int lo = 0, hi = kFinalThreads - 1;                          // first non-empty word
+    while (lo < hi) { const int mid = (lo + hi) >> 1; if (before[mid + 1] > 0) hi = mid; else lo = mid + 1; }
+    const int kmin = 64 * lo + __builtin_ctzll(present[lo]);
 
     const double n = (double)(count - 1ull);
     const double span = key_value((uint32_t)kmax, dtype) - key_value((uint32_t)kmin, dtype);
@@ -141,21 +158,32 @@ proxy_final_kernel(const uint32_t* __restrict__ hist, int dtype, unsigned long l
     }
     const double inv_mean = n / span;            // 1 / (sum(G) / n)
 
+    // ranks r0 .. r1-1 of the present keys are this thread's
+    const int r0 = (int)((long long)tid * D / kFinalThreads), r1 = (int)((long long)(tid + 1) * D / kFinalThreads);
     double sc = 0.0, sk[kMaxTerms + 1];
     for (int k = 0; k <= kMaxTerms; ++k) sk[k] = 0.0;
-    int prev = prev_before;
-    for (int i = 0; i < kKeysPerThread; ++i) {
-        const int key = k0 + i;
-        if (!hist[key]) continue;
-        if (prev >= 0) {
-            const double g = key_value((uint32_t)key, dtype) - key_value((uint32_t)prev, dtype);   // exact
-            const double t = g * inv_mean;
-            if (t > 0.0) sc += t * log(t);
-            const double u = t - 1.0;
-            double p = u;
-            for (int k = 2; k <= terms; ++k) { p *= u; sk[k] += p; }
+    if (r1 > r0) {
+        lo = 0; hi = kFinalThreads - 1;                          // the word that holds rank r0
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (before[mid + 1] > r0) hi = mid; else lo = mid + 1; }
+        int wd = lo;
+        unsigned long long m = present[wd];
+        for (int skip = r0 - before[wd]; skip > 0; --skip) m &= m - 1;   // drop the keys ranked below r0
+        const unsigned long long dropped = present[wd] ^ m;
+        int prev = dropped ? 64 * wd + 63 - __builtin_clzll(dropped) : (wd ? last_present[wd - 1] : -1);
+        for (int r = r0; r < r1; ++r) {
+            while (!m) m = present[++wd];
+            const int key = 64 * wd + __builtin_ctzll(m);
+            m &= m - 1;
+            if (prev >= 0) {
+                const double g = key_value((uint32_t)key, dtype) - key_value((uint32_t)prev, dtype);   // exact
+                const double t = g * inv_mean;
+                if (t > 0.0) sc += t * log(t);
+                const double u = t - 1.0;
+                double p = u;
+                for (int k = 2; k <= terms; ++k) { p *= u; sk[k] += p; }
+            }
+            prev = key;
         }
-        prev = key;
     }
     const double sum_c = block_sum(sc, scratch);
     double sum_k[kMaxTerms + 1];
@@ -163,7 +191,7 @@ proxy_final_kernel(const uint32_t* __restrict__ hist, int dtype, unsigned long l
 
     if (tid == 0) {
         // the count - D intervals between equal weights have t = 0: t ln t = 0, (t - 1)^k = (-1)^k
-        const double zero_gaps = (double)count - D;
+        const double zero_gaps = (double)count - (double)D;
         double Pf = 0.0;
         for (int k = 2; k <= terms; ++k) {
             const double s = sum_k[k] + ((k & 1) ? -zero_gaps : zero_gaps);
@@ -176,19 +204,38 @@ proxy_final_kernel(const uint32_t* __restrict__ hist, int dtype, unsigned long l
     }
 }
 
-hipError_t launch_proxy(const void* w, int dtype, unsigned long long count, int terms, double tau_c,
-                        double tau_f, uint32_t* hist, double* out, int32_t* phi, hipStream_t s) {
-    hipLaunchKernelGGL(proxy_clear_kernel, dim3(kProxyBins / 256), dim3(256), 0, s, hist);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const unsigned long long nchunks = (count + kHistChunk - 1) / kHistChunk;
-    const int grid = (int)(nchunks < 256 ? nchunks : 256);     // one workgroup (128 KB of LDS) per CU
-    hipLaunchKernelGGL(proxy_hist_kernel, dim3(grid), dim3(kHistThreads), 0, s, (const uint16_t*)w, count, hist);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(proxy_final_kernel, dim3(1), dim3(kFinalThreads), 0, s, hist, dtype, count, terms, tau_c,
-                       tau_f, out, phi);
-    return hipGetLastError();
+hipError_t launch_proxy(const void* const* ws, const unsigned long long* counts, int n_mats, int dtype, int terms,
+                        double tau_c, double tau_f, uint32_t* bitmaps, double* out, int32_t* phi, hipStream_t s) {
+    for (int base = 0; base < n_mats; base += kProxyMaxMats) {
+        ProxyArgs a;
+        const int cnt = n_mats - base < kProxyMaxMats ? n_mats - base : kProxyMaxMats;
+        int wgs = 0;
+        for (int i = 0; i < cnt; ++i) {
+            const unsigned long long nvec = counts[base + i] / 8;
+            unsigned long long g = (nvec + 16ull * kSetThreads - 1) / (16ull * kSetThreads);   // >= 128 weights per thread
+            g = g < 1 ? 1 : g > (unsigned long long)kSetMaxWgs ? kSetMaxWgs : g;
+            wgs += (int)g;
+            a.wg_end[i] = wgs;
+            a.w[i] = (const uint16_t*)ws[base + i];
+            a.count[i] = counts[base + i];
+        }
+        for (int i = cnt; i < kProxyMaxMats; ++i) { a.wg_end[i] = 0x7FFFFFFF; a.w[i] = nullptr; a.count[i] = 0; }
+        a.bitmaps = bitmaps + (size_t)base * kBitmapWords;
+        a.out = out + 2 * base;
+        a.phi = phi + base;
+        a.n_mats = cnt; a.dtype = dtype; a.terms = terms; a.pad = 0;
+        a.tau_c = tau_c; a.tau_f = tau_f;
+        hipLaunchKernelGGL(proxy_clear_kernel, dim3(cnt * kBitmapWords / 256), dim3(256), 0, s, a.bitmaps);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(proxy_set_kernel, dim3(wgs), dim3(kSetThreads), 0, s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(proxy_final_kernel, dim3(cnt), dim3(kFinalThreads), 0, s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace rwkvq

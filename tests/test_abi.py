@@ -108,20 +108,22 @@ def test_dispatch_rejects():
 
 def test_proxy_rejects():
     L = B.lib()
-    assert L.rwkvq_proxy_workspace_bytes() == 65536 * 4
-    ok = (FAKE, B.BF16, 256, 256, 5, 1.5, 50.0, FAKE, FAKE, FAKE, None)
+    assert L.rwkvq_proxy_workspace_bytes(1) == 65536 // 8
+    assert L.rwkvq_proxy_workspace_bytes(256) == 256 * 65536 // 8
+    assert L.rwkvq_proxy_workspace_bytes(0) == 0
 
-    def call(**kw):
-        names = ["w", "dt", "N", "K", "terms", "tc", "tf", "ws", "out", "phi", "stream"]
-        args = list(ok)
-        for k, v in kw.items():
-            args[names.index(k)] = v
-        return L.rwkvq_proxy(*args)
+    def call(w=FAKE, N=256, K=256, n=1, dt=B.BF16, terms=5, ws=FAKE, out=FAKE, phi=FAKE, null_table=False):
+        wp = (ctypes.c_void_p * 2)(w, FAKE)
+        Ns = (ctypes.c_int * 2)(N, 256)
+        Ks = (ctypes.c_int * 2)(K, 256)
+        return L.rwkvq_proxy(None if null_table else wp, Ns, Ks, n, dt, terms, 1.5, 50.0, ws, out, phi, None)
 
+    assert call(null_table=True) == B.ERR_NULL
     assert call(w=None) == B.ERR_NULL
     assert call(ws=None) == B.ERR_NULL
     assert call(out=None) == B.ERR_NULL
     assert call(phi=None) == B.ERR_NULL
+    assert call(n=0) == B.ERR_SHAPE
     assert call(dt=B.F32) == B.ERR_UNSUPPORTED
     assert call(terms=1) == B.ERR_UNSUPPORTED
     assert call(terms=9) == B.ERR_UNSUPPORTED

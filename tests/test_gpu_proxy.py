@@ -15,7 +15,7 @@ def run(bits, dtype, terms=5, tau_c=1.5, tau_f=50.0):
     import torch
     from paper_2505_03803_amd import binding as B
     w = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
-    return B.proxy(w, B.DTYPES[dtype], terms, tau_c, tau_f)
+    return B.proxy([w], B.DTYPES[dtype], terms, tau_c, tau_f)[0]
 
 
 def check(bits, dtype, terms=5):
@@ -65,6 +65,20 @@ def test_proxy_decision_bit():
     ePc, ePf = PO.proxies(PO.widen16(bits, "bf16"))
     for tau_c, tau_f in ((ePc * 2, ePf * 2), (ePc * 2, ePf / 2), (ePc / 2, ePf * 2), (ePc / 2, ePf / 2)):
         assert run(bits, "bf16", 5, tau_c, tau_f)[2] == PO.phi(ePc, ePf, tau_c, tau_f)
+
+
+def test_proxy_many_matrices_in_one_call():
+    """70 matrices of mixed shapes: two launches of the grouped kernels, results per matrix."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    rng = np.random.default_rng(8)
+    shapes = [(64 + 16 * (i % 5), 96 + 8 * (i % 7)) for i in range(69)] + [(1024, 1536)]
+    mats = [synth.gen_dense_weights(rng, N, K, "bf16", outlier_fraction=1e-3 * (i % 3)) for i, (N, K) in enumerate(shapes)]
+    got = B.proxy([torch.from_numpy(m.view(np.int16)).cuda() for m in mats], B.BF16, 5, 9.0, 1e12)
+    for m, (Pc, Pf, flag) in zip(mats, got):
+        ePc, ePf = PO.proxies(PO.widen16(m, "bf16"))
+        assert Pc == pytest.approx(ePc, rel=REL) and Pf == pytest.approx(ePf, rel=REL)
+        assert flag == PO.phi(ePc, ePf, 9.0, 1e12)
 
 
 @pytest.mark.parametrize("N,K", [(4096, 4096), (4096, 14336)])
