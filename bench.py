@@ -33,6 +33,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 DECODE_KERNEL = "rwkvq::decode_kernel<1>"
 PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT>"   # bf16; one instantiation per weight format
+PROXY_KERNEL = "rwkvq::proxy_set_kernel"
 DECODE_MATS_PER_LAUNCH = 64
 # HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
 # scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic_config3.txt.
@@ -123,6 +124,8 @@ def main():
     ap.add_argument("--prefill-steps", type=int, default=3)
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--skip-proxy", action="store_true")
+    ap.add_argument("--proxy-layers", type=int, default=8, help="layers of dense bf16 weights the proxy leg scans per call")
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for --pmc byte counters)")
@@ -197,6 +200,55 @@ def main():
                                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
         del pf, runp
+        torch.cuda.empty_cache()
+
+    # ---------------- proxy leg: P_c, P_f, phi of the dense bf16 matrices of some layers
+    if not args.skip_proxy:
+        from paper_2505_03803_amd import synth
+        shapes = [(N, K) for _ in range(args.proxy_layers) for _, N, K in synth.layer_shapes(4096, 14336)]
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(2000)
+        mats = [(torch.randn(sh, device="cuda", generator=gen) * 0.02).to(torch.bfloat16).view(torch.int16)
+                for sh in shapes]
+        n = len(mats)
+        table = B.ProxyTable(mats, shapes)
+        wsp = torch.empty(B.rwkvq_proxy_workspace_bytes(n) // 4, dtype=torch.int32, device="cuda")
+        pout = torch.empty(2 * n, dtype=torch.float64, device="cuda")
+        pphi = torch.empty(n + 3, dtype=torch.int32, device="cuda")
+        runx = lambda: B.rwkvq_proxy(table, B.BF16, 5, 1.5, 50.0, wsp, pout, pphi)
+        xtotal, xper, _ = time_steps(runx, 10, 2)
+        xms = xtotal / 10
+        xbytes = sum(a * b * 2 for a, b in shapes)
+        launches = (n + 63) // 64
+        out["proxy"] = {"value": xbytes / (xms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_call": xms, "calls": 10,
+                        "dtype": "f64", "matrices": n, "dense_weight_bytes_per_call": xbytes,
+                        "pct_hbm_peak": 100.0 * xbytes / (xms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "workload": "dense bf16 N(0, 0.02) weights of %d RWKV-6-7B-shaped layers "
+                                    "(d=4096, ffn=14336), K = 5 terms" % args.proxy_layers}
+        out["roofline_proxy"] = {"kernel": PROXY_KERNEL, "bound": "hbm",
+                                 "achieved": xbytes / (xms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                 "frac": xbytes / (xms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 # FETCH_SIZE x 2 + WRITE_SIZE of the set kernel for the default 8 layers
+                                 # (profiles/proxy_kernel_trace_and_traffic_7b_layers.txt)
+                                 "traffic": 3495.6e6 if args.proxy_layers == 8 else None,
+                                 "algorithmic_bytes_per_launch": xbytes / launches,
+                                 "avg_launch_ms": xms / launches,
+                                 "note": "achieved = dense weight bytes / time of the whole call (clear + set + "
+                                         "final kernels); the set kernel alone is the HBM-bound pass"}
+        if not args.skip_cpu:
+            # the oracle (sort-based definition) on the first matrices, about ten seconds of host time
+            from oracle import proxy_oracle as PO
+            secs, nb, k = 0.0, 0, 0
+            while secs < 8.0 and k < n:
+                host = mats[k].cpu().numpy().view(np.uint16)
+                t = time.perf_counter()
+                PO.proxies(PO.widen16(host, "bf16"))
+                secs += time.perf_counter() - t
+                nb += host.size * 2
+                k += 1
+            out["proxy"]["cpu_baseline"] = {"value": nb / secs / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                            "sample": "first %d of the %d matrices (%d dense bytes in %.2f s)" % (k, n, nb, secs)}
+        del mats, table, wsp, pout, pphi
         torch.cuda.empty_cache()
 
     # ---------------- CPU oracle baseline (reported, not a target)

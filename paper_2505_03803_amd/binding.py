@@ -45,6 +45,10 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(_build.LIB):
             _build.build()
+        # The tensors and streams passed in come from PyTorch's HIP runtime: load it first, so
+        # that the library binds to that copy of the runtime and not to a second one of its own
+        # (kernels launched through another copy on torch's streams fail with a launch error).
+        import torch  # noqa: F401
         L = ctypes.CDLL(_build.LIB)
         L.rwkvq_version.restype = c_int
         L.rwkvq_version.argtypes = []
