@@ -159,6 +159,32 @@ int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats,
                 double tau_c, double tau_f, void* workspace, double* proxies, int32_t* phi,
                 void* stream);
 
+/* ---- encoders (Sec. 2.2, Eq. "SQ" and Eq. "VQ"): dense weights -> canonical-layout codes -----------
+ *
+ * w: DEVICE pointer, row-major [N][K], fp16 / bf16 bit patterns or binary32 (w_dtype), finite.
+ * Every floating-point step is one binary32 operation rounded to nearest even, so the integer
+ * results are reproducible by any implementation of the same steps.
+ *
+ * rwkvq_sq_encode, per row and group of `group` = 128 columns, bits = 3:
+ *     s = (max - min) / (2^bits - 1)  stored as fp16;   z = -min / s  (with the stored s), stored
+ *     as fp16;   q = clamp(rne(w / s + z), 0, 2^bits - 1)  with the stored s and z (ties to even).
+ *   A constant group, or one whose fp16 scale would be zero, takes s = 1, z = -min.  A group's
+ *   scale and zero point must fit fp16.  Outputs in the canonical layout: codes [N][3K/32],
+ *   scales [N][K/128], zeros [N][K/128].
+ *
+ * rwkvq_vq_assign (vdim = 2, kbits = 6 or 8, 256 x 256 blocks): index of the codebook entry
+ *   nearest to (w[n][2j], w[n][2j+1]) in squared Euclidean distance
+ *   fl(fl((v0 - c0)^2) + fl((v1 - c1)^2)); equal distances resolve to the lowest index.
+ *   codebooks as for rwkvq_vq_gemm; indices out in the canonical layout [N][(K/2) kbits / 32].
+ *
+ * All pointers 16-byte aligned; asynchronous on `stream`; no scratch memory.
+ * Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_UNSUPPORTED (format parameters, dtype), RWKVQ_ERR_SHAPE (K not a
+ * multiple of the group / N, K not multiples of the block), RWKVQ_ERR_ALIGN, RWKVQ_ERR_DEVICE. */
+int rwkvq_sq_encode(const void* w, int w_dtype, int N, int K, int bits, int group, void* codes,
+                    void* scales, void* zeros, void* stream);
+int rwkvq_vq_assign(const void* w, int w_dtype, const void* codebooks, int N, int K, int vdim, int kbits,
+                    int block_rows, int block_cols, void* indices, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

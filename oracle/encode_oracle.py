@@ -21,7 +21,9 @@ Readings (the paper is silent or ambiguous; also listed in the design doc):
     the nearest point of the grid {(q - z) s} that the dequantization spans;
   * rounding to nearest resolves ties to even;
   * s and z are stored as fp16 and the codes are chosen against the stored values;
-  * a constant group (max = min) takes s = 1, z = -min, q = 0.
+  * a constant group (max = min), or one whose range is below the resolution of an fp16 scale,
+    takes s = 1, z = -min (the codes then round w - min, i.e. are 0);
+  * inputs are finite and a group's scale and zero point must fit fp16.
 
 VQ (Eq. "VQ", d = 2): the vector (w[n][2j], w[n][2j+1]) is replaced by
     argmin_e  fl( fl((v0 - c_e0)^2) + fl((v1 - c_e1)^2) )
@@ -58,9 +60,10 @@ def sq_encode(W: np.ndarray, bits: int = 3, group: int = 128):
     lo = Wg.min(axis=2)
     hi = Wg.max(axis=2)
     levels = F32(2 ** bits - 1)
-    const = hi == lo
     with np.errstate(divide="ignore", invalid="ignore"):
-        s32 = (hi - lo) / levels
+        s32 = ((hi - lo) / levels).astype(F32)
+    # constant group, or a range so small that the fp16 scale would be zero
+    const = (hi == lo) | (s32.astype(np.float16) == 0)
     s32 = np.where(const, F32(1.0), s32).astype(F32)
     s16 = s32.astype(np.float16)
     s = s16.astype(F32)

@@ -20,7 +20,8 @@ DTYPES = {"f16": F16, "bf16": BF16, "f32": F32}
 
 EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq_prepack",
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
-           "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy"]
+           "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
+           "rwkvq_vq_assign"]
 
 
 class rwkvq_matrix(Structure):
@@ -79,6 +80,12 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_proxy.restype = c_int
         L.rwkvq_proxy.argtypes = [POINTER(c_void_p), POINTER(c_int), POINTER(c_int), c_int, c_int, c_int,
                                   c_double, c_double, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.rwkvq_sq_encode.restype = c_int
+        L.rwkvq_sq_encode.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                      c_void_p]
+        L.rwkvq_vq_assign.restype = c_int
+        L.rwkvq_vq_assign.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
+                                      c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -172,6 +179,19 @@ def rwkvq_proxy(table: ProxyTable, w_dtype, terms, tau_c, tau_f, workspace, prox
                 check=True):
     st = lib().rwkvq_proxy(table.ws, table.Ns, table.Ks, table.n, w_dtype, terms, tau_c, tau_f,
                            _ptr(workspace), _ptr(proxies), _ptr(phi), _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_sq_encode(w, w_dtype, N, K, bits, group, codes, scales, zeros, stream=None, check=True):
+    st = lib().rwkvq_sq_encode(_ptr(w), w_dtype, N, K, bits, group, _ptr(codes), _ptr(scales), _ptr(zeros),
+                               _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_vq_assign(w, w_dtype, codebooks, N, K, vdim, kbits, block_rows, block_cols, indices, stream=None,
+                    check=True):
+    st = lib().rwkvq_vq_assign(_ptr(w), w_dtype, _ptr(codebooks), N, K, vdim, kbits, block_rows, block_cols,
+                               _ptr(indices), _stream(stream))
     return _check(st) if check else st
 
 
@@ -290,3 +310,25 @@ def proxy(ws, w_dtype: int, terms: int = 5, tau_c: float = 1.5, tau_f: float = 5
     o = out.cpu().numpy()
     f = flag.cpu().numpy()
     return [(float(o[2 * i]), float(o[2 * i + 1]), int(f[i])) for i in range(table.n)]
+
+
+def sq_encode(w, w_dtype: int, stream=None) -> DeviceMatrix:
+    """Round-to-nearest SQ of a dense [N][K] tensor on the GPU (int16 bit patterns or float32) ->
+    canonical-layout DeviceMatrix."""
+    import torch
+    N, K = w.shape
+    codes = torch.empty((N, 3 * K // 32), dtype=torch.int32, device=w.device)
+    scales = torch.empty((N, K // 128), dtype=torch.int16, device=w.device)
+    zeros = torch.empty((N, K // 128), dtype=torch.int16, device=w.device)
+    rwkvq_sq_encode(w, w_dtype, N, K, 3, 128, codes, scales, zeros, stream)
+    return DeviceMatrix(SQ, CANONICAL, N, K, 0, codes, scales, zeros, None, codes.numel() * 4 + scales.numel() * 4)
+
+
+def vq_assign(w, w_dtype: int, codebooks, kbits: int, stream=None) -> DeviceMatrix:
+    """Nearest-entry VQ assignment of a dense [N][K] tensor against given codebooks (int16 fp16 bit
+    patterns, [N/256][K/256][2^kbits][2]) -> canonical-layout DeviceMatrix."""
+    import torch
+    N, K = w.shape
+    idx = torch.empty((N, K // 2 * kbits // 32), dtype=torch.int32, device=w.device)
+    rwkvq_vq_assign(w, w_dtype, codebooks, N, K, 2, kbits, 256, 256, idx, stream)
+    return DeviceMatrix(VQ, CANONICAL, N, K, kbits, idx, None, None, codebooks, idx.numel() * 4 + codebooks.numel() * 2)

@@ -205,4 +205,31 @@ int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats,
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 
+static int dense_dtype(int w_dtype) {
+    return w_dtype == RWKVQ_F16 ? DT_F16 : w_dtype == RWKVQ_BF16 ? DT_BF16 : w_dtype == RWKVQ_F32 ? DT_F32 : -1;
+}
+
+int rwkvq_sq_encode(const void* w, int w_dtype, int N, int K, int bits, int group, void* codes, void* scales,
+                    void* zeros, void* stream) {
+    if (!w || !codes || !scales || !zeros) return RWKVQ_ERR_NULL;
+    if (bits != 3 || group != 128 || dense_dtype(w_dtype) < 0) return RWKVQ_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1 || K % 128 != 0) return RWKVQ_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(codes) || !aligned16(scales) || !aligned16(zeros)) return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_sq_encode(w, dense_dtype(w_dtype), N, K, (uint32_t*)codes, (uint16_t*)scales,
+                                    (uint16_t*)zeros, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
+int rwkvq_vq_assign(const void* w, int w_dtype, const void* codebooks, int N, int K, int vdim, int kbits,
+                    int block_rows, int block_cols, void* indices, void* stream) {
+    if (!w || !codebooks || !indices) return RWKVQ_ERR_NULL;
+    if (vdim != 2 || (kbits != 6 && kbits != 8) || block_rows != 256 || block_cols != 256 || dense_dtype(w_dtype) < 0)
+        return RWKVQ_ERR_UNSUPPORTED;
+    if (N < 1 || K < 1 || N % 256 != 0 || K % 256 != 0) return RWKVQ_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(codebooks) || !aligned16(indices)) return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_vq_assign(w, dense_dtype(w_dtype), N, K, kbits, (const uint16_t*)codebooks,
+                                    (uint32_t*)indices, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
 }  // extern "C"

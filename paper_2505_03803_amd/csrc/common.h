@@ -133,6 +133,11 @@ hipError_t launch_proxy(const void* const* ws, const unsigned long long* counts,
                         int terms, double tau_c, double tau_f, uint32_t* bitmaps, double* out, int32_t* phi,
                         hipStream_t s);
 
+hipError_t launch_sq_encode(const void* w, int wdt, int N, int K, uint32_t* codes, uint16_t* scales,
+                            uint16_t* zeros, hipStream_t s);
+hipError_t launch_vq_assign(const void* w, int wdt, int N, int K, int kbits, const uint16_t* codebooks,
+                            uint32_t* indices, hipStream_t s);
+
 constexpr int kDecodeMaxM = 16;    // native layout: M <= this goes to the streaming kernels
 constexpr int kDecodeMaxK = 20480; // ... whose per-group activation sums for K columns fit their LDS
 

@@ -133,3 +133,21 @@ def test_proxy_rejects():
     assert call(w=FAKE + 2) == B.ERR_ALIGN
     assert call(ws=FAKE + 8) == B.ERR_ALIGN
     assert call(phi=FAKE + 2) == B.ERR_ALIGN
+
+
+def test_encoder_rejects():
+    L = B.lib()
+    sq = lambda **kw: L.rwkvq_sq_encode(*[kw.get(k, v) for k, v in
+                                          [("w", FAKE), ("dt", B.BF16), ("N", 256), ("K", 256), ("bits", 3), ("group", 128),
+                                           ("codes", FAKE), ("s", FAKE), ("z", FAKE), ("stream", None)]])
+    assert sq(w=None) == B.ERR_NULL and sq(codes=None) == B.ERR_NULL and sq(s=None) == B.ERR_NULL and sq(z=None) == B.ERR_NULL
+    assert sq(bits=4) == B.ERR_UNSUPPORTED and sq(group=64) == B.ERR_UNSUPPORTED and sq(dt=7) == B.ERR_UNSUPPORTED
+    assert sq(K=200) == B.ERR_SHAPE and sq(N=0) == B.ERR_SHAPE
+    assert sq(w=FAKE + 2) == B.ERR_ALIGN and sq(z=FAKE + 8) == B.ERR_ALIGN
+    vq = lambda **kw: L.rwkvq_vq_assign(*[kw.get(k, v) for k, v in
+                                          [("w", FAKE), ("dt", B.F32), ("cb", FAKE), ("N", 256), ("K", 512), ("vdim", 2),
+                                           ("kbits", 6), ("br", 256), ("bc", 256), ("idx", FAKE), ("stream", None)]])
+    assert vq(w=None) == B.ERR_NULL and vq(cb=None) == B.ERR_NULL and vq(idx=None) == B.ERR_NULL
+    assert vq(vdim=4) == B.ERR_UNSUPPORTED and vq(kbits=7) == B.ERR_UNSUPPORTED and vq(br=128) == B.ERR_UNSUPPORTED
+    assert vq(N=300) == B.ERR_SHAPE and vq(K=128) == B.ERR_SHAPE
+    assert vq(idx=FAKE + 4) == B.ERR_ALIGN

@@ -1,0 +1,93 @@
+"""GPU parity of the encoders against the encoder oracle: integer outputs (codes, indices) and the
+fp16 scales / zero points bit for bit; and the loop dense weights -> encode -> prepack -> GEMV."""
+import numpy as np
+import pytest
+
+from oracle import encode_oracle as E
+from oracle import rwkvq_oracle as orc
+from paper_2505_03803_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a, dtype):
+    import torch
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def dense(rng, N, K, dtype, **kw):
+    """(what the GPU gets, the same values widened to float32 for the oracle)"""
+    if dtype == "f32":
+        w = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+        return w, w
+    bits = synth.gen_dense_weights(rng, N, K, dtype, **kw)
+    wide = bits.view(np.float16).astype(np.float32) if dtype == "f16" else (bits.astype(np.uint32) << 16).view(np.float32)
+    return bits, wide
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("N,K", [(1, 128), (5, 384), (256, 1024), (1000, 4096)])
+def test_sq_encode_bit_exact(dtype, N, K):
+    from paper_2505_03803_amd import binding as B
+    print(f"sq_encode {dtype} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(N + K)
+    w, wide = dense(rng, N, K, dtype, outlier_fraction=1e-3)
+    if N >= 5:
+        wide = wide.copy(); w = w.copy()
+        wide[1, :128] = wide[1, 0]                          # a constant group
+        w[1, :128] = w[1, 0]
+    dm = B.sq_encode(dev(w, dtype), B.DTYPES[dtype])
+    codes, s16, z16 = E.sq_encode_packed(wide)
+    assert np.array_equal(dm.scales.cpu().numpy().view(np.uint16), s16)
+    assert np.array_equal(dm.zeros.cpu().numpy().view(np.uint16), z16)
+    assert np.array_equal(dm.codes.cpu().numpy().view(np.uint32), codes)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("kbits,N,K", [(6, 256, 256), (6, 512, 768), (8, 256, 512)])
+def test_vq_assign_bit_exact(dtype, kbits, N, K):
+    from paper_2505_03803_amd import binding as B
+    print(f"vq_assign {dtype} k={kbits} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(kbits * 1000 + N + K)
+    w, wide = dense(rng, N, K, dtype)
+    cb = (rng.standard_normal((N // 256, K // 256, 2 ** kbits, 2)) * 0.02).astype(np.float16).view(np.uint16)
+    cb[0, 0, 5] = cb[0, 0, 3]                               # a duplicate entry: ties go to index 3
+    dm = B.vq_assign(dev(w, dtype), B.DTYPES[dtype], dev(cb, "f16"), kbits)
+    want = E.vq_assign_packed(wide, cb, kbits)
+    assert np.array_equal(dm.codes.cpu().numpy().view(np.uint32), want)
+
+
+def test_encode_then_multiply():
+    """Dense weights -> GPU encoders -> prepack -> decode GEMV, against the oracle run on the
+    oracle's own encoding of the same weights (the two encodings are bit-identical, see above)."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    from tests import gpu_util as G
+    rng = np.random.default_rng(77)
+    N, K = 512, 1024
+    w, wide = dense(rng, N, K, "bf16")
+    x = synth.gen_activations(rng, 1, K, "f16")
+    # SQ
+    dm = B.sq_encode(dev(w, "bf16"), B.BF16)
+    cn = torch.empty_like(dm.codes); sz = torch.empty(dm.scales.numel() * 2, dtype=torch.int16, device="cuda")
+    B.rwkvq_sq_prepack(dm.codes, dm.scales, dm.zeros, N, K, 3, 128, cn, sz)
+    nat = B.DeviceMatrix(B.SQ, B.NATIVE, N, K, 0, cn, sz, None, None, 0)
+    y = G.gpu_gemm(nat, x, "f16")
+    codes, s16, z16 = E.sq_encode_packed(wide)
+    mat = synth.QMatrix("enc", "sq", N, K, 0, codes, s16, z16, None)
+    G.check_outputs(y, mat, x, "f16", fed=None, tight=2e-5)
+    # the quantization error itself: each weight within half a step of its reconstruction
+    What = orc.dequant(mat)
+    step = np.repeat(s16.view(np.float16).astype(np.float64), 128, axis=1)
+    assert np.all(np.abs(wide - What) <= 0.51 * step)
+    # VQ
+    cb = (rng.standard_normal((N // 256, K // 256, 64, 2)) * 0.02).astype(np.float16).view(np.uint16)
+    dv = B.vq_assign(dev(w, "bf16"), B.BF16, dev(cb, "f16"), 6)
+    vn = torch.empty_like(dv.codes)
+    B.rwkvq_vq_prepack(dv.codes, N, K, 2, 6, vn)
+    natv = B.DeviceMatrix(B.VQ, B.NATIVE, N, K, 6, vn, None, None, dv.codebooks, 0)
+    yv = G.gpu_gemm(natv, x, "f16")
+    matv = synth.QMatrix("enc", "vq", N, K, 6, E.vq_assign_packed(wide, cb, 6), None, None, cb)
+    G.check_outputs(yv, matv, x, "f16", fed=None, tight=2e-5)
