@@ -124,7 +124,8 @@ def main():
     ap.add_argument("--prefill-steps", type=int, default=3)
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--skip-proxy", action="store_true")
+    ap.add_argument("--skip-proxy", action="store_true", help="skip the proxy and encoder legs")
+    ap.add_argument("--skip-encode", action="store_true")
     ap.add_argument("--proxy-layers", type=int, default=8, help="layers of dense bf16 weights the proxy leg scans per call")
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -248,6 +249,48 @@ def main():
                 k += 1
             out["proxy"]["cpu_baseline"] = {"value": nb / secs / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
                                             "sample": "first %d of the %d matrices (%d dense bytes in %.2f s)" % (k, n, nb, secs)}
+        # ---------------- encoder leg: the same dense matrices -> SQ codes, and -> 6-bit VQ indices
+        if not args.skip_encode:
+            Nmax = max(a * b for a, b in shapes)
+            codes = torch.empty(Nmax * 3 // 32, dtype=torch.int32, device="cuda")
+            sc = torch.empty(Nmax // 128, dtype=torch.int16, device="cuda")
+            zr = torch.empty_like(sc)
+            idx = torch.empty(Nmax // 2 * 6 // 32, dtype=torch.int32, device="cuda")
+            cbs = (torch.randn(Nmax // 65536 * 64 * 2, device="cuda", generator=gen) * 0.02).to(torch.float16).view(torch.int16)
+
+            def run_sq():
+                for m, (N_, K_) in zip(mats, shapes):
+                    B.rwkvq_sq_encode(m, B.BF16, N_, K_, 3, 128, codes, sc, zr)
+
+            def run_vq():
+                for m, (N_, K_) in zip(mats, shapes):
+                    B.rwkvq_vq_assign(m, B.BF16, cbs, N_, K_, 2, 6, 256, 256, idx)
+
+            st, _, _ = time_steps(run_sq, 5, 1)
+            sms = st / 5
+            vt, _, _ = time_steps(run_vq, 3, 1)
+            vms = vt / 3
+            nw = sum(a * b for a, b in shapes)
+            sq_bytes = nw * 2 + nw * 3 // 8 + nw // 128 * 4          # dense in, codes + scale + zero out
+            vq_flop = (nw // 2) * 64 * 5                             # 2 sub, 2 mul, 1 add per pair and entry
+            out["encode"] = {
+                "sq": {"value": sq_bytes / (sms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": sms, "dtype": "f32",
+                       "bytes_per_step": sq_bytes},
+                "vq6": {"value": vq_flop / (vms * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": vms, "dtype": "f32",
+                        "flop_per_step": vq_flop},
+                "workload": "the proxy leg's %d dense bf16 matrices: round-to-nearest SQ (3 bit, g128) and "
+                            "nearest-entry assignment to 64-entry codebooks" % n}
+            out["roofline_sq_encode"] = {"kernel": "rwkvq::sq_encode_kernel", "bound": "hbm",
+                                         "achieved": sq_bytes / (sms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": sq_bytes / (sms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                         "avg_launch_ms": sms / n}
+            out["roofline_vq_assign"] = {"kernel": "rwkvq::vq_assign_kernel<6>", "bound": "alu",
+                                         "achieved": vq_flop / (vms * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                                         "frac": vq_flop / (vms * 1e-3) / 1e12 / 157.3, "traffic": None,
+                                         "avg_launch_ms": vms / n,
+                                         "note": "no step of the distance is a fused multiply-add (each is rounded "
+                                                 "separately), so the reachable rate is half the FMA-counted peak"}
+            del codes, sc, zr, idx, cbs
         del mats, table, wsp, pout, pphi
         torch.cuda.empty_cache()
 
