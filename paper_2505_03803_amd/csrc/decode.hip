@@ -82,28 +82,6 @@ __device__ __forceinline__ half8_t sq_operand(uint32_t w0, uint32_t w1, uint32_t
     return __builtin_bit_cast(half8_t, v);
 }
 
-template <int P>
-__device__ __forceinline__ uint32_t vq6_addr(uint32_t w0, uint32_t w1, uint32_t w2) {
-    // byte address (index * 4) of codebook entry P for ds_bpermute
-    if constexpr (P < 15) {
-        constexpr int p = P % 5;
-        uint32_t w = (P / 5 == 0) ? w0 : (P / 5 == 1) ? w1 : w2;
-        return (w >> (6 * p)) & 0xFCu;
-    } else {
-        return ((w0 & 3u) << 2) | ((w1 & 3u) << 4) | ((w2 & 3u) << 6);
-    }
-}
-
-template <int T>
-__device__ __forceinline__ half8_t vq6_operand(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t cb) {
-    uint4_t v;
-    v.x = __builtin_amdgcn_ds_bpermute(vq6_addr<4 * T + 0>(w0, w1, w2), cb);
-    v.y = __builtin_amdgcn_ds_bpermute(vq6_addr<4 * T + 1>(w0, w1, w2), cb);
-    v.z = __builtin_amdgcn_ds_bpermute(vq6_addr<4 * T + 2>(w0, w1, w2), cb);
-    v.w = __builtin_amdgcn_ds_bpermute(vq6_addr<4 * T + 3>(w0, w1, w2), cb);
-    return __builtin_bit_cast(half8_t, v);
-}
-
 __device__ __forceinline__ half8_t vq8_operand(uint32_t w, const uint32_t* cb) {
     uint4_t v = {cb[w & 255u], cb[(w >> 8) & 255u], cb[(w >> 16) & 255u], cb[w >> 24]};
     return __builtin_bit_cast(half8_t, v);
@@ -119,15 +97,17 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int MT>
-struct XRegs { uint2_t v[MT]; };
+// Batch 2..16: the activation tile [MT rows][256 columns] of a column tile is shared by the four
+// wavefronts of the workgroup.  Thread t fetches 16 columns of row t / 16 (rows beyond M repeat row
+// M - 1: every load is unconditional, see tile_pipeline) and later stores them, converted to fp16,
+// into one of two LDS buffers.
+struct XShared { uint4_t a, b; };
 
-template <int MT>
-__device__ __forceinline__ void x_load(XRegs<MT>& r, const uint16_t* x, int M, int K, int T, int lane) {
-    const uint16_t* xt = x + 256 * T;             // uniform part of the address
-    // rows beyond M repeat row M-1: every load is unconditional (see tile_pipeline)
-#pragma unroll
-    for (int m = 0; m < MT; ++m) r.v[m] = *(const uint2_t*)(xt + (size_t)(m < M ? m : M - 1) * K + 4 * lane);
+__device__ __forceinline__ void x_load_wg(XShared& r, const uint16_t* x, int M, int K, int T, int tid) {
+    const int row = (tid >> 4) < M ? (tid >> 4) : M - 1;
+    const uint16_t* p = x + (size_t)row * K + 256 * T + 16 * (tid & 15);
+    r.a = *(const uint4_t*)p;
+    r.b = *(const uint4_t*)(p + 8);
 }
 
 __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
@@ -137,12 +117,16 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
 }
 
 template <int MT>
-__device__ __forceinline__ void x_store(const XRegs<MT>& r, half_t* xs, int lane, bool bf16) {
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        uint2_t v = r.v[m];
-        if (bf16) { v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y); }
-        *(uint2_t*)(xs + m * kXStride + 4 * lane) = v;
+__device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, int tid, bool bf16) {
+    if ((tid >> 4) < MT) {
+        uint4_t a = r.a, b = r.b;
+        if (bf16) {
+            a.x = bf16x2_to_f16x2(a.x); a.y = bf16x2_to_f16x2(a.y); a.z = bf16x2_to_f16x2(a.z); a.w = bf16x2_to_f16x2(a.w);
+            b.x = bf16x2_to_f16x2(b.x); b.y = bf16x2_to_f16x2(b.y); b.z = bf16x2_to_f16x2(b.z); b.w = bf16x2_to_f16x2(b.w);
+        }
+        half_t* d = xs + (tid >> 4) * kXStride + 16 * (tid & 15);
+        *(uint4_t*)d = a;
+        *(uint4_t*)(d + 8) = b;
     }
 }
 
@@ -158,14 +142,8 @@ __device__ __forceinline__ float dpp_add(float v) {
     return v + __builtin_bit_cast(float, o);
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
 
 // ---- per-format tile loops ------------------------------------------------------------------
-template <int MT> struct Acc { static constexpr int n = MT == 1 ? 1 : 4; };
 
 #define RWKVQ_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (c), 0, 0, 0)
 
@@ -213,172 +191,6 @@ __device__ __forceinline__ void tile_pipeline(int KT, Load load, Compute compute
     }
 }
 
-template <int MT> struct SqRegs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XRegs<MT> x; };
-template <int MT> struct Vq6Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XRegs<MT> x; };
-template <int MT> struct Vq8Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XRegs<MT> x; };
-
-// Everything a tile loop needs about its wavefront's position; R0, R1 are the two row tiles
-// (R1 == R0 when the matrix has an odd number of row tiles and this is the last wavefront).
-struct WavePos { int R[2], M, lane; bool xbf16; };
-
-template <int MT, int DEPTH>
-__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, const float* xsumX,
-                                       const float* xsum8, float4_t (&out)[kRT]) {
-    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
-    const uint2_t* sz[2] = {(const uint2_t*)mt.aux + (size_t)wp.R[0] * KT * 16,
-                            (const uint2_t*)mt.aux + (size_t)wp.R[1] * KT * 16};
-    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    const int mrow = MT == 16 ? 4 * (lane >> 4) : 0;      // first batch row this lane accumulates
-    // The and-or that builds 8 + q takes its mask from a VGPR and the fp16 pattern of 8.0 from an
-    // SGPR: a VOP3 instruction of this ISA takes no literal and at most one scalar operand.
-    uint32_t mask, magic;
-    asm("v_mov_b32 %0, 0x03800380" : "=v"(mask));
-    asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
-    auto load = [&](SqRegs<MT>& r, int T) {
-#pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 384;
-            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
-            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
-            r.sz[rt] = (sz[rt] + (size_t)T * 16)[lane & 15];
-        }
-        x_load<MT>(r.x, (const uint16_t*)mt.x, M, mt.K, T, lane);
-    };
-    auto compute = [&](const SqRegs<MT>& r, int T) {
-        wave_lds_sync();
-        x_store<MT>(r.x, xs, lane, wp.xbf16);
-        wave_lds_sync();
-        // All LDS reads of the tile are issued first; their latency is covered by the unpack work.
-        half8_t xa[2][4];
-        float4_t c8[2], cx[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int g = 2 * T + u;
-            c8[u] = *(const float4_t*)(xsum8 + g * MT + mrow);
-            cx[u] = *(const float4_t*)(xsumX + g * MT + mrow);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
-                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
-                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
-                float4_t acc = c8[u];
-                acc = RWKVQ_MFMA(xa[u][0], sq_operand<0>(w0, w1, w2, mask, magic), acc);
-                acc = RWKVQ_MFMA(xa[u][1], sq_operand<1>(w0, w1, w2, mask, magic), acc);
-                acc = RWKVQ_MFMA(xa[u][2], sq_operand<2>(w0, w1, w2, mask, magic), acc);
-                acc = RWKVQ_MFMA(xa[u][3], sq_operand<3>(w0, w1, w2, mask, magic), acc);
-                const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
-                const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
-                const float z = f16_bits_to_f32((uint16_t)(szw >> 16));
-#pragma unroll
-                for (int i = 0; i < Acc<MT>::n; ++i) out[rt][i] = fmaf(s, fmaf(-z, cx[u][i], acc[i]), out[rt][i]);
-            }
-        }
-    };
-    tile_pipeline<DEPTH, SqRegs<MT>>(KT, load, compute);
-}
-
-template <int MT, int DEPTH>
-__device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float4_t (&out)[kRT]) {
-    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
-    const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
-    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    auto load = [&](Vq6Regs<MT>& r, int T) {
-#pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 384;
-            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
-            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
-        }
-        r.cb = (cbs + (size_t)T * 64)[lane];
-        x_load<MT>(r.x, (const uint16_t*)mt.x, M, mt.K, T, lane);
-    };
-    auto compute = [&](const Vq6Regs<MT>& r, int) {
-        wave_lds_sync();
-        x_store<MT>(r.x, xs, lane, wp.xbf16);
-        wave_lds_sync();
-        half8_t xa[2][4];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
-                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
-                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
-                out[rt] = RWKVQ_MFMA(xa[u][0], vq6_operand<0>(w0, w1, w2, r.cb), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa[u][1], vq6_operand<1>(w0, w1, w2, r.cb), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa[u][2], vq6_operand<2>(w0, w1, w2, r.cb), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa[u][3], vq6_operand<3>(w0, w1, w2, r.cb), out[rt]);
-            }
-        }
-    };
-    tile_pipeline<DEPTH, Vq6Regs<MT>>(KT, load, compute);
-}
-
-template <int MT, int DEPTH>
-__device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                        float4_t (&out)[kRT]) {
-    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 512, mt.codes + (size_t)wp.R[1] * KT * 512};
-    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
-    const half_t* xrow = xs + ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    auto load = [&](Vq8Regs<MT>& r, int T) {
-#pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 512;
-            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
-            r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
-        }
-        r.cb = (cbs + (size_t)T * 64)[lane];
-        x_load<MT>(r.x, (const uint16_t*)mt.x, M, mt.K, T, lane);
-    };
-    auto compute = [&](const Vq8Regs<MT>& r, int) {
-        wave_lds_sync();
-        x_store<MT>(r.x, xs, lane, wp.xbf16);
-        *(uint4_t*)(cb_lds + 4 * lane) = r.cb;
-        wave_lds_sync();
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const half8_t xa0 = *(const half8_t*)(xrow + 128 * u + 0);
-            const half8_t xa1 = *(const half8_t*)(xrow + 128 * u + 32);
-            const half8_t xa2 = *(const half8_t*)(xrow + 128 * u + 64);
-            const half8_t xa3 = *(const half8_t*)(xrow + 128 * u + 96);
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
-                const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
-                out[rt] = RWKVQ_MFMA(xa0, vq8_operand(w.x, cb_lds), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa1, vq8_operand(w.y, cb_lds), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa2, vq8_operand(w.z, cb_lds), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa3, vq8_operand(w.w, cb_lds), out[rt]);
-            }
-        }
-    };
-    tile_pipeline<DEPTH, Vq8Regs<MT>>(KT, load, compute);
-}
-
-// ------------------------------------------------------------------------------------------
-// Batch 1 (GEMV proper).  Same streaming structure and native layout, but the contraction is
-// done by the vector ALU (v_dot2c_f32_f16: two multiply-adds per lane, binary32 accumulate):
-// with a single activation row fifteen sixteenths of every MFMA would be spent on padding, and
-// the padded MFMA costs the same issue time as the dot products.  Lane (r, kg) accumulates the part
-// of row r's dot product that falls on its own columns; the four kg lanes of a row are summed at
-// the end.  The activations are not staged in LDS: lane (kg, i) loads pair i of the sixteen
-// column pairs that column group kg multiplies in a unit, and each dot product names the lane of
-// its row that holds its pair (DPP row broadcast).
-//   SQ:  the codes are multiplied in place as fp16 subnormals; per group
-//        y += s * (sum q x - z * Xp), Xp = the sum of the lane's own activations of the group.
-//   VQ:  the codebook of the current block sits in a wavefront-private LDS region; each pair of
-//        weights is one ds_read_b32 gather feeding one dot2.
-
 template <int P>
 __device__ __forceinline__ uint32_t vq6_lds_addr(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t m, uint32_t base) {
     // LDS byte address of codebook entry P: (index * 4) | base, base aligned to 256 bytes
@@ -399,6 +211,190 @@ __device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_
                  lds_gather(vq6_lds_addr<4 * T4 + 2>(w0, w1, w2, m, base)), lds_gather(vq6_lds_addr<4 * T4 + 3>(w0, w1, w2, m, base))};
     return v;
 }
+
+struct SqRegs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XShared x; };
+struct Vq6Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XShared x; };
+struct Vq8Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XShared x; };
+
+// Everything a tile loop needs about its wavefront's position; R0, R1 are the two row tiles
+// (R1 == R0 when the matrix has an odd number of row tiles and this is the last wavefront).
+struct WavePos { int R[2], M, lane, tid; bool xbf16; };
+
+// Batch 2..16 on the matrix cores: activations = A operand (row m of the MFMA = batch row m, read
+// from the shared LDS tile), weights = B operand.  `xs` points at the two activation buffers; the
+// one workgroup barrier per tile both publishes tile T and guards the buffer tile T + 1 will
+// overwrite (every wavefront has finished reading it once it has passed the barrier of tile T).
+//
+// SQ: the codes enter as 8 + q (one shift and one and-or per pair).  The group sums of the
+// activations come from the matrix cores too: one more MFMA per k-step with an all-ones B operand
+// leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float4_t (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
+    const uint2_t* sz[2] = {(const uint2_t*)mt.aux + (size_t)wp.R[0] * KT * 16,
+                            (const uint2_t*)mt.aux + (size_t)wp.R[1] * KT * 16};
+    const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    // The and-or that builds 8 + q takes its mask from a VGPR and the fp16 pattern of 8.0 from an
+    // SGPR: a VOP3 instruction of this ISA takes no literal and at most one scalar operand.
+    uint32_t mask, magic;
+    asm("v_mov_b32 %0, 0x03800380" : "=v"(mask));
+    asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
+    const uint4_t ones4 = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
+    const half8_t ones = __builtin_bit_cast(half8_t, ones4);
+    auto load = [&](SqRegs& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
+            r.sz[rt] = (sz[rt] + (size_t)T * 16)[lane & 15];
+        }
+        x_load_wg(r.x, (const uint16_t*)mt.x, M, mt.K, T, wp.tid);
+    };
+    auto compute = [&](const SqRegs& r, int T) {
+        half_t* buf = xs + (T & 1) * (MT * kXStride);
+        x_store_wg<MT>(r.x, buf, wp.tid, wp.xbf16);
+        __syncthreads();
+        const half_t* xrow = buf + xoff;
+        half8_t xa[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            float4_t X = {0, 0, 0, 0};               // X_g[m] for the lane's batch rows
+#pragma unroll
+            for (int t = 0; t < 4; ++t) X = RWKVQ_MFMA(xa[u][t], ones, X);
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                float4_t acc = {0, 0, 0, 0};
+                acc = RWKVQ_MFMA(xa[u][0], sq_operand<0>(w0, w1, w2, mask, magic), acc);
+                acc = RWKVQ_MFMA(xa[u][1], sq_operand<1>(w0, w1, w2, mask, magic), acc);
+                acc = RWKVQ_MFMA(xa[u][2], sq_operand<2>(w0, w1, w2, mask, magic), acc);
+                acc = RWKVQ_MFMA(xa[u][3], sq_operand<3>(w0, w1, w2, mask, magic), acc);
+                const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
+                const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
+                const float z8 = f16_bits_to_f32((uint16_t)(szw >> 16)) + 8.0f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) out[rt][i] = fmaf(s, fmaf(-z8, X[i], acc[i]), out[rt][i]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, SqRegs>(KT, load, compute);
+}
+
+// 6-bit VQ: the codebook of a tile (64 entries, one per lane) goes through a wavefront-private LDS
+// slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+                                        float4_t (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
+    const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
+    const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    const uint32_t base0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
+    uint32_t m;
+    asm("v_mov_b32 %0, 0xfc" : "=v"(m));
+    auto load = [&](Vq6Regs& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
+        }
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        x_load_wg(r.x, (const uint16_t*)mt.x, M, mt.K, T, wp.tid);
+    };
+    auto compute = [&](const Vq6Regs& r, int T) {
+        half_t* buf = xs + (T & 1) * (MT * kXStride);
+        x_store_wg<MT>(r.x, buf, wp.tid, wp.xbf16);
+        cb_lds[(T & 1) * 256 + lane] = r.cb;         // two slots, 1 KB apart (the gather address ORs the index in)
+        __syncthreads();
+        const uint32_t base = base0 + (T & 1) * 1024;
+        const half_t* xrow = buf + xoff;
+        half8_t xa[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                out[rt] = RWKVQ_MFMA(xa[u][0], __builtin_bit_cast(half8_t, vq6_gather4<0>(w0, w1, w2, m, base)), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa[u][1], __builtin_bit_cast(half8_t, vq6_gather4<1>(w0, w1, w2, m, base)), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa[u][2], __builtin_bit_cast(half8_t, vq6_gather4<2>(w0, w1, w2, m, base)), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa[u][3], __builtin_bit_cast(half8_t, vq6_gather4<3>(w0, w1, w2, m, base)), out[rt]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, Vq6Regs>(KT, load, compute);
+}
+
+// 8-bit VQ: the codebook of a tile (256 entries) goes through a wavefront-private LDS region; the
+// workgroup barrier that publishes the activations also orders that store before the gathers.
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+                                        float4_t (&out)[kRT]) {
+    const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
+    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 512, mt.codes + (size_t)wp.R[1] * KT * 512};
+    const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
+    const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    auto load = [&](Vq8Regs& r, int T) {
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) {
+            const uint32_t* t = codes[rt] + (size_t)T * 512;
+            r.a[rt] = *(const uint4_t*)(t + 4 * lane);
+            r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
+        }
+        r.cb = (cbs + (size_t)T * 64)[lane];
+        x_load_wg(r.x, (const uint16_t*)mt.x, M, mt.K, T, wp.tid);
+    };
+    auto compute = [&](const Vq8Regs& r, int T) {
+        half_t* buf = xs + (T & 1) * (MT * kXStride);
+        uint32_t* cbuf = cb_lds + (T & 1) * 256;     // two codebook slots, like the activations
+        x_store_wg<MT>(r.x, buf, wp.tid, wp.xbf16);
+        *(uint4_t*)(cbuf + 4 * lane) = r.cb;
+        __syncthreads();
+        const half_t* xrow = buf + xoff;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const half8_t xa0 = *(const half8_t*)(xrow + 128 * u + 0);
+            const half8_t xa1 = *(const half8_t*)(xrow + 128 * u + 32);
+            const half8_t xa2 = *(const half8_t*)(xrow + 128 * u + 64);
+            const half8_t xa3 = *(const half8_t*)(xrow + 128 * u + 96);
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
+                out[rt] = RWKVQ_MFMA(xa0, vq8_operand(w.x, cbuf), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa1, vq8_operand(w.y, cbuf), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa2, vq8_operand(w.z, cbuf), out[rt]);
+                out[rt] = RWKVQ_MFMA(xa3, vq8_operand(w.w, cbuf), out[rt]);
+            }
+        }
+    };
+    tile_pipeline<DEPTH, Vq8Regs>(KT, load, compute);
+}
+
+// ------------------------------------------------------------------------------------------
+// Batch 1 (GEMV proper).  Same streaming structure and native layout, but the contraction is
+// done by the vector ALU (v_dot2c_f32_f16: two multiply-adds per lane, binary32 accumulate):
+// with a single activation row fifteen sixteenths of every MFMA would be spent on padding, and
+// the padded MFMA costs the same issue time as the dot products.  Lane (r, kg) accumulates the part
+// of row r's dot product that falls on its own columns; the four kg lanes of a row are summed at
+// the end.  The activations are not staged in LDS: lane (kg, i) loads pair i of the sixteen
+// column pairs that column group kg multiplies in a unit, and each dot product names the lane of
+// its row that holds its pair (DPP row broadcast).
+//   SQ:  the codes are multiplied in place as fp16 subnormals; per group
+//        y += s * (sum q x - z * Xp), Xp = the sum of the lane's own activations of the group.
+//   VQ:  the codebook of the current block sits in a wavefront-private LDS region; each pair of
+//        weights is one ds_read_b32 gather feeding one dot2.
 
 // acc += w . x, where x is the fp16 pair that lane N of the 16-lane row holds in xp (DPP
 // row_newbcast): the sixteen rows' lanes of a column group all multiply by the same activations,
@@ -625,12 +621,11 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
 // (its unpack is the cheapest per weight) while the VQ matrices use the vector-ALU path above,
 // whose LDS gathers are cheaper than ds_bpermute.
 template <int MT>
-__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : 1) decode_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : 2) decode_kernel(DecodeArgs a) {
     constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : 2;
-    __shared__ __attribute__((aligned(16))) half_t xs_all[4][MT * kXStride];
-    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[4][256];
-    __shared__ __attribute__((aligned(16))) float xsumX[kDecodeMaxK / kGroup * MT];
-    __shared__ __attribute__((aligned(16))) float xsum8[kDecodeMaxK / kGroup * MT];
+    // batch > 1: two activation tiles shared by the workgroup; codebook slots per wavefront
+    __shared__ __attribute__((aligned(16))) half_t xs[MT == 1 ? 8 : 2 * MT * kXStride];
+    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[4][MT == 1 ? 256 : 512];
 
     // Which matrix does this workgroup belong to?  Lane i compares against the end of matrix i
     // (one load per wavefront from the argument block); the count of matrices that end at or
@@ -644,29 +639,15 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     const int M = a.M;
     const bool xbf16 = a.xdt == DT_BF16;
 
-    if (MT != 1 && mt.fmt == FMT_SQ3) {
-        // Prologue: X[g][m] = sum of the activations of group g (as the fp16 values the MFMA
-        // will see), and -8 X, for every group of the matrix; wavefronts take groups round-robin.
-        const int G = mt.K / kGroup;
-        for (int g = wave; g < G; g += 4)
-            for (int m = 0; m < M; ++m) {
-                uint32_t v = *(const uint32_t*)((const uint16_t*)mt.x + (size_t)m * mt.K + kGroup * g + 2 * lane);
-                if (xbf16) v = bf16x2_to_f16x2(v);
-                half2_t h = __builtin_bit_cast(half2_t, v);
-                float sum = wave_sum((float)h.x + (float)h.y);
-                if (lane == 0) { xsumX[g * MT + m] = sum; xsum8[g * MT + m] = -8.0f * sum; }
-            }
-        __syncthreads();
-    }
-
     const int NR = mt.N >> 4;
     WavePos wp;
     wp.R[0] = kRT * (4 * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
-    if (wp.R[0] >= NR) return;                     // rows beyond N (N not a multiple of kWgRows)
-    wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
-    wp.M = M; wp.lane = lane; wp.xbf16 = xbf16;
+    const bool live = wp.R[0] < NR;                // rows beyond N (N not a multiple of kWgRows)
+    wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xbf16;
 
     if constexpr (MT == 1) {
+        if (!live) return;
+        wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
         float part[kRT];
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) part[rt] = 0.f;
@@ -681,33 +662,30 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
             v += __shfl_xor(v, 32, 64);
             if (lane < 16) store_from_f32(mt.y, (size_t)16 * wp.R[rt] + lane, a.ydt, v);
         }
-        return;
     } else {
-
-    float4_t out[kRT];
+        // every wavefront takes part in the shared activation tiles and their barriers; one
+        // beyond the last row tile works on the last tile again and stores nothing
+        if (!live) wp.R[0] = NR - 1;
+        wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
+        float4_t out[kRT];
 #pragma unroll
-    for (int rt = 0; rt < kRT; ++rt) out[rt] = float4_t{0, 0, 0, 0};
-    if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH>(mt, wp, xs_all[wave], xsumX, xsum8, out);
-    else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH>(mt, wp, xs_all[wave], out);
-    else run_vq8<MT, DEPTH>(mt, wp, xs_all[wave], cb_all[wave], out);
-
+        for (int rt = 0; rt < kRT; ++rt) out[rt] = float4_t{0, 0, 0, 0};
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH>(mt, wp, xs, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
+        else run_vq8<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
+        if (!live) return;
+        // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 of output column n
 #pragma unroll
-    for (int rt = 0; rt < kRT; ++rt) {
-        if (rt == 1 && wp.R[1] == wp.R[0]) break;
-        const int n = 16 * wp.R[rt] + (lane & 15);
-        if (MT == 16) {
+        for (int rt = 0; rt < kRT; ++rt) {
+            if (rt == 1 && wp.R[1] == wp.R[0]) break;
+            const int n = 16 * wp.R[rt] + (lane & 15);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int m = 4 * (lane >> 4) + i;
                 if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, out[rt][i]);
             }
-        } else if (lane < 16) {
-#pragma unroll
-            for (int i = 0; i < Acc<MT>::n; ++i)
-                if (i < M) store_from_f32(mt.y, (size_t)i * mt.N + n, a.ydt, out[rt][i]);
         }
     }
-    }   // MT > 1
 }
 
 hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
