@@ -238,11 +238,106 @@ __device__ __forceinline__ void w_unpack(const WRegs<FMT>& r, char* wt, const ui
     }
 }
 
+// The same work cut into 128 micro-slices, one per MFMA of the previous k-step (see mma_step): a
+// weight pair takes four of them (mask / address; subtract the zero point or start the look-up;
+// scale; pack and, every fourth pair, store the finished 16-byte chunk).  Micro-slice S works on
+// pair (S / 4) % 4 of chunk (S / 16) % 2 of row tile S / 32.  Each is two or three vector
+// instructions: what the matrix core leaves room for behind one MFMA of the same wavefront.
+template <int FMT> struct UnpackState {
+    char *d0, *d1;            // LDS addresses of the lane's two chunks of row tile 0
+    uint4_t stage;            // the chunk being assembled
+    float s, z;               // SQ: scale and zero point of the current row tile and unit
+    float lo, hi;             // SQ: the pair in flight
+    uint32_t m;               // masked codes / look-up address / looked-up pair in flight
+    uint32_t cb;              // VQ6: the lane's codebook entry, converted to the operand type
+};
+
+template <bool BF16, int FMT>
+__device__ __forceinline__ void unpack_begin(UnpackState<FMT>& st, const WRegs<FMT>& r, char* wt, int wave, int lane) {
+    const int row0 = 64 * wave + (lane & 15), kg = lane >> 4;
+    st.d0 = wt + tile_off(row0, kg);
+    st.d1 = wt + tile_off(row0, 4 + kg);
+    if constexpr (FMT == FMT_VQ6) st.cb = Elem<BF16>::from_f16x2(r.cb);
+}
+
+// The SQ pair P as masked in-place codes (fp16 subnormals q * 2^(b-24)) and the power of two that
+// undoes the position (see sq_pair_deq).
+template <int P>
+__device__ __forceinline__ uint32_t sq_pair_mask(uint32_t w0, uint32_t w1, uint32_t w2) {
+    if constexpr (P < 15) {
+        constexpr int p = P % 5;
+        const uint32_t w = (P / 5 == 0) ? w0 : (P / 5 == 1) ? w1 : w2;
+        if constexpr (p == 0) return w & 0x000E000Eu;
+        else if constexpr (p == 1) return w & 0x00700070u;
+        else if constexpr (p == 2) return w & 0x03800380u;
+        else if constexpr (p == 3) return (w >> 9) & 0x000E000Eu;
+        else return (w >> 9) & 0x00700070u;
+    } else {
+        return (w0 & 0x00010001u) | ((w1 & 0x00010001u) << 1) | ((w2 & 0x00010001u) << 2);
+    }
+}
+template <int P> constexpr float sq_pair_unscale() {
+    return P == 15 ? 16777216.f : (P % 5 == 0 || P % 5 == 3) ? 8388608.f : (P % 5 == 1 || P % 5 == 4) ? 1048576.f : 131072.f;
+}
+
+template <bool BF16, int FMT, int KQ, int S>
+__device__ __forceinline__ void unpack_micro(UnpackState<FMT>& st, const WRegs<FMT>& r, const uint32_t* cb8) {
+    constexpr int u = KQ >> 1, t0 = 2 * (KQ & 1);
+    constexpr int i = S >> 5, c = (S >> 4) & 1, p = (S >> 2) & 3, q = S & 3, P = 4 * (t0 + c) + p;
+    if constexpr (FMT == FMT_SQ3) {
+        const uint32_t w0 = u == 0 ? r.a[i].x : r.a[i].w, w1 = u == 0 ? r.a[i].y : r.b[i].x,
+                       w2 = u == 0 ? r.a[i].z : r.b[i].y;
+        if constexpr (q == 0) {
+            if constexpr ((S & 31) == 0) {
+                const uint32_t szw = u == 0 ? r.sz[i].x : r.sz[i].y;
+                st.s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
+                st.z = f16_bits_to_f32((uint16_t)(szw >> 16));
+            }
+            st.m = sq_pair_mask<P>(w0, w1, w2);
+        } else if constexpr (q == 1) {
+            const half2_t h = __builtin_bit_cast(half2_t, st.m);
+            st.lo = fmaf((float)h.x, sq_pair_unscale<P>(), -st.z);
+            st.hi = fmaf((float)h.y, sq_pair_unscale<P>(), -st.z);
+        } else if constexpr (q == 2) {
+            st.lo = __fmul_rn(st.lo, st.s);
+            st.hi = __fmul_rn(st.hi, st.s);
+        } else {
+            st.m = Elem<BF16>::pack(st.lo, st.hi);
+        }
+    } else if constexpr (FMT == FMT_VQ6) {
+        const uint32_t w0 = u == 0 ? r.a[i].x : r.a[i].w, w1 = u == 0 ? r.a[i].y : r.b[i].x,
+                       w2 = u == 0 ? r.a[i].z : r.b[i].y;
+        if constexpr (q == 0) st.m = vq6_byteaddr<P>(w0, w1, w2);
+        else if constexpr (q == 1) st.m = __builtin_amdgcn_ds_bpermute(st.m, st.cb);
+    } else {
+        const uint32_t wa = u == 0 ? (t0 == 0 ? r.a[i].x : r.a[i].z) : (t0 == 0 ? r.b[i].x : r.b[i].z);
+        const uint32_t wb = u == 0 ? (t0 == 0 ? r.a[i].y : r.a[i].w) : (t0 == 0 ? r.b[i].y : r.b[i].w);
+        const uint32_t w = c == 0 ? wa : wb;
+        if constexpr (q == 0) st.m = (w >> (8 * p)) & 255u;
+        else if constexpr (q == 1) st.m = cb8[st.m];
+    }
+    if constexpr (q == 3) {
+        if constexpr (p == 0) st.stage.x = st.m;
+        else if constexpr (p == 1) st.stage.y = st.m;
+        else if constexpr (p == 2) st.stage.z = st.m;
+        else {
+            st.stage.w = st.m;
+            *(uint4_t*)((c == 0 ? st.d0 : st.d1) + 16 * i * kRowBytes) = st.stage;
+        }
+    }
+}
+
 // Copy the activation tile, columns k0..k0+63 of the block's 256 rows, into an LDS tile, 16 bytes
 // per lane and instruction, the load unit writing LDS directly.  LDS slot p (16 bytes) = row
 // p/8, position p%8; the lane that owns slot p fetches the logical chunk the swizzle stores there.
 // xoff[i] is the lane's byte offset (row * K * 2 + chunk * 16) from the tile's first row, computed
 // once; xk = activations of the tile's first row at column k0 (uniform).
+template <int I>
+__device__ __forceinline__ void x_tile_dma_one(const char* xk, const uint32_t (&xoff)[8], char* xt, int wave) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xk + xoff[I]),
+                                     (__attribute__((address_space(3))) void*)(xt + (256 * I + 64 * wave) * 16),
+                                     16, 0, 0);
+}
 __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff)[8], char* xt, int wave) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -258,11 +353,52 @@ __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff
 // the first LDS reads have been issued and `mid` between the halves: vector-ALU work placed
 // there (unpacking the next k-step) covers more latency.
 constexpr int kAhead = 3;
-template <bool BF16, class F0, class F1>
+template <int S> struct SliceTag { static constexpr int value = S; };
+
+template <bool BF16, int F, int NI, class Slice>
+__device__ __forceinline__ void mma_one(const uint4_t (&b)[8], const uint4_t af, float4_t (&acc)[8][8], Slice& slice) {
+    // One MFMA of x fragment F, then one micro-slice of vector-ALU work, fenced so that the
+    // instruction scheduler leaves it there: a wavefront issues in order, and only the two or
+    // three instructions placed right behind an MFMA run while the matrix core is busy with it
+    // (left alone, the scheduler gathers the unpack work into long runs before its stores, and
+    // the matrix core idles through them).
+    Elem<BF16>::mfma(b[NI], af, acc[F & 7][NI]);
+    __builtin_amdgcn_sched_barrier(0);
+    slice(SliceTag<8 * F + NI>{});
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (NI < 7) mma_one<BF16, F, NI + 1>(b, af, acc, slice);
+}
+template <bool BF16, int F, class Slice>
+__device__ __forceinline__ void mma_row(const uint4_t (&b)[8], const uint4_t af, float4_t (&acc)[8][8], Slice& slice) {
+    mma_one<BF16, F, 0>(b, af, acc, slice);
+}
+
+template <bool BF16, int F, class Slice>
+__device__ __forceinline__ void mma_rows(const char* const (&xa)[2], const char* wb1, uint4_t (&b)[8], uint4_t (&b1)[8],
+                                         uint4_t (&a)[kAhead + 1], float4_t (&acc)[8][8], Slice& slice) {
+    if constexpr (F < 16) {
+        if constexpr (F + kAhead < 16)
+            a[(F + kAhead) % (kAhead + 1)] = *(const uint4_t*)(xa[(F + kAhead) >> 3] + 16 * ((F + kAhead) & 7) * kRowBytes);
+        if constexpr (F >= 4 && F < 8) {
+            b1[2 * (F - 4)] = *(const uint4_t*)(wb1 + 16 * (2 * (F - 4)) * kRowBytes);
+            b1[2 * (F - 4) + 1] = *(const uint4_t*)(wb1 + 16 * (2 * (F - 4) + 1) * kRowBytes);
+        }
+        if constexpr (F < 8) mma_row<BF16, F>(b, a[F % (kAhead + 1)], acc, slice);
+        else mma_row<BF16, F>(b1, a[F % (kAhead + 1)], acc, slice);
+        mma_rows<BF16, F + 1>(xa, wb1, b, b1, a, acc, slice);
+    }
+}
+
+// One k-step (64 columns) of the wavefront tile = 16 rows of 8 MFMAs: x fragment f (f = 0..15:
+// m-subtile f%8 of column half f/8) against the eight W fragments of that half.  x fragments are
+// read kAhead rows ahead of their use and the W fragments of the second half during rows 4..7,
+// so that an LDS round trip is hidden behind several rows of MFMAs.  `slice(SliceTag<S>)`, S =
+// 0..127, is called after MFMA S: the unpacking of the next k-step goes there.
+template <bool BF16, class Slice>
 __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm, int wn, int lane,
-                                         float4_t (&acc)[8][8], F0 early, F1 mid) {
+                                         float4_t (&acc)[8][8], Slice slice) {
     const int r = lane & 15, kg = lane >> 4;
-    const char* xa[2] = {xt + tile_off(128 * wm + r, kg), xt + tile_off(128 * wm + r, 4 + kg)};
+    const char* const xa[2] = {xt + tile_off(128 * wm + r, kg), xt + tile_off(128 * wm + r, 4 + kg)};
     const char* wb0 = wt + tile_off(128 * wn + r, kg);
     const char* wb1 = wt + tile_off(128 * wn + r, 4 + kg);
     uint4_t b[8], b1[8], a[kAhead + 1];
@@ -270,20 +406,7 @@ __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm,
     for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb0 + 16 * ni * kRowBytes);
 #pragma unroll
     for (int f = 0; f < kAhead; ++f) a[f] = *(const uint4_t*)(xa[0] + 16 * f * kRowBytes);
-    early();
-#pragma unroll
-    for (int f = 0; f < 16; ++f) {
-        if (f == 8) mid();
-        if (f + kAhead < 16)
-            a[(f + kAhead) % (kAhead + 1)] = *(const uint4_t*)(xa[(f + kAhead) >> 3] + 16 * ((f + kAhead) & 7) * kRowBytes);
-        if (f >= 4 && f < 8) {
-            b1[2 * (f - 4)] = *(const uint4_t*)(wb1 + 16 * (2 * (f - 4)) * kRowBytes);
-            b1[2 * (f - 4) + 1] = *(const uint4_t*)(wb1 + 16 * (2 * (f - 4) + 1) * kRowBytes);
-        }
-        const uint4_t af = a[f % (kAhead + 1)];
-#pragma unroll
-        for (int ni = 0; ni < 8; ++ni) Elem<BF16>::mfma(f < 8 ? b[ni] : b1[ni], af, acc[f & 7][ni]);
-    }
+    mma_rows<BF16, 0>(xa, wb1, b, b1, a, acc, slice);
 }
 
 // Convert and stage the 8-bit-index codebook of a tile (256 entries) into LDS.
@@ -356,6 +479,7 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 
     // prologue: packed words of tile 0, k-step 0 (and 1) of the activations, k-step 0 of W
     WRegs<FMT> wr;
+    UnpackState<FMT> us;
     w_load<FMT>(wr, src, 0, lane);
     x_tile_dma(xk(0), xoff, xbase + x0, wave);
     if (LA == 2) x_tile_dma(xk(1), xoff, xbase + x1, wave);
@@ -371,27 +495,47 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     for (int T = 0; T < KT; ++T) {
         const int Tn = T + 1 < KT ? T + 1 : T;
         const int g = 4 * T;                               // k-step index of the tile's first step
-        // k-step 0 of the tile is in W buffer 0; steps 1..3 come from the same packed words.
-        x_tile_dma(xk(g + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
-        mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc,
-                       [&] { w_unpack<BF16, FMT, 1, 0, 2>(wr, wt1, CB8(T), wave, lane); },
-                       [&] { w_unpack<BF16, FMT, 1, 2, 4>(wr, wt1, CB8(T), wave, lane); });
+        // k-step 0 of the tile is in W buffer 0; steps 1..3 come from the same packed words and are
+        // unpacked, a few instructions at a time, behind the MFMAs of the step before; the eight
+        // copy instructions of the activation tile LA steps ahead go behind MFMAs as well.
+        {
+            const char* xsrc = xk(g + LA);
+            char* xdst = xbase + (LA == 2 ? x2 : x1);
+            unpack_begin<BF16, FMT>(us, wr, wt1, wave, lane);
+            mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc, [&](auto tag) {
+                constexpr int S = decltype(tag)::value;
+                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                unpack_micro<BF16, FMT, 1, S>(us, wr, CB8(T));
+            });
+        }
         wait_step();
         RWKVQ_BARRIER();
         rotate();
 
-        x_tile_dma(xk(g + 1 + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
-        mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc,
-                       [&] { w_unpack<BF16, FMT, 2, 0, 2>(wr, wt0, CB8(T), wave, lane); },
-                       [&] { w_unpack<BF16, FMT, 2, 2, 4>(wr, wt0, CB8(T), wave, lane); });
+        {
+            const char* xsrc = xk(g + 1 + LA);
+            char* xdst = xbase + (LA == 2 ? x2 : x1);
+            unpack_begin<BF16, FMT>(us, wr, wt0, wave, lane);
+            mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc, [&](auto tag) {
+                constexpr int S = decltype(tag)::value;
+                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                unpack_micro<BF16, FMT, 2, S>(us, wr, CB8(T));
+            });
+        }
         wait_step();
         RWKVQ_BARRIER();
         rotate();
 
-        x_tile_dma(xk(g + 2 + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
-        mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc,
-                       [&] { w_unpack<BF16, FMT, 3, 0, 2>(wr, wt1, CB8(T), wave, lane); },
-                       [&] { w_unpack<BF16, FMT, 3, 2, 4>(wr, wt1, CB8(T), wave, lane); });
+        {
+            const char* xsrc = xk(g + 2 + LA);
+            char* xdst = xbase + (LA == 2 ? x2 : x1);
+            unpack_begin<BF16, FMT>(us, wr, wt1, wave, lane);
+            mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc, [&](auto tag) {
+                constexpr int S = decltype(tag)::value;
+                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                unpack_micro<BF16, FMT, 3, S>(us, wr, CB8(T));
+            });
+        }
         wait_step();
         RWKVQ_BARRIER();
         rotate();
@@ -400,8 +544,14 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
         // (before the activation copy, so that waiting for them leaves the copy in flight); they
         // have a whole MFMA step to arrive
         w_load<FMT>(wr, src, Tn, lane);
-        x_tile_dma(xk(g + 3 + LA), xoff, xbase + (LA == 2 ? x2 : x1), wave);
-        mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc, [] {}, [] {});
+        {
+            const char* xsrc = xk(g + 3 + LA);
+            char* xdst = xbase + (LA == 2 ? x2 : x1);
+            mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc, [&](auto tag) {
+                constexpr int S = decltype(tag)::value;
+                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+            });
+        }
         if constexpr (FMT == FMT_VQ8) {
             cb8_store<BF16>(wr, CB8(T + 1), wave, lane);
             RWKVQ_WAIT_VM0_LGKM0();
