@@ -34,10 +34,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 DECODE_KERNEL = "rwkvq::decode_kernel<1>"
 PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT>"   # bf16; one instantiation per weight format
 PROXY_KERNEL = "rwkvq::proxy_set_kernel"
-DECODE_MATS_PER_LAUNCH = 64
+DECODE_MATS_PER_LAUNCH = 256
 # HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
 # scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic_config3.txt.
-DECODE_TRAFFIC_BYTES_PER_LAUNCH = 701.9e6
+DECODE_TRAFFIC_BYTES_PER_LAUNCH = 2807.6e6
 
 
 def log(*a):
@@ -118,10 +118,13 @@ def cpu_baseline(n_layers, min_seconds=10.0, max_passes=8):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # Defaults: long enough to time the steady state.  After idle the first ~100 decode steps run
+    # through a power-management transient (step time 0.47 -> 0.69 -> 0.49 ms on the 7B stack).
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--layers", type=int, default=32, help="layers of the stack (32 = the full workload)")
-    ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--prefill-steps", type=int, default=40)
+    ap.add_argument("--prefill-warmup", type=int, default=10)
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-proxy", action="store_true", help="skip the proxy and encoder legs")
@@ -188,10 +191,11 @@ def main():
         pf = build_stack(4, 2048, args.layers, gpu_activations=True, y_dtype=B.BF16)
         log(f"prefill stack resident: {pf['n_mats']} matrices, {pf['flops'] / 1e12:.2f} TFLOP/step, {time.time() - t:.1f} s")
         runp = lambda: B.rwkvq_linear_dispatch(pf["table"], 2048, pf["x_dtype"], B.BF16)
-        ptotal, pper, _ = time_steps(runp, args.prefill_steps, 1)
+        ptotal, pper, _ = time_steps(runp, args.prefill_steps, args.prefill_warmup)
         pms = ptotal / args.prefill_steps
         tflops = pf["flops"] / (pms * 1e-3) / 1e12
         out["prefill"] = {"value": tflops, "unit": "TFLOP/s", "ms_per_step": pms, "steps": args.prefill_steps,
+                          "warmup": args.prefill_warmup,
                           "dtype": "bf16", "tokens_per_s": 2048 * 1e3 / pms,
                           "pct_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
                           "workload": "configs[3]: same stack recipe (seed 3), M=2048 tokens, bf16 "
@@ -217,11 +221,12 @@ def main():
         pout = torch.empty(2 * n, dtype=torch.float64, device="cuda")
         pphi = torch.empty(n + 3, dtype=torch.int32, device="cuda")
         runx = lambda: B.rwkvq_proxy(table, B.BF16, 5, 1.5, 50.0, wsp, pout, pphi)
-        xtotal, xper, _ = time_steps(runx, 10, 2)
-        xms = xtotal / 10
+        xcalls = 300
+        xtotal, xper, _ = time_steps(runx, xcalls, 100)
+        xms = xtotal / xcalls
         xbytes = sum(a * b * 2 for a, b in shapes)
         launches = (n + 63) // 64
-        out["proxy"] = {"value": xbytes / (xms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_call": xms, "calls": 10,
+        out["proxy"] = {"value": xbytes / (xms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_call": xms, "calls": xcalls,
                         "dtype": "f64", "matrices": n, "dense_weight_bytes_per_call": xbytes,
                         "pct_hbm_peak": 100.0 * xbytes / (xms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                         "workload": "dense bf16 N(0, 0.02) weights of %d RWKV-6-7B-shaped layers "
@@ -266,10 +271,10 @@ def main():
                 for m, (N_, K_) in zip(mats, shapes):
                     B.rwkvq_vq_assign(m, B.BF16, cbs, N_, K_, 2, 6, 256, 256, idx)
 
-            st, _, _ = time_steps(run_sq, 5, 1)
-            sms = st / 5
-            vt, _, _ = time_steps(run_vq, 3, 1)
-            vms = vt / 3
+            st, _, _ = time_steps(run_sq, 30, 10)
+            sms = st / 30
+            vt, _, _ = time_steps(run_vq, 10, 3)
+            vms = vt / 10
             nw = sum(a * b for a, b in shapes)
             sq_bytes = nw * 2 + nw * 3 // 8 + nw // 128 * 4          # dense in, codes + scale + zero out
             vq_flop = (nw // 2) * 64 * 5                             # 2 sub, 2 mul, 1 add per pair and entry

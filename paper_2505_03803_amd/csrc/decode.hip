@@ -36,7 +36,8 @@ namespace rwkvq {
 #ifndef RWKVQ_DECODE_DEPTH
 #define RWKVQ_DECODE_DEPTH 2
 #endif
-constexpr int kMaxGroupMats = 64;     // matrices per grouped launch (descriptor table in kernarg)
+constexpr int kMaxGroupMats = 256;    // matrices per grouped launch (descriptor table in kernarg: a whole
+                                      // 32-layer stack is one launch, one ramp-up and one tail)
 constexpr int kXStride = 264;         // fp16 per staged activation row (256 + 8: bank spread)
 #ifndef RWKVQ_DECODE_RT
 #define RWKVQ_DECODE_RT 1
@@ -52,7 +53,7 @@ struct DecodeMat {
     void* y;
     int N, K, fmt, pad;
 };
-struct DecodeArgs {                   // 3344 bytes of kernel arguments
+struct DecodeArgs {                   // 13 KB of kernel arguments
     int wg_end[kMaxGroupMats];        // first workgroup index after matrix i (INT_MAX when unused)
     DecodeMat m[kMaxGroupMats];
     int M, xdt, ydt, pad;
@@ -631,8 +632,11 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     // (one load per wavefront from the argument block); the count of matrices that end at or
     // before this workgroup is its matrix index.
     const int wg = blockIdx.x;
-    static_assert(kMaxGroupMats == 64, "one table entry per lane");
-    const int mi = __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[threadIdx.x & 63]));
+    static_assert(kMaxGroupMats % 64 == 0, "one table entry per lane and pass");
+    int mi = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxGroupMats; j += 64)
+        mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
     const DecodeMat mt = a.m[mi];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

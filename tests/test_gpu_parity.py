@@ -162,6 +162,31 @@ def test_dispatch_equals_single_calls():
             assert torch.equal(single, y)
 
 
+@pytest.mark.parametrize("M", [1, 4, 40])
+def test_dispatch_many_matrices(M):
+    """300 small matrices in one table: the decode launch holds 256 descriptors (four passes of the
+    workgroup -> matrix look-up) and splits after them; the prefill launches split at 64 per format.
+    Every output must equal the single-matrix call's, bit for bit."""
+    torch = G.torch_()
+    kinds = ("sq", "vq6", "vq8")
+    shapes = ((48, 256), (256, 256), (256, 512), (32, 256), (512, 256))
+    base = [make(kinds[i % 3], *(shapes[i % 5] if kinds[i % 3] == "sq" else (256, 256 + 256 * (i % 2))), 100 + i)
+            for i in range(15)]
+    dbase = [B.upload(m, native=True) for m in base]
+    n = 300
+    xs = [G.to_dev_bits(acts(M, base[i % 15].K, "f16", 200 + i)) for i in range(n)]
+    ys = [torch.empty((M, base[i % 15].N), dtype=torch.float32, device="cuda") for i in range(n)]
+    table = B.DispatchTable([dbase[i % 15].desc() for i in range(n)], xs, ys)
+    B.rwkvq_linear_dispatch(table, M, B.F16, B.F32)
+    torch.cuda.synchronize()
+    for i in range(0, n, 7):
+        single = B.gemm(dbase[i % 15], xs[i], M, B.F16, B.F32)
+        torch.cuda.synchronize()
+        assert torch.equal(single, ys[i]), i
+    i = n - 1
+    assert torch.equal(B.gemm(dbase[i % 15], xs[i], M, B.F16, B.F32), ys[i])
+
+
 # ------------------------------------------------------------------ the configurations
 
 def test_config1_full():
