@@ -37,7 +37,7 @@ PROXY_KERNEL = "rwkvq::proxy_set_kernel"
 DECODE_MATS_PER_LAUNCH = 256
 # HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
 # scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic_config3.txt.
-DECODE_TRAFFIC_BYTES_PER_LAUNCH = 2807.6e6
+DECODE_TRAFFIC_BYTES_PER_LAUNCH = 2806.4e6
 
 
 def log(*a):
@@ -174,6 +174,9 @@ def main():
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "tokens_per_s": 1e3 / ms,
         "ms_per_step_min": min(per), "ms_per_step_median": float(np.median(per)),
+        # mean of ten equal slices of the timed steps, in order: shows drift (with --warmup 0, the
+        # power-management transient after idle)
+        "ms_per_step_slices": [round(float(np.mean(c)), 4) for c in np.array_split(np.asarray(per), 10)] if args.steps >= 10 else None,
         "wall_ms_per_step": wall_ms / args.steps,
         "roofline": {"kernel": DECODE_KERNEL, "bound": "hbm",
                      "achieved": dec["wbytes"] / launches / (ms / launches * 1e-3) / 1e9,
