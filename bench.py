@@ -129,6 +129,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-proxy", action="store_true", help="skip the proxy and encoder legs")
     ap.add_argument("--skip-encode", action="store_true")
+    ap.add_argument("--skip-mu", action="store_true", help="skip the element-wise multiplication leg")
     ap.add_argument("--proxy-layers", type=int, default=8, help="layers of dense bf16 weights the proxy leg scans per call")
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -300,6 +301,65 @@ def main():
                                                  "separately), so the reachable rate is half the FMA-counted peak"}
             del codes, sc, zr, idx, cbs
         del mats, table, wsp, pout, pphi
+        torch.cuda.empty_cache()
+
+    # ---------------- element-wise multiplication leg: token-shift mix with VQ weights, and its calibration
+    if not args.skip_mu:
+        from paper_2505_03803_amd import synth
+        d, M, L = 4096, 2048, args.layers
+        rng = np.random.default_rng(3000)
+        tdev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+        x = tdev(synth.gen_activations(rng, M, d, "bf16"))
+        xprev = tdev(synth.gen_activations(rng, 1, d, "bf16")[0])
+        # per layer: five mixes of the time-mixing block and two of the channel-mixing block
+        tables, keep = [], []
+        outs5 = [torch.empty((M, d), dtype=torch.int16, device="cuda") for _ in range(5)]
+        for layer in range(L):
+            for P in (5, 2):
+                idx = [tdev(rng.integers(0, 64, size=d // 2, dtype=np.uint8)) for _ in range(P)]
+                cbs = [tdev(synth.gen_codebook(rng, 64)) for _ in range(P)]
+                tables.append(B.MixTable(idx, cbs, outs5[:P]))
+        def run_mix():
+            for t in tables:
+                B.rwkvq_token_shift_mix(x, xprev, B.BF16, M, d, t, 6)
+        mt, _, _ = time_steps(run_mix, 30, 10)
+        mms = mt / 30
+        mix_bytes = L * (6 + 3) * M * d * 2 + L * 7 * (d // 2 + 256)     # x once per call + the outputs; indices, codebooks
+        # calibration of one layer-set: representative activation (128 samples) and 7 L codebooks
+        cal = tdev(synth.gen_calibration(rng, 128, d, "bf16"))
+        xbar = torch.empty(d, dtype=torch.float32, device="cuda")
+        run_clip = lambda: B.rwkvq_clip_mean(cal, B.BF16, 128, d, 1.0, xbar)
+        ct, _, _ = time_steps(run_clip, 10, 3)
+        nt = 7 * L
+        mus = [tdev(synth.gen_mu(rng, d, "bf16")) for _ in range(nt)]
+        cb0 = [tdev(synth.gen_codebook(rng, 64)) for _ in range(nt)]
+        idxo = [torch.empty(d // 2, dtype=torch.uint8, device="cuda") for _ in range(nt)]
+        run_cb = lambda: B.rwkvq_mu_codebook(mus, [xbar] * nt, [d] * nt, B.BF16, 6, 10, cb0, idxo)
+        kt, _, _ = time_steps(run_cb, 5, 2)
+        out["mu"] = {"mix": {"value": mix_bytes / (mms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": mms, "dtype": "f32",
+                             "bytes_per_step": mix_bytes, "calls_per_step": 2 * L},
+                     "clip_mean_ms": ct / 10, "codebook_ms": kt / 5, "codebook_tensors": nt, "codebook_iters": 10,
+                     "workload": "%d layers x (5 + 2) token-shift mixes of M=2048 x d=4096 bf16 activations with "
+                                 "6-bit VQ mix weights; calibration: 128 samples x 4096, %d weight tensors of 4096" % (L, nt)}
+        out["roofline_mix"] = {"kernel": "rwkvq::token_shift_mix_kernel", "bound": "hbm",
+                               "achieved": mix_bytes / (mms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": mix_bytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                               "avg_launch_ms": mms / (2 * L)}
+        if not args.skip_cpu:
+            from oracle import mu_oracle as MO
+            from oracle import rwkvq_oracle as orc
+            xs = orc.widen(x[:256].cpu().numpy().view(np.uint16), "bf16")
+            xp = orc.widen(xprev.cpu().numpy().view(np.uint16), "bf16")
+            m_hat = rng.uniform(0, 1, d).astype(np.float16).astype(np.float32)
+            secs, nb = 0.0, 0
+            while secs < 3.0:
+                t = time.perf_counter()
+                MO.narrow(MO.token_shift_mix(xs, xp, m_hat), "bf16")
+                secs += time.perf_counter() - t
+                nb += 2 * 256 * d * 2
+            out["mu"]["cpu_baseline"] = {"value": nb / secs / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                         "sample": "one projection, 256 of the 2048 rows, repeated for %.1f s" % secs}
+        del tables, mus, cb0, idxo, outs5, x, cal
         torch.cuda.empty_cache()
 
     # ---------------- CPU oracle baseline (reported, not a target)

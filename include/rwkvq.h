@@ -185,6 +185,45 @@ int rwkvq_sq_encode(const void* w, int w_dtype, int N, int K, int bits, int grou
 int rwkvq_vq_assign(const void* w, int w_dtype, const void* codebooks, int N, int K, int vdim, int kbits,
                     int block_rows, int block_cols, void* indices, void* stream);
 
+/* ---- element-wise multiplication weights (Sec. 3.2, "Codebook Optimization for Element-wise
+ *      Multiplication") and the token-shift mix of Eq. "time mixing r/k/v", "channel mixing r/k" ----
+ *
+ * rwkvq_clip_mean: the representative activation X of a calibration batch.  x: DEVICE pointer,
+ *   row-major [n_samples][n] (fp16 / bf16 bit patterns or binary32, finite); per position the
+ *   samples are limited to the range between their percentile-th and (100 - percentile)-th
+ *   percentile (linear interpolation between order statistics, rank (B - 1) q / 100, binary64) and
+ *   averaged (binary64 sum in sample order, divided by B, rounded to binary32).  xbar: DEVICE
+ *   pointer to n floats.  percentile in [0, 50] (0 = plain mean); n_samples <= 65536.
+ *
+ * rwkvq_mu_codebook: X^2-weighted Lloyd iterations (weighted KMeans under the loss of Eq.
+ *   "quantization loss of mul") for n_tensors weight tensors at once.  Tensor i: mus[i] = n_elems[i]
+ *   weights (mu_dtype; row-major flattening, cut into vectors of 2 consecutive elements),
+ *   xbars[i] = n_elems[i] floats (element weight = xbar^2 in binary32), codebooks[i] = 2^kbits x 2
+ *   fp16 entries: the initial codebook on entry (the caller draws it), the final one on return;
+ *   indices[i] = n_elems[i] / 2 bytes out, the entry of each vector under the final codebook.
+ *   Per iteration: assignment argmin_e fl(fl(w0 fl(t0^2)) + fl(w1 fl(t1^2))), t = mu - c_e, binary32,
+ *   lowest index on ties; update c_ej = sum w mu / sum w over the assigned vectors (binary64),
+ *   rounded once to fp16; a coordinate whose weight sum is zero keeps its value.  `iters` updates,
+ *   then one more assignment.  kbits = 6 or 8; n_elems[i] even, >= 2.  The arrays of pointers and
+ *   n_elems are HOST arrays of DEVICE pointers, read before return.
+ *
+ * rwkvq_token_shift_mix: outs[p][t][j] = mu_p[j] x[t][j] + (1 - mu_p[j]) x[t-1][j] for n_proj <= 8
+ *   projections in one pass, mu_p[j] = codebooks[p][indices[p][j / 2]][j % 2]; row 0 takes x[-1]
+ *   from x_prev[d].  Binary32 with one rounding per operation, fl(fl(m x_t) + fl(fl(1 - m) x_prev)),
+ *   then rounded once to x_dtype (fp16 or bf16).  x: [M][d], outs[p]: [M][d], d a multiple of 8.
+ *
+ * All device pointers 16-byte aligned (xbar of rwkvq_clip_mean: 4); asynchronous on `stream`; no
+ * scratch memory.  Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_UNSUPPORTED (dtype, kbits, percentile, n_proj,
+ * iters outside [0, 1000]), RWKVQ_ERR_SHAPE, RWKVQ_ERR_ALIGN, RWKVQ_ERR_DEVICE. */
+int rwkvq_clip_mean(const void* x, int x_dtype, int n_samples, int n, double percentile, float* xbar,
+                    void* stream);
+int rwkvq_mu_codebook(const void* const* mus, const float* const* xbars, const int* n_elems, int n_tensors,
+                      int mu_dtype, int kbits, int iters, void* const* codebooks, uint8_t* const* indices,
+                      void* stream);
+int rwkvq_token_shift_mix(const void* x, const void* x_prev, int x_dtype, int M, int d,
+                          const uint8_t* const* indices, const void* const* codebooks, int kbits, int n_proj,
+                          void* const* outs, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

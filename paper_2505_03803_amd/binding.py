@@ -21,7 +21,7 @@ DTYPES = {"f16": F16, "bf16": BF16, "f32": F32}
 EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq_prepack",
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
-           "rwkvq_vq_assign"]
+           "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix"]
 
 
 class rwkvq_matrix(Structure):
@@ -86,6 +86,14 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_vq_assign.restype = c_int
         L.rwkvq_vq_assign.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
                                       c_void_p, c_void_p]
+        L.rwkvq_clip_mean.restype = c_int
+        L.rwkvq_clip_mean.argtypes = [c_void_p, c_int, c_int, c_int, c_double, c_void_p, c_void_p]
+        L.rwkvq_mu_codebook.restype = c_int
+        L.rwkvq_mu_codebook.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p,
+                                        c_void_p]
+        L.rwkvq_token_shift_mix.restype = c_int
+        L.rwkvq_token_shift_mix.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_int, c_int,
+                                            c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -192,6 +200,39 @@ def rwkvq_vq_assign(w, w_dtype, codebooks, N, K, vdim, kbits, block_rows, block_
                     check=True):
     st = lib().rwkvq_vq_assign(_ptr(w), w_dtype, _ptr(codebooks), N, K, vdim, kbits, block_rows, block_cols,
                                _ptr(indices), _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_clip_mean(x, x_dtype, n_samples, n, percentile, xbar, stream=None, check=True):
+    st = lib().rwkvq_clip_mean(_ptr(x), x_dtype, n_samples, n, float(percentile), _ptr(xbar), _stream(stream))
+    return _check(st) if check else st
+
+
+def _ptr_array(items):
+    return (c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+def rwkvq_mu_codebook(mus, xbars, n_elems, mu_dtype, kbits, iters, codebooks, indices, stream=None, check=True):
+    """mus, xbars, codebooks, indices: sequences of device tensors (one per weight tensor)."""
+    n = len(mus)
+    st = lib().rwkvq_mu_codebook(_ptr_array(mus), _ptr_array(xbars), (c_int * n)(*[int(v) for v in n_elems]), n,
+                                 mu_dtype, kbits, iters, _ptr_array(codebooks), _ptr_array(indices), _stream(stream))
+    return _check(st) if check else st
+
+
+class MixTable:
+    """Host arrays for rwkvq_token_shift_mix (indices, codebooks and outputs of the projections)."""
+
+    def __init__(self, indices: Sequence, codebooks: Sequence, outs: Sequence):
+        assert len(indices) == len(codebooks) == len(outs)
+        self.n = len(indices)
+        self.idx, self.cb, self.out = _ptr_array(indices), _ptr_array(codebooks), _ptr_array(outs)
+        self.keep = (indices, codebooks, outs)
+
+
+def rwkvq_token_shift_mix(x, x_prev, x_dtype, M, d, table: MixTable, kbits, stream=None, check=True):
+    st = lib().rwkvq_token_shift_mix(_ptr(x), _ptr(x_prev), x_dtype, M, d, table.idx, table.cb, kbits, table.n,
+                                     table.out, _stream(stream))
     return _check(st) if check else st
 
 

@@ -3,6 +3,7 @@
 #include "common.h"
 #include "../../include/rwkvq.h"
 
+#include <cmath>
 #include <vector>
 
 using namespace rwkvq;
@@ -229,6 +230,53 @@ int rwkvq_vq_assign(const void* w, int w_dtype, const void* codebooks, int N, in
     if (!aligned16(w) || !aligned16(codebooks) || !aligned16(indices)) return RWKVQ_ERR_ALIGN;
     hipError_t e = launch_vq_assign(w, dense_dtype(w_dtype), N, K, kbits, (const uint16_t*)codebooks,
                                     (uint32_t*)indices, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
+int rwkvq_clip_mean(const void* x, int x_dtype, int n_samples, int n, double percentile, float* xbar, void* stream) {
+    if (!x || !xbar) return RWKVQ_ERR_NULL;
+    if (dense_dtype(x_dtype) < 0) return RWKVQ_ERR_UNSUPPORTED;
+    if (n_samples < 1 || n_samples > 65536 || n < 1) return RWKVQ_ERR_SHAPE;
+    if (!(percentile >= 0.0 && percentile <= 50.0)) return RWKVQ_ERR_UNSUPPORTED;
+    if (!aligned16(x) || ((uintptr_t)xbar & 3u)) return RWKVQ_ERR_ALIGN;
+    // rank of the q-th percentile among B ordered samples: r = (B - 1) q / 100, split into its
+    // integer part and the interpolation weight (binary64, the formula the definition states)
+    const double r_lo = (n_samples - 1) * (percentile / 100.0), r_hi = (n_samples - 1) * ((100.0 - percentile) / 100.0);
+    const int k_lo = (int)std::floor(r_lo), k_hi = (int)std::floor(r_hi);
+    hipError_t e = launch_clip_mean(x, dense_dtype(x_dtype), n_samples, n, k_lo, r_lo - k_lo, k_hi, r_hi - k_hi, xbar,
+                                    (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
+int rwkvq_mu_codebook(const void* const* mus, const float* const* xbars, const int* n_elems, int n_tensors,
+                      int mu_dtype, int kbits, int iters, void* const* codebooks, uint8_t* const* indices,
+                      void* stream) {
+    if (!mus || !xbars || !n_elems || !codebooks || !indices) return RWKVQ_ERR_NULL;
+    if (n_tensors < 1) return RWKVQ_ERR_SHAPE;
+    if ((kbits != 6 && kbits != 8) || dense_dtype(mu_dtype) < 0 || iters < 0 || iters > 1000) return RWKVQ_ERR_UNSUPPORTED;
+    for (int i = 0; i < n_tensors; ++i) {
+        if (!mus[i] || !xbars[i] || !codebooks[i] || !indices[i]) return RWKVQ_ERR_NULL;
+        if (n_elems[i] < 2 || (n_elems[i] & 1)) return RWKVQ_ERR_SHAPE;
+        if (!aligned16(mus[i]) || !aligned16(xbars[i]) || !aligned16(codebooks[i])) return RWKVQ_ERR_ALIGN;
+    }
+    hipError_t e = launch_mu_codebook(mus, xbars, n_elems, n_tensors, dense_dtype(mu_dtype), kbits, iters, codebooks,
+                                      indices, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
+int rwkvq_token_shift_mix(const void* x, const void* x_prev, int x_dtype, int M, int d, const uint8_t* const* indices,
+                          const void* const* codebooks, int kbits, int n_proj, void* const* outs, void* stream) {
+    if (!x || !x_prev || !indices || !codebooks || !outs) return RWKVQ_ERR_NULL;
+    if (x_dtype != RWKVQ_F16 && x_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    if ((kbits != 6 && kbits != 8) || n_proj < 1 || n_proj > 8) return RWKVQ_ERR_UNSUPPORTED;
+    if (M < 1 || d < 8 || d % 8 != 0 || (long long)M * d > (1ll << 40)) return RWKVQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(x_prev)) return RWKVQ_ERR_ALIGN;
+    for (int p = 0; p < n_proj; ++p) {
+        if (!indices[p] || !codebooks[p] || !outs[p]) return RWKVQ_ERR_NULL;
+        if (!aligned16(indices[p]) || !aligned16(codebooks[p]) || !aligned16(outs[p])) return RWKVQ_ERR_ALIGN;
+    }
+    hipError_t e = launch_token_shift_mix(x, x_prev, x_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, M, d, indices, codebooks,
+                                          kbits, n_proj, outs, (hipStream_t)stream);
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 

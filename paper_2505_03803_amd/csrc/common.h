@@ -137,6 +137,12 @@ hipError_t launch_sq_encode(const void* w, int wdt, int N, int K, uint32_t* code
                             uint16_t* zeros, hipStream_t s);
 hipError_t launch_vq_assign(const void* w, int wdt, int N, int K, int kbits, const uint16_t* codebooks,
                             uint32_t* indices, hipStream_t s);
+hipError_t launch_clip_mean(const void* x, int dt, int B, int n, int k_lo, double f_lo, int k_hi, double f_hi,
+                            float* out, hipStream_t s);
+hipError_t launch_mu_codebook(const void* const* mus, const float* const* xbars, const int* n_elems, int n_tensors,
+                              int dt, int kbits, int iters, void* const* cbs, uint8_t* const* idx, hipStream_t s);
+hipError_t launch_token_shift_mix(const void* x, const void* x_prev, int dt, int M, int d, const uint8_t* const* idx,
+                                  const void* const* cbs, int kbits, int n_proj, void* const* outs, hipStream_t s);
 
 constexpr int kDecodeMaxM = 16;    // native layout: M <= this goes to the streaming kernels
 constexpr int kDecodeMaxK = 20480; // ... whose per-group activation sums for K columns fit their LDS

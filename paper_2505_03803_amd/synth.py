@@ -177,3 +177,31 @@ def gen_dense_weights(rng: np.random.Generator, N: int, K: int, dtype: str = "bf
         mask = rng.random((N, K)) < outlier_fraction
         w = np.where(mask, w * np.float32(outlier_scale), w).astype(np.float32)
     return f32_to_f16_bits(w) if dtype == "f16" else f32_to_bf16_bits(w)
+
+
+def gen_mu(rng: np.random.Generator, n: int, dtype: str = "bf16") -> np.ndarray:
+    """A token-shift mix weight as RWKV checkpoints hold it: n values in (0, 1), 16-bit storage
+    (fp16 / bf16 bit patterns).  Trained mix weights fill the unit interval unevenly; a Beta(2, 3)
+    draw stands in for them."""
+    v = rng.beta(2.0, 3.0, size=n).astype(np.float32)
+    return f32_to_f16_bits(v) if dtype == "f16" else f32_to_bf16_bits(v)
+
+
+def gen_calibration(rng: np.random.Generator, n_samples: int, n: int, dtype: str = "bf16",
+                    outlier_fraction: float = 0.01, outlier_scale: float = 30.0) -> np.ndarray:
+    """[n_samples][n] calibration activations for the element-wise multiplication (Sec. 3.2 and
+    its ablation: near-normal per channel, a per-channel offset and scale, a small fraction of
+    samples far out) as fp16 / bf16 bit patterns or float32 (dtype "f32")."""
+    loc = rng.normal(0.0, 0.5, size=n).astype(np.float32)
+    scale = rng.uniform(0.5, 2.0, size=n).astype(np.float32)
+    x = rng.standard_normal((n_samples, n), dtype=np.float32) * scale[None, :] + loc[None, :]
+    mask = rng.random((n_samples, n)) < outlier_fraction
+    x = np.where(mask, x * np.float32(outlier_scale), x).astype(np.float32)
+    if dtype == "f32":
+        return x
+    return f32_to_f16_bits(x) if dtype == "f16" else f32_to_bf16_bits(x)
+
+
+def gen_codebook(rng: np.random.Generator, entries: int, lo: float = 0.0, hi: float = 1.0) -> np.ndarray:
+    """[entries][2] fp16 bit patterns drawn uniformly from [lo, hi): an initial codebook."""
+    return f32_to_f16_bits(rng.uniform(lo, hi, size=(entries, 2)).astype(np.float32))

@@ -151,3 +151,37 @@ def test_encoder_rejects():
     assert vq(vdim=4) == B.ERR_UNSUPPORTED and vq(kbits=7) == B.ERR_UNSUPPORTED and vq(br=128) == B.ERR_UNSUPPORTED
     assert vq(N=300) == B.ERR_SHAPE and vq(K=128) == B.ERR_SHAPE
     assert vq(idx=FAKE + 4) == B.ERR_ALIGN
+
+
+def test_mu_path_rejects():
+    from ctypes import c_int, c_void_p
+    L = B.lib()
+    cm = lambda **kw: L.rwkvq_clip_mean(*[kw.get(k, v) for k, v in
+                                          [("x", FAKE), ("dt", B.BF16), ("B", 128), ("n", 4096), ("p", 1.0), ("out", FAKE),
+                                           ("stream", None)]])
+    assert cm(x=None) == B.ERR_NULL and cm(out=None) == B.ERR_NULL
+    assert cm(dt=9) == B.ERR_UNSUPPORTED and cm(p=-1.0) == B.ERR_UNSUPPORTED and cm(p=50.5) == B.ERR_UNSUPPORTED
+    assert cm(p=float("nan")) == B.ERR_UNSUPPORTED
+    assert cm(B=0) == B.ERR_SHAPE and cm(B=70000) == B.ERR_SHAPE and cm(n=0) == B.ERR_SHAPE
+    assert cm(x=FAKE + 2) == B.ERR_ALIGN and cm(out=FAKE + 2) == B.ERR_ALIGN
+
+    arr = lambda *v: (c_void_p * len(v))(*v)
+    cb = lambda **kw: L.rwkvq_mu_codebook(*[kw.get(k, v) for k, v in
+                                            [("mus", arr(FAKE)), ("xb", arr(FAKE)), ("n", (c_int * 1)(4096)), ("nt", 1),
+                                             ("dt", B.BF16), ("kbits", 6), ("iters", 10), ("cbs", arr(FAKE)),
+                                             ("idx", arr(FAKE)), ("stream", None)]])
+    assert cb(mus=None) == B.ERR_NULL and cb(idx=None) == B.ERR_NULL and cb(mus=arr(None)) == B.ERR_NULL
+    assert cb(nt=0) == B.ERR_SHAPE and cb(n=(c_int * 1)(4097)) == B.ERR_SHAPE and cb(n=(c_int * 1)(0)) == B.ERR_SHAPE
+    assert cb(kbits=7) == B.ERR_UNSUPPORTED and cb(dt=9) == B.ERR_UNSUPPORTED and cb(iters=-1) == B.ERR_UNSUPPORTED
+    assert cb(iters=1001) == B.ERR_UNSUPPORTED
+    assert cb(xb=arr(FAKE + 4)) == B.ERR_ALIGN and cb(cbs=arr(FAKE + 2)) == B.ERR_ALIGN
+
+    mx = lambda **kw: L.rwkvq_token_shift_mix(*[kw.get(k, v) for k, v in
+                                                [("x", FAKE), ("xp", FAKE), ("dt", B.F16), ("M", 4), ("d", 4096),
+                                                 ("idx", arr(FAKE, FAKE)), ("cbs", arr(FAKE, FAKE)), ("kbits", 6), ("P", 2),
+                                                 ("outs", arr(FAKE, FAKE)), ("stream", None)]])
+    assert mx(x=None) == B.ERR_NULL and mx(xp=None) == B.ERR_NULL and mx(outs=arr(FAKE, None)) == B.ERR_NULL
+    assert mx(dt=B.F32) == B.ERR_UNSUPPORTED and mx(kbits=4) == B.ERR_UNSUPPORTED and mx(P=0) == B.ERR_UNSUPPORTED
+    assert mx(P=9) == B.ERR_UNSUPPORTED
+    assert mx(M=0) == B.ERR_SHAPE and mx(d=4100) == B.ERR_SHAPE and mx(d=0) == B.ERR_SHAPE
+    assert mx(x=FAKE + 8) == B.ERR_ALIGN and mx(idx=arr(FAKE, FAKE + 1)) == B.ERR_ALIGN
