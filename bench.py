@@ -137,7 +137,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); a multi-GPU figure is not "
-                 "part of it - see DESIGN.md for how the path would shard.")
+                 "part of it (the design notes say how the path would shard).")
 
     import torch
     from paper_2505_03803_amd import binding as B

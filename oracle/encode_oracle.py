@@ -14,7 +14,7 @@ SQ, per row and per group of `group` consecutive input channels (Eq. "SQ", b bit
     z  = (-min) / s                       with the stored s, binary32 divide, rounded to fp16 (stored)
     q  = clamp( rne( w / s + z ), 0, 2^b - 1 )    with the stored s and z: divide, add, round
 The dequantized value is (q - z) s, the inverse the run-time path evaluates.
-Readings (the paper is silent or ambiguous; also listed in the design doc):
+Readings (the paper is silent or ambiguous; also listed in the design notes):
   * the scale is printed as (max - min)/2^b - 1; read as /(2^b - 1);
   * the zero point is real-valued (no rounding is shown) and the equation adds it outside the
     rounding, which would make the code a non-integer; it is added inside, so that q is the index of

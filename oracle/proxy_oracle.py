@@ -18,7 +18,7 @@ The oracle is the paper's definition written out, step by step, in binary64:
     P_f = sum_{k=2}^{K} v_k |M_k|                  Eq. "fine_proxy"
     phi = 1 (SQ) iff P_c < tau_c and P_f < tau_f   Eq. "multi_scale_proxy"; otherwise 0 (VQ)
 
-Readings where the paper is silent (listed in the design doc too):
+Readings where the paper is silent (also listed in the design notes):
   * K: a hyper-parameter; a remark left in the source speaks of the first four terms, k = 2..5,
     which is the default here.
   * ties in W give intervals of length zero: 0 ln 0 := 0 (the limit), and delta_i = -1/n for them.
