@@ -219,7 +219,11 @@ struct Vq8Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XShared x; };
 
 // Everything a tile loop needs about its wavefront's position; R0, R1 are the two row tiles
 // (R1 == R0 when the matrix has an odd number of row tiles and this is the last wavefront).
-struct WavePos { int R[2], M, lane, tid; bool xbf16; };
+struct WavePos {
+    int R[2], M, lane, tid;
+    bool xbf16;
+    int t0, ts, nt;      // split-K (batch 1): this wavefront's column tiles are t0, t0 + ts, ... (nt of them)
+};
 
 // Batch 2..16 on the matrix cores: activations = A operand (row m of the MFMA = batch row m, read
 // from the shared LDS tile), weights = B operand.  `xs` points at the two activation buffers; the
@@ -434,7 +438,7 @@ __device__ __forceinline__ void xpairs_load(XPairs& r, const uint16_t* x, int T,
 
 struct Vq6M1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XPairs x; };
 
-template <int DEPTH>
+template <int DEPTH, bool SPLIT = false>
 __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     const int KT = mt.K >> 8, lane = wp.lane;
     const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
@@ -444,6 +448,7 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
     float acc1 = 0.f;                      // second accumulation chain, folded in at the end
     auto load = [&](Vq6M1Regs& r, int T) {
+        if (SPLIT) T = wp.t0 + T * wp.ts;
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 384;
@@ -486,7 +491,7 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
         acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
         out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
     };
-    tile_pipeline<DEPTH, Vq6M1Regs>(KT, load, compute);
+    tile_pipeline<DEPTH, Vq6M1Regs>(SPLIT ? wp.nt : KT, load, compute);
     RWKVQ_DOT_RESULT_FENCE("+v"(out[0]), "+v"(acc1));
     out[0] += acc1;
 }
@@ -525,13 +530,14 @@ __device__ __forceinline__ void sq_dot_pairs(float (&acc)[3], uint32_t xp, uint3
     (sq_dot_pair<P>(acc, xp, w0, w1, w2, s0, s1, s2), ...);
 }
 
-template <int DEPTH>
+template <int DEPTH, bool SPLIT = false>
 __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp, float (&out)[kRT]) {
     static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
     const uint32_t* codes = mt.codes + (size_t)wp.R[0] * KT * 384;
     const uint2_t* sz = (const uint2_t*)mt.aux + (size_t)wp.R[0] * KT * 16;
     auto load = [&](SqM1Regs& r, int T) {
+        if (SPLIT) T = wp.t0 + T * wp.ts;
         const uint32_t* t = codes + (size_t)T * 384;
         r.a[0] = *(const uint4_t*)(t + 4 * lane);
         r.b[0] = *(const uint2_t*)(t + 256 + 2 * lane);
@@ -566,13 +572,13 @@ __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp
             out[0] = fmaf(s, fmaf(-z, Xp, S), out[0]);
         }
     };
-    tile_pipeline<DEPTH, SqM1Regs>(KT, load, compute);
+    tile_pipeline<DEPTH, SqM1Regs>(SPLIT ? wp.nt : KT, load, compute);
     out[0] *= 131072.f;
 }
 
 struct Vq8M1Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XPairs x; };
 
-template <int DEPTH>
+template <int DEPTH, bool SPLIT = false>
 __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
@@ -580,6 +586,7 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
     const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
     float acc1 = 0.f;
     auto load = [&](Vq8M1Regs& r, int T) {
+        if (SPLIT) T = wp.t0 + T * wp.ts;
         const uint32_t* t = codes + (size_t)T * 512;
         r.a[0] = *(const uint4_t*)(t + 4 * lane);
         r.b[0] = *(const uint4_t*)(t + 256 + 4 * lane);
@@ -612,7 +619,7 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
         acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
         out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
     };
-    tile_pipeline<DEPTH, Vq8M1Regs>(KT, load, compute);
+    tile_pipeline<DEPTH, Vq8M1Regs>(SPLIT ? wp.nt : KT, load, compute);
     RWKVQ_DOT_RESULT_FENCE("+v"(out[0]), "+v"(acc1));
     out[0] += acc1;
 }
@@ -692,6 +699,49 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     }
 }
 
+// Batch 1 when a launch holds too few row tiles to fill the device (a single projection, the
+// matrices of one stage of a block): one workgroup per 16-row tile, its S wavefronts take the
+// column tiles s, s + S, s + 2S, ... and their partial sums meet in LDS in a fixed order.  The
+// grouped kernel above gives one wavefront a whole row tile, which keeps 4096 x 4096 on a quarter
+// of the SIMDs.
+template <int S>
+__global__ void __launch_bounds__(64 * S) decode_splitk_kernel(DecodeArgs a) {
+    constexpr int DEPTH = RWKVQ_DECODE_DEPTH;
+    static_assert(kRT == 1, "one row tile per wavefront");
+    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[S][256];
+    __shared__ float red[S][16];
+    const int wg = blockIdx.x;
+    int mi = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxGroupMats; j += 64)
+        mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
+    const DecodeMat mt = a.m[mi];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KT = mt.K >> 8;
+    WavePos wp;
+    wp.R[0] = wp.R[1] = wg - (mi ? a.wg_end[mi - 1] : 0);      // here wg_end counts row tiles
+    wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
+    wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
+    float part[kRT] = {0.f};
+    if (wp.nt > 0) {
+        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true>(mt, wp, part);
+        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, true>(mt, wp, cb_all[wave], part);
+        else run_vq8_m1<DEPTH, true>(mt, wp, cb_all[wave], part);
+    }
+    float v = part[0];                             // sum the four column groups of each row
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    if (lane < 16) red[wave][lane] = v;
+    __syncthreads();
+    if (wave == 0 && lane < 16) {
+        float t = red[0][lane];
+#pragma unroll
+        for (int s = 1; s < S; ++s) t += red[s][lane];
+        store_from_f32(mt.y, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+    }
+}
+
 hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
     for (int base = 0; base < n_mats; base += kMaxGroupMats) {
         DecodeArgs a;
@@ -702,10 +752,16 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         int order[kMaxGroupMats];
         for (int i = 0; i < cnt; ++i) order[i] = base + i;
         std::stable_sort(order, order + cnt, [&](int p, int q) { return mats[p].K > mats[q].K; });
+        // Batch 1 with fewer row tiles than four per SIMD: split the columns over S wavefronts of a
+        // workgroup (one workgroup per row tile), S the smallest of 4, 8, 16 that fills the device.
+        int tiles = 0;
+        for (int i = 0; i < cnt; ++i) tiles += (mats[order[i]].N + 15) / 16;
+        int split = 0;
+        if (M == 1 && tiles < 4096) split = tiles * 4 >= 4096 ? 4 : tiles * 8 >= 4096 ? 8 : 16;
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[order[i]];
-            wgs += (m.N + kWgRows - 1) / kWgRows;
+            wgs += split ? (m.N + 15) / 16 : (m.N + kWgRows - 1) / kWgRows;
             a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, 0};
             a.wg_end[i] = wgs;
         }
@@ -714,7 +770,10 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
             a.wg_end[i] = 0x7FFFFFFF;
         }
         a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
-        if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
+        if (split == 4) hipLaunchKernelGGL(decode_splitk_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
+        else if (split == 8) hipLaunchKernelGGL(decode_splitk_kernel<8>, dim3(wgs), dim3(512), 0, s, a);
+        else if (split == 16) hipLaunchKernelGGL(decode_splitk_kernel<16>, dim3(wgs), dim3(1024), 0, s, a);
+        else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
         else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
         else hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(256), 0, s, a);
         hipError_t e = hipGetLastError();

@@ -79,6 +79,20 @@ def test_decode_small(fmt, N, K, M, xdt):
     G.check_outputs(y, mat, x, xdt, fed=None, tight=2e-5)
 
 
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+@pytest.mark.parametrize("N,K", [(256, 256), (256, 3584), (8192, 256), (8192, 1280), (16384, 512), (65536, 256)])
+def test_decode_batch1_launch_shapes(fmt, N, K):
+    """Batch 1 picks its kernel by the number of 16-row tiles in the launch: 16, 8 or 4 wavefronts
+    per tile with the column tiles dealt round-robin (fewer than 256 / 512 / 1024 ... tiles), or one
+    wavefront per tile (4096 tiles and more).  Rows with fewer column tiles than wavefronts, and
+    tile counts that do not divide, are part of the sweep."""
+    print(f"decode shapes {fmt} N={N} K={K}", flush=True)
+    mat = make(fmt, N, K, 8)
+    x = acts(1, K, "f16", N + K)
+    y = G.gpu_gemm(B.upload(mat, native=True), x, "f16")
+    G.check_outputs(y, mat, x, "f16", fed=None, tight=2e-5)
+
+
 @pytest.mark.parametrize("fmt,N,K", [("sq", 256, 768), ("vq6", 256, 768), ("vq8", 512, 512)])
 @pytest.mark.parametrize("M", [17, 256, 300])
 @pytest.mark.parametrize("xdt", ["bf16", "f16"])
