@@ -38,7 +38,8 @@ namespace rwkvq {
 #endif
 constexpr int kMaxGroupMats = 256;    // matrices per grouped launch (descriptor table in kernarg: a whole
                                       // 32-layer stack is one launch, one ramp-up and one tail)
-constexpr int kXStride = 264;         // fp16 per staged activation row (256 + 8: bank spread)
+constexpr int kXStride = 272;         // fp16 per staged activation row: 34 units of 16 bytes, so that the 16 lanes an LDS
+                                      // cycle serves (rows m..m+7 of column groups kg, kg+1) fall into 16 distinct units
 #ifndef RWKVQ_DECODE_RT
 #define RWKVQ_DECODE_RT 1
 #endif
