@@ -268,7 +268,10 @@ def main():
                           "flop_per_step": pf["flops"]}
         out["roofline_prefill"] = {"kernel": PREFILL_KERNEL, "bound": "mfma", "achieved": tflops,
                                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+                                   "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+                                   # FETCH_SIZE x 2 + WRITE_SIZE per launch, mean of the four launches of a step
+                                   # (profiles/prefill_and_mix_hbm_traffic.txt)
+                                   "traffic": 8.87e9 if args.layers == 32 else None}
         del pf, runp
         torch.cuda.empty_cache()
 
@@ -404,7 +407,10 @@ def main():
                                  "6-bit VQ mix weights; calibration: 128 samples x 4096, %d weight tensors of 4096" % (L, nt)}
         out["roofline_mix"] = {"kernel": "rwkvq::token_shift_mix_kernel", "bound": "hbm",
                                "achieved": mix_bytes / (mms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": mix_bytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                               "frac": mix_bytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                               # mean per call (profiles/prefill_and_mix_hbm_traffic.txt)
+                               "traffic": 75.7e6,
+                               "algorithmic_bytes_per_launch": mix_bytes / (2 * L),
                                "avg_launch_ms": mms / (2 * L)}
         if not args.skip_cpu:
             from oracle import mu_oracle as MO

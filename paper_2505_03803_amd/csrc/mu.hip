@@ -190,7 +190,12 @@ __global__ void __launch_bounds__(256) token_shift_mix_kernel(MixArgs a) {
     }
     __syncthreads();
     const int chunks = a.d >> 3;
-    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD one
+    // contiguous range of rows, so that x_{t-1} (the row above) is in the L2 that just read it as x_t
+    // (with the plain order the two reads of a row came from different XCDs: twice the fetches).
+    const int per_xcd = gridDim.x >> 3;                    // the grid is a multiple of 8 workgroups
+    const long long blk = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const long long g = blk * 256 + threadIdx.x;
     if (g >= (long long)a.M * chunks) return;
     const int row = (int)(g / chunks), c = (int)(g - (long long)row * chunks);
     const uint4_t xt = ((const uint4_t*)a.x)[(size_t)row * chunks + c];
@@ -227,7 +232,7 @@ hipError_t launch_token_shift_mix(const void* x, const void* x_prev, int dt, int
     }
     a.M = M; a.d = d; a.dt = dt; a.n_proj = n_proj; a.E = 1 << kbits; a.pad = 0;
     const long long threads = (long long)M * (d >> 3);
-    const dim3 grid((unsigned)((threads + 255) / 256));
+    const dim3 grid((unsigned)((((threads + 255) / 256) + 7) / 8 * 8));
     if (dt == DT_BF16) hipLaunchKernelGGL(token_shift_mix_kernel<true>, grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(token_shift_mix_kernel<false>, grid, dim3(256), 0, s, a);
     return hipGetLastError();
