@@ -40,6 +40,10 @@ constexpr int kMaxGroupMats = 256;    // matrices per grouped launch (descriptor
                                       // 32-layer stack is one launch, one ramp-up and one tail)
 constexpr int kXStride = 272;         // fp16 per staged activation row: 34 units of 16 bytes, so that the 16 lanes an LDS
                                       // cycle serves (rows m..m+7 of column groups kg, kg+1) fall into 16 distinct units
+#ifndef RWKVQ_SPLIT_TARGET
+#define RWKVQ_SPLIT_TARGET 2048
+#endif
+constexpr int kSplitTarget = RWKVQ_SPLIT_TARGET;   // wavefronts a batch-1 launch should have before it stops splitting K
 #ifndef RWKVQ_DECODE_RT
 #define RWKVQ_DECODE_RT 1
 #endif
@@ -753,12 +757,13 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         int order[kMaxGroupMats];
         for (int i = 0; i < cnt; ++i) order[i] = base + i;
         std::stable_sort(order, order + cnt, [&](int p, int q) { return mats[p].K > mats[q].K; });
-        // Batch 1 with fewer row tiles than four per SIMD: split the columns over S wavefronts of a
-        // workgroup (one workgroup per row tile), S the smallest of 4, 8, 16 that fills the device.
+        // Batch 1 with fewer row tiles than two per SIMD: split the columns over S wavefronts of a
+        // workgroup (one workgroup per row tile), S the smallest of 4, 8, 16 that reaches that count
+        // (measured on the stages of a 7B block: 2048 beats 1024 and 4096 by 3-8 %, 16384 loses 40 %).
         int tiles = 0;
         for (int i = 0; i < cnt; ++i) tiles += (mats[order[i]].N + 15) / 16;
         int split = 0;
-        if (M == 1 && tiles < 4096) split = tiles * 4 >= 4096 ? 4 : tiles * 8 >= 4096 ? 8 : 16;
+        if (M == 1 && tiles < kSplitTarget) split = tiles * 4 >= kSplitTarget ? 4 : tiles * 8 >= kSplitTarget ? 8 : 16;
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[order[i]];

@@ -80,11 +80,11 @@ def test_decode_small(fmt, N, K, M, xdt):
 
 
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
-@pytest.mark.parametrize("N,K", [(256, 256), (256, 3584), (8192, 256), (8192, 1280), (16384, 512), (65536, 256)])
+@pytest.mark.parametrize("N,K", [(256, 256), (256, 3584), (4096, 512), (4096, 1792), (8192, 256), (8192, 1280), (16384, 512), (65536, 256)])
 def test_decode_batch1_launch_shapes(fmt, N, K):
     """Batch 1 picks its kernel by the number of 16-row tiles in the launch: 16, 8 or 4 wavefronts
-    per tile with the column tiles dealt round-robin (fewer than 256 / 512 / 1024 ... tiles), or one
-    wavefront per tile (4096 tiles and more).  Rows with fewer column tiles than wavefronts, and
+    per tile with the column tiles dealt round-robin (small launches), or one wavefront per tile
+    (2048 tiles and more).  Rows with fewer column tiles than wavefronts, and
     tile counts that do not divide, are part of the sweep."""
     print(f"decode shapes {fmt} N={N} K={K}", flush=True)
     mat = make(fmt, N, K, 8)
@@ -173,14 +173,17 @@ def test_dispatch_equals_single_calls():
         for dm, x, y in zip(dms, xs, ys):
             single = B.gemm(dm, x, M, B.DTYPES[xdt], B.F32)
             torch.cuda.synchronize()
-            assert torch.equal(single, y)
+            if M == 1:      # the batch-1 kernel is picked by launch size: same sums, possibly another order
+                assert (single - y).abs().max() <= 4e-6 * y.abs().max()
+            else:
+                assert torch.equal(single, y)
 
 
 @pytest.mark.parametrize("M", [1, 4, 40])
 def test_dispatch_many_matrices(M):
     """300 small matrices in one table: the decode launch holds 256 descriptors (four passes of the
     workgroup -> matrix look-up) and splits after them; the prefill launches split at 64 per format.
-    Every output must equal the single-matrix call's, bit for bit."""
+    Every output must equal the single-matrix call's (bit for bit on the matrix-core paths)."""
     torch = G.torch_()
     kinds = ("sq", "vq6", "vq8")
     shapes = ((48, 256), (256, 256), (256, 512), (32, 256), (512, 256))
@@ -193,12 +196,16 @@ def test_dispatch_many_matrices(M):
     table = B.DispatchTable([dbase[i % 15].desc() for i in range(n)], xs, ys)
     B.rwkvq_linear_dispatch(table, M, B.F16, B.F32)
     torch.cuda.synchronize()
-    for i in range(0, n, 7):
+    def same(a, b):
+        # batch 1 picks its kernel by launch size (a single call splits the columns over several
+        # wavefronts, the big launch does not): the binary32 sums differ in their order only
+        if M == 1:
+            return bool((a - b).abs().max() <= 4e-6 * b.abs().max())
+        return torch.equal(a, b)
+    for i in list(range(0, n, 7)) + [n - 1]:
         single = B.gemm(dbase[i % 15], xs[i], M, B.F16, B.F32)
         torch.cuda.synchronize()
-        assert torch.equal(single, ys[i]), i
-    i = n - 1
-    assert torch.equal(B.gemm(dbase[i % 15], xs[i], M, B.F16, B.F32), ys[i])
+        assert same(single, ys[i]), i
 
 
 # ------------------------------------------------------------------ the configurations
