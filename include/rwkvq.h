@@ -224,6 +224,26 @@ int rwkvq_token_shift_mix(const void* x, const void* x_prev, int x_dtype, int M,
                           const uint8_t* const* indices, const void* const* codebooks, int kbits, int n_proj,
                           void* const* outs, void* stream);
 
+/* rwkvq_linear_dispatch_mixed: batch 1 with the token-shift mix fused into the GEMV.  For matrix i
+ *   y_i = Deq(W_i) . round_x( mu_i (.) x_i + (1 - mu_i) (.) x_prev_i ),  mu_i[j] =
+ *   codebook_i[indices_i[j / 2]][j % 2]:  the mix is evaluated element by element as
+ *   rwkvq_token_shift_mix defines it (binary32, one rounding per operation, then rounded to x_dtype)
+ *   while the activations are loaded, so the result equals that of rwkvq_token_shift_mix followed by
+ *   rwkvq_linear_dispatch on the same matrices, bit for bit, without the pass over memory and the
+ *   launch in between.  mats: native layout only; ys[i]: [N_i] values of y_dtype.
+ *   Errors as rwkvq_linear_dispatch; RWKVQ_ERR_UNSUPPORTED also for canonical-layout matrices,
+ *   K > 20480 and kbits other than 6 or 8. */
+typedef struct rwkvq_mix_input {
+    const void* x;           /* DEVICE: [K] activations of the current token (x_dtype) */
+    const void* x_prev;      /* DEVICE: [K] activations of the previous token */
+    const uint8_t* indices;  /* DEVICE: [K / 2] indices of the mix weight's 2-vectors */
+    const void* codebook;    /* DEVICE: 2^kbits x 2 fp16 entries */
+    int32_t kbits;           /* 6 or 8 */
+    int32_t reserved;
+} rwkvq_mix_input;
+int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input* mixes, void* const* ys,
+                                int n_mats, int x_dtype, int y_dtype, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

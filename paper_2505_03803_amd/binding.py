@@ -21,7 +21,12 @@ DTYPES = {"f16": F16, "bf16": BF16, "f32": F32}
 EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq_prepack",
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
-           "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix"]
+           "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed"]
+
+
+class rwkvq_mix_input(Structure):
+    _fields_ = [("x", c_void_p), ("x_prev", c_void_p), ("indices", c_void_p), ("codebook", c_void_p),
+                ("kbits", c_int32), ("reserved", c_int32)]
 
 
 class rwkvq_matrix(Structure):
@@ -94,6 +99,8 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_token_shift_mix.restype = c_int
         L.rwkvq_token_shift_mix.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_int, c_int,
                                             c_void_p, c_void_p]
+        L.rwkvq_linear_dispatch_mixed.restype = c_int
+        L.rwkvq_linear_dispatch_mixed.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]
         _lib = L
     return _lib
 
@@ -233,6 +240,26 @@ class MixTable:
 def rwkvq_token_shift_mix(x, x_prev, x_dtype, M, d, table: MixTable, kbits, stream=None, check=True):
     st = lib().rwkvq_token_shift_mix(_ptr(x), _ptr(x_prev), x_dtype, M, d, table.idx, table.cb, kbits, table.n,
                                      table.out, _stream(stream))
+    return _check(st) if check else st
+
+
+class MixedDispatchTable:
+    """Host arrays for rwkvq_linear_dispatch_mixed: per matrix its descriptor, (x, x_prev, indices,
+    codebook, kbits) of the mix in front of it, and the output."""
+
+    def __init__(self, descs: Sequence, mixes: Sequence, ys: Sequence):
+        n = len(descs)
+        assert len(mixes) == n and len(ys) == n
+        self.n = n
+        self.mats = (rwkvq_matrix * n)(*descs)
+        self.mixes = (rwkvq_mix_input * n)(*[rwkvq_mix_input(_ptr(x), _ptr(xp), _ptr(ix), _ptr(cb), int(kb), 0)
+                                             for x, xp, ix, cb, kb in mixes])
+        self.ys = _ptr_array(ys)
+        self.keep = (mixes, ys)
+
+
+def rwkvq_linear_dispatch_mixed(table: MixedDispatchTable, x_dtype, y_dtype, stream=None, check=True):
+    st = lib().rwkvq_linear_dispatch_mixed(table.mats, table.mixes, table.ys, table.n, x_dtype, y_dtype, _stream(stream))
     return _check(st) if check else st
 
 

@@ -280,4 +280,27 @@ int rwkvq_token_shift_mix(const void* x, const void* x_prev, int x_dtype, int M,
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 
+int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input* mixes, void* const* ys, int n_mats,
+                                int x_dtype, int y_dtype, void* stream) {
+    if (!mats || !mixes || !ys) return RWKVQ_ERR_NULL;
+    if (n_mats <= 0) return RWKVQ_ERR_SHAPE;
+    int st;
+    if ((st = check_dtype_x(x_dtype)) != RWKVQ_OK) return st;
+    if ((st = check_dtype_y(y_dtype)) != RWKVQ_OK) return st;
+    std::vector<MatDev> md((size_t)n_mats);
+    std::vector<MixDev> xd((size_t)n_mats);
+    for (int i = 0; i < n_mats; ++i) {
+        const rwkvq_mix_input& x = mixes[i];
+        if (!x.x || !x.x_prev || !x.indices || !x.codebook || !ys[i]) return RWKVQ_ERR_NULL;
+        if (x.kbits != 6 && x.kbits != 8) return RWKVQ_ERR_UNSUPPORTED;
+        if (!aligned16(x.x) || !aligned16(x.x_prev) || !aligned16(x.indices) || !aligned16(x.codebook) || !aligned16(ys[i]))
+            return RWKVQ_ERR_ALIGN;
+        if ((st = to_dev(mats[i], x.x, ys[i], &md[(size_t)i])) != RWKVQ_OK) return st;
+        if (md[(size_t)i].layout != RWKVQ_NATIVE || md[(size_t)i].K > kDecodeMaxK) return RWKVQ_ERR_UNSUPPORTED;
+        xd[(size_t)i] = MixDev{x.x_prev, x.indices, (const uint16_t*)x.codebook, 1 << x.kbits};
+    }
+    hipError_t e = launch_decode_mixed(md.data(), xd.data(), n_mats, x_dtype, y_dtype, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
 }  // extern "C"

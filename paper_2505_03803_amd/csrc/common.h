@@ -124,6 +124,11 @@ hipError_t launch_vq_prepack(const uint32_t* indices, int N, int K, int kbits, u
                              hipStream_t s);
 hipError_t launch_dequant(const MatDev& m, void* w_out, int w_dtype, hipStream_t s);
 hipError_t launch_ref_gemm(const MatDev& m, int M, int x_dtype, int y_dtype, hipStream_t s);
+// The token-shift mix in front of a batch-1 GEMV: the previous token's activations and the mix
+// weight (indices of 2-vectors, one per column pair, and its codebook of E fp16 pairs).
+struct MixDev { const void* x_prev; const uint8_t* idx; const uint16_t* cb; int E; };
+hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_mats, int x_dtype, int y_dtype,
+                               hipStream_t s);
 hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype,
                          hipStream_t s);
 hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype,

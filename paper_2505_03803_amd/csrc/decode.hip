@@ -58,7 +58,24 @@ struct DecodeMat {
     void* y;
     int N, K, fmt, pad;
 };
+// A matrix whose input is mixed on the fly: x (of DecodeMat) is x_t.
+struct MixedMat : DecodeMat {
+    const uint16_t* xprev;            // x_{t-1}, same type and length as x
+    const uint8_t* mix_idx;           // K / 2 indices of the mix weight
+    const uint32_t* mix_cb;           // its codebook: mix_E entries of two fp16
+    int mix_E, pad2;
+};
+constexpr int kMaxMixedMats = 64;
+struct MixedDecodeArgs {
+    static constexpr bool kMixed = true;
+    static constexpr int kMats = kMaxMixedMats;
+    int wg_end[kMaxMixedMats];
+    MixedMat m[kMaxMixedMats];
+    int M, xdt, ydt, pad;
+};
 struct DecodeArgs {                   // 13 KB of kernel arguments
+    static constexpr bool kMixed = false;
+    static constexpr int kMats = kMaxGroupMats;
     int wg_end[kMaxGroupMats];        // first workgroup index after matrix i (INT_MAX when unused)
     DecodeMat m[kMaxGroupMats];
     int M, xdt, ydt, pad;
@@ -228,6 +245,11 @@ struct WavePos {
     int R[2], M, lane, tid;
     bool xbf16;
     int t0, ts, nt;      // split-K (batch 1): this wavefront's column tiles are t0, t0 + ts, ... (nt of them)
+    // fused token-shift mix (batch 1): the previous token's activations, the mix weight's indices
+    // (one per column pair) and its codebook staged in LDS by this wavefront
+    const uint16_t* xprev;
+    const uint8_t* mix_idx;
+    const uint32_t* mix_cb;
 };
 
 // Batch 2..16 on the matrix cores: activations = A operand (row m of the MFMA = batch row m, read
@@ -441,9 +463,44 @@ __device__ __forceinline__ void xpairs_load(XPairs& r, const uint16_t* x, int T,
     r.p[1] = *(const uint32_t*)(xt + 128);
 }
 
-struct Vq6M1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XPairs x; };
+// Fused token-shift mix (Eq. "time mixing r/k/v"): the wavefront loads, beside its pairs of x_t, the
+// same pairs of x_{t-1} and the two index bytes of the mix weight (one 2-vector of the weight covers
+// exactly one column pair), and mixes before the dot products: fl(fl(m x_t) + fl(fl(1 - m) x_{t-1}))
+// per element in binary32, rounded to the activation type - the values a separate mix pass would
+// have stored.
+__device__ __forceinline__ void mix_load(XPairs& xq, uint32_t& mi, const WavePos& wp, int T, int lane) {
+    xpairs_load(xq, wp.xprev, T, lane);
+    const int i = lane & 15, kg = lane >> 4;
+    const uint8_t* p = wp.mix_idx + 128 * T + 16 * (i >> 2) + 4 * kg + (i & 3);
+    mi = (uint32_t)p[0] | ((uint32_t)p[64] << 8);
+}
+__device__ __forceinline__ uint32_t mix_pair(uint32_t xt, uint32_t xp, uint32_t entry, bool bf16) {
+    const half2_t mh = __builtin_bit_cast(half2_t, entry);
+    const half_t ma = mh.x, mb = mh.y;
+    const float m0 = (float)ma, m1 = (float)mb;
+    float t0, t1, u0, u1;
+    if (bf16) {
+        t0 = __uint_as_float(xt << 16); t1 = __uint_as_float(xt & 0xFFFF0000u);
+        u0 = __uint_as_float(xp << 16); u1 = __uint_as_float(xp & 0xFFFF0000u);
+    } else {
+        const half2_t th = __builtin_bit_cast(half2_t, xt), uh = __builtin_bit_cast(half2_t, xp);
+        const half_t ta = th.x, tb = th.y, ua = uh.x, ub = uh.y;
+        t0 = (float)ta; t1 = (float)tb; u0 = (float)ua; u1 = (float)ub;
+    }
+    const float o0 = __fadd_rn(__fmul_rn(m0, t0), __fmul_rn(__fsub_rn(1.0f, m0), u0));
+    const float o1 = __fadd_rn(__fmul_rn(m1, t1), __fmul_rn(__fsub_rn(1.0f, m1), u1));
+    if (bf16) return (uint32_t)f32_to_bf16_bits(o0) | ((uint32_t)f32_to_bf16_bits(o1) << 16);
+    return (uint32_t)f32_to_f16_bits(o0) | ((uint32_t)f32_to_f16_bits(o1) << 16);
+}
+template <class Regs>
+__device__ __forceinline__ void mix_apply(const Regs& r, const WavePos& wp, uint32_t& x0, uint32_t& x1) {
+    x0 = mix_pair(r.x.p[0], r.xq.p[0], wp.mix_cb[r.mi & 255u], wp.xbf16);
+    x1 = mix_pair(r.x.p[1], r.xq.p[1], wp.mix_cb[(r.mi >> 8) & 255u], wp.xbf16);
+}
 
-template <int DEPTH, bool SPLIT = false>
+struct Vq6M1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XPairs x, xq; uint32_t mi; };
+
+template <int DEPTH, bool SPLIT = false, bool MIXED = false>
 __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     const int KT = mt.K >> 8, lane = wp.lane;
     const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
@@ -462,12 +519,14 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
         }
         r.cb = (cbs + (size_t)T * 64)[lane];
         xpairs_load(r.x, (const uint16_t*)mt.x, T, lane);
+        if (MIXED) mix_load(r.xq, r.mi, wp, T, lane);
     };
     auto compute = [&](const Vq6M1Regs& r, int) {
         wave_lds_sync();
         cb_lds[lane] = r.cb;
         wave_lds_sync();
         uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
+        if (MIXED) mix_apply(r, wp, x0, x1);
         if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
         // a DPP read needs two wait states after a vector-ALU write of the register
         asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));
@@ -507,7 +566,7 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
 // or 7 of the halves) or a share of one shift by 9 that brings the codes at bits 10 and 13 down
 // to bits 1 and 4.  Products of different bit positions go to different accumulators (acc[0..2] for
 // bits 1, 4, 7), which are combined with exact powers of two once per group.
-struct SqM1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XPairs x; };
+struct SqM1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XPairs x, xq; uint32_t mi; };
 
 template <int P>
 __device__ __forceinline__ void sq_dot_pair(float (&acc)[3], uint32_t xp, uint32_t w0, uint32_t w1, uint32_t w2,
@@ -535,7 +594,7 @@ __device__ __forceinline__ void sq_dot_pairs(float (&acc)[3], uint32_t xp, uint3
     (sq_dot_pair<P>(acc, xp, w0, w1, w2, s0, s1, s2), ...);
 }
 
-template <int DEPTH, bool SPLIT = false>
+template <int DEPTH, bool SPLIT = false, bool MIXED = false>
 __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp, float (&out)[kRT]) {
     static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
@@ -548,9 +607,11 @@ __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp
         r.b[0] = *(const uint2_t*)(t + 256 + 2 * lane);
         r.sz[0] = (sz + (size_t)T * 16)[lane & 15];
         xpairs_load(r.x, (const uint16_t*)mt.x, T, lane);
+        if (MIXED) mix_load(r.xq, r.mi, wp, T, lane);
     };
     auto compute = [&](const SqM1Regs& r, int) {
         uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
+        if (MIXED) mix_apply(r, wp, x0, x1);
         if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
         asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));     // vector-ALU write -> DPP read
 #pragma unroll
@@ -581,9 +642,9 @@ __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp
     out[0] *= 131072.f;
 }
 
-struct Vq8M1Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XPairs x; };
+struct Vq8M1Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XPairs x, xq; uint32_t mi; };
 
-template <int DEPTH, bool SPLIT = false>
+template <int DEPTH, bool SPLIT = false, bool MIXED = false>
 __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
@@ -597,12 +658,14 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
         r.b[0] = *(const uint4_t*)(t + 256 + 4 * lane);
         r.cb = (cbs + (size_t)T * 64)[lane];
         xpairs_load(r.x, (const uint16_t*)mt.x, T, lane);
+        if (MIXED) mix_load(r.xq, r.mi, wp, T, lane);
     };
     auto compute = [&](const Vq8M1Regs& r, int) {
         wave_lds_sync();
         *(uint4_t*)(cb_lds + 4 * lane) = r.cb;
         wave_lds_sync();
         uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
+        if (MIXED) mix_apply(r, wp, x0, x1);
         if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
         asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));     // vector-ALU write -> DPP read
         uint4_t g[2][4];
@@ -709,18 +772,20 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
 // column tiles s, s + S, s + 2S, ... and their partial sums meet in LDS in a fixed order.  The
 // grouped kernel above gives one wavefront a whole row tile, which keeps 4096 x 4096 on a quarter
 // of the SIMDs.
-template <int S>
-__global__ void __launch_bounds__(64 * S) decode_splitk_kernel(DecodeArgs a) {
+template <int S, class Args>
+__global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     constexpr int DEPTH = RWKVQ_DECODE_DEPTH;
+    constexpr bool MIXED = Args::kMixed;
     static_assert(kRT == 1, "one row tile per wavefront");
     __shared__ __attribute__((aligned(1024))) uint32_t cb_all[S][256];
+    __shared__ uint32_t cb_mix[MIXED ? S : 1][256];
     __shared__ float red[S][16];
     const int wg = blockIdx.x;
     int mi = 0;
 #pragma unroll
-    for (int j = 0; j < kMaxGroupMats; j += 64)
+    for (int j = 0; j < Args::kMats; j += 64)
         mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
-    const DecodeMat mt = a.m[mi];
+    const auto mt = a.m[mi];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KT = mt.K >> 8;
@@ -728,11 +793,16 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(DecodeArgs a) {
     wp.R[0] = wp.R[1] = wg - (mi ? a.wg_end[mi - 1] : 0);      // here wg_end counts row tiles
     wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
     wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
+    if constexpr (MIXED) {
+        for (int e = lane; e < mt.mix_E; e += 64) cb_mix[wave][e] = mt.mix_cb[e];
+        wave_lds_sync();
+        wp.xprev = mt.xprev; wp.mix_idx = mt.mix_idx; wp.mix_cb = cb_mix[wave];
+    }
     float part[kRT] = {0.f};
     if (wp.nt > 0) {
-        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true>(mt, wp, part);
-        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, true>(mt, wp, cb_all[wave], part);
-        else run_vq8_m1<DEPTH, true>(mt, wp, cb_all[wave], part);
+        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true, MIXED>(mt, wp, part);
+        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, true, MIXED>(mt, wp, cb_all[wave], part);
+        else run_vq8_m1<DEPTH, true, MIXED>(mt, wp, cb_all[wave], part);
     }
     float v = part[0];                             // sum the four column groups of each row
     v += __shfl_xor(v, 16, 64);
@@ -745,6 +815,49 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(DecodeArgs a) {
         for (int s = 1; s < S; ++s) t += red[s][lane];
         store_from_f32(mt.y, (size_t)16 * wp.R[0] + lane, a.ydt, t);
     }
+}
+
+// Smallest S of 4, 8, 16 that brings `tiles` row tiles to kSplitTarget wavefronts.
+static int pick_split(int tiles) { return tiles * 4 >= kSplitTarget ? 4 : tiles * 8 >= kSplitTarget ? 8 : 16; }
+
+template <class Args>
+static hipError_t launch_splitk(int split, int wgs, const Args& a, hipStream_t s) {
+    if (split == 4) hipLaunchKernelGGL((decode_splitk_kernel<4, Args>), dim3(wgs), dim3(256), 0, s, a);
+    else if (split == 8) hipLaunchKernelGGL((decode_splitk_kernel<8, Args>), dim3(wgs), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((decode_splitk_kernel<16, Args>), dim3(wgs), dim3(1024), 0, s, a);
+    return hipGetLastError();
+}
+
+// Batch 1 with the token-shift mix fused into the activation load: always the split-K kernel
+// (these are the stages of a block; 64 matrices per launch).
+hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_mats, int x_dtype, int y_dtype,
+                               hipStream_t s) {
+    for (int base = 0; base < n_mats; base += kMaxMixedMats) {
+        MixedDecodeArgs a;
+        const int cnt = n_mats - base < kMaxMixedMats ? n_mats - base : kMaxMixedMats;
+        int tiles = 0;
+        for (int i = 0; i < cnt; ++i) tiles += (mats[base + i].N + 15) / 16;
+        int wgs = 0;
+        for (int i = 0; i < kMaxMixedMats; ++i) {
+            if (i < cnt) {
+                const MatDev& m = mats[base + i];
+                const MixDev& x = mixes[base + i];
+                wgs += (m.N + 15) / 16;
+                MixedMat mm;
+                mm.codes = m.codes; mm.aux = m.aux; mm.x = m.x; mm.y = m.y; mm.N = m.N; mm.K = m.K; mm.fmt = m.fmt; mm.pad = 0;
+                mm.xprev = (const uint16_t*)x.x_prev; mm.mix_idx = x.idx; mm.mix_cb = (const uint32_t*)x.cb; mm.mix_E = x.E; mm.pad2 = 0;
+                a.m[i] = mm;
+                a.wg_end[i] = wgs;
+            } else {
+                a.m[i] = MixedMat{};
+                a.wg_end[i] = 0x7FFFFFFF;
+            }
+        }
+        a.M = 1; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
+        hipError_t e = launch_splitk(pick_split(tiles), wgs, a, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
@@ -763,7 +876,7 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         int tiles = 0;
         for (int i = 0; i < cnt; ++i) tiles += (mats[order[i]].N + 15) / 16;
         int split = 0;
-        if (M == 1 && tiles < kSplitTarget) split = tiles * 4 >= kSplitTarget ? 4 : tiles * 8 >= kSplitTarget ? 8 : 16;
+        if (M == 1 && tiles < kSplitTarget) split = pick_split(tiles);
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[order[i]];
@@ -776,9 +889,7 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
             a.wg_end[i] = 0x7FFFFFFF;
         }
         a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
-        if (split == 4) hipLaunchKernelGGL(decode_splitk_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
-        else if (split == 8) hipLaunchKernelGGL(decode_splitk_kernel<8>, dim3(wgs), dim3(512), 0, s, a);
-        else if (split == 16) hipLaunchKernelGGL(decode_splitk_kernel<16>, dim3(wgs), dim3(1024), 0, s, a);
+        if (split) { hipError_t e = launch_splitk(split, wgs, a, s); if (e != hipSuccess) return e; }
         else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
         else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
         else hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(256), 0, s, a);

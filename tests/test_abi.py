@@ -185,3 +185,26 @@ def test_mu_path_rejects():
     assert mx(P=9) == B.ERR_UNSUPPORTED
     assert mx(M=0) == B.ERR_SHAPE and mx(d=4100) == B.ERR_SHAPE and mx(d=0) == B.ERR_SHAPE
     assert mx(x=FAKE + 8) == B.ERR_ALIGN and mx(idx=arr(FAKE, FAKE + 1)) == B.ERR_ALIGN
+
+
+def test_dispatch_mixed_rejects():
+    L = B.lib()
+    good = B.rwkvq_matrix(B.SQ, B.NATIVE, 256, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, None, None)
+    canon = B.rwkvq_matrix(B.SQ, B.CANONICAL, 256, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, FAKE, None)
+    mix = lambda **kw: B.rwkvq_mix_input(kw.get("x", FAKE), kw.get("xp", FAKE), kw.get("idx", FAKE), kw.get("cb", FAKE),
+                                         kw.get("kbits", 6), 0)
+    from ctypes import c_void_p
+
+    def call(mat=good, m=None, y=FAKE, n=1, xdt=B.F16, ydt=B.F32, mats_null=False):
+        mats = (B.rwkvq_matrix * 1)(mat)
+        mixes = (B.rwkvq_mix_input * 1)(m if m is not None else mix())
+        ys = (c_void_p * 1)(y)
+        return L.rwkvq_linear_dispatch_mixed(None if mats_null else mats, mixes, ys, n, xdt, ydt, None)
+
+    assert call(mats_null=True) == B.ERR_NULL and call(y=None) == B.ERR_NULL
+    assert call(m=mix(x=None)) == B.ERR_NULL and call(m=mix(xp=None)) == B.ERR_NULL
+    assert call(m=mix(idx=None)) == B.ERR_NULL and call(m=mix(cb=None)) == B.ERR_NULL
+    assert call(n=0) == B.ERR_SHAPE
+    assert call(m=mix(kbits=7)) == B.ERR_UNSUPPORTED and call(mat=canon) == B.ERR_UNSUPPORTED
+    assert call(xdt=B.F32) == B.ERR_UNSUPPORTED
+    assert call(m=mix(xp=FAKE + 2)) == B.ERR_ALIGN and call(y=FAKE + 4) == B.ERR_ALIGN

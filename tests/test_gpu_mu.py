@@ -150,3 +150,46 @@ def test_calibrate_quantize_mix_gemv_chain():
         ref = orc.linear(mats[p], orc.widen(mixed, "f16"), "f64")
         err = np.abs(ys[p].cpu().numpy() - ref).max() / np.abs(ref).max()
         assert err < 2e-3, err
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("kbits", [6, 8])
+def test_fused_mix_gemv_equals_chain(dt, kbits):
+    """rwkvq_linear_dispatch_mixed against rwkvq_token_shift_mix followed by rwkvq_linear_dispatch on
+    the same matrices (bit for bit: same mixed values, same kernel shape), and against the oracle
+    chain; shapes that take 4, 8 and 16 wavefronts per row tile, all three weight formats."""
+    torch = G.torch_()
+    rng = np.random.default_rng(70 + kbits)
+    E = 1 << kbits
+    for shapes in ([(256, 512), (512, 256), (48, 768)], [(4096, 512)], [(8192, 256), (256, 3584)]):
+        mats = []
+        for j, (N, K) in enumerate(shapes):
+            kind = ("sq", "vq6", "vq8")[(j + kbits) % 3]
+            N_ = N if kind == "sq" else max(256, N // 256 * 256)
+            mats.append(synth.gen_sq(rng, N_, K) if kind == "sq" else synth.gen_vq(rng, N_, K, 6 if kind == "vq6" else 8))
+        dms = [B.upload(m, native=True) for m in mats]
+        xs = [synth.gen_activations(rng, 1, m.K, dt) for m in mats]
+        xps = [synth.gen_activations(rng, 1, m.K, dt)[0] for m in mats]
+        idx = [rng.integers(0, E, size=m.K // 2, dtype=np.uint8) for m in mats]
+        cbs = [synth.gen_codebook(rng, E).reshape(E, 2) for m in mats]
+        xd, xpd = [dev(x) for x in xs], [dev(x) for x in xps]
+        idd, cbd = [dev(i) for i in idx], [dev(c) for c in cbs]
+        # chain: one mix call per matrix (their K differ), then one dispatch
+        mixed = [torch.empty((1, m.K), dtype=torch.int16, device="cuda") for m in mats]
+        for m, x, xp, i, c, o in zip(mats, xd, xpd, idd, cbd, mixed):
+            B.rwkvq_token_shift_mix(x, xp, B.DTYPES[dt], 1, m.K, B.MixTable([i], [c], [o]), kbits)
+        y_chain = [torch.empty((1, m.N), dtype=torch.float32, device="cuda") for m in mats]
+        B.rwkvq_linear_dispatch(B.DispatchTable([d.desc() for d in dms], mixed, y_chain), 1, B.DTYPES[dt], B.F32)
+        y_fused = [torch.zeros((1, m.N), dtype=torch.float32, device="cuda") for m in mats]
+        table = B.MixedDispatchTable([d.desc() for d in dms],
+                                     [(x, xp, i, c, kbits) for x, xp, i, c in zip(xd, xpd, idd, cbd)], y_fused)
+        print(f"fused mix {dt} kbits={kbits} shapes={shapes}", flush=True)
+        B.rwkvq_linear_dispatch_mixed(table, B.DTYPES[dt], B.F32)
+        torch.cuda.synchronize()
+        for m, x, xp, i, c, yc, yf in zip(mats, xs, xps, idx, cbs, y_chain, y_fused):
+            assert torch.equal(yc, yf), (m.kind, m.N, m.K)
+            mu_hat = orc.widen(c, "f16")[i].reshape(-1)
+            xm = MO.narrow(MO.token_shift_mix(orc.widen(x, dt), orc.widen(xp, dt), mu_hat), dt)
+            ref = orc.linear(m, orc.widen(xm, dt), "f64")
+            err = np.abs(yf.cpu().numpy() - ref).max() / np.abs(ref).max()
+            assert err <= 2e-5, err
