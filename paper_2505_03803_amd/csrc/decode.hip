@@ -3,28 +3,30 @@
 // Computes y = x * Deq(W)^T (the W. products of App. A.1) for several matrices in one launch,
 // each SQ or VQ as its flag says (Sec. 3.1, Eq. "optimization goal").  The work is bound by
 // reading the packed weights once from HBM, so everything else is arranged around keeping
-// 16-byte coalesced loads in flight while spending as few issue slots per weight as possible:
+// 16-byte coalesced loads in flight while spending as few issue slots per weight as possible.
 //
-//   * One wavefront owns two adjacent 16-row tiles of one matrix and streams their 256-column
-//     tiles in order, DEPTH tiles ahead (about 3 KB per tile pair in flight).  Four such
-//     wavefronts form a workgroup (128 rows); after a short common prologue they share nothing.
-//   * The contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16) with the activations as
-//     the A operand (rows = batch index) and the weights as the B operand, so the vector ALU only
-//     has to turn packed fields into fp16 pairs.  With M = 1 fifteen of the sixteen A rows are
-//     idle, which costs nothing: the matrix cores have ~5x headroom at this arithmetic intensity.
-//     One A fragment read from LDS feeds both row tiles.
-//   * SQ: a 3-bit code q becomes the fp16 number 8 + q with one shift and one and-or (the code
-//     lands in the top mantissa bits of 0x4800).  Per group of 128 columns the accumulator starts
-//     at -8 * X (X = sum of the group's activations, computed once per workgroup in the prologue)
-//     so that it ends as sum q x exactly as an integer-weighted sum; scale and zero point are
-//     then applied in binary32:   y += s * (sum q x - z * X) = s * sum (q - z) x.
-//     q, 8 + q and the products are exact; only binary32 accumulation rounds.
-//   * VQ, 6-bit indices: the 64-entry codebook of the current 256 x 256 block is one 32-bit
-//     register across the wavefront (lane i holds entry i = two fp16 weights); ds_bpermute_b32
-//     gathers entry[index] straight into the B operand.  8-bit indices: the 256-entry codebook
-//     is staged in a wavefront-private LDS region and gathered with ds_read_b32.
-//   * Activations are staged per wavefront and per column tile in LDS (fp16; bf16 inputs are
-//     converted, exact for |x| in [2^-14, 65504]) and read back in A-operand order.
+//   * decode_kernel<MT>: one wavefront owns one 16-row tile of one matrix and streams its
+//     256-column tiles in order with DEPTH tiles in flight (tile_pipeline); four wavefronts form a
+//     workgroup (64 rows).  Up to 256 matrices per launch, longest rows first; a workgroup finds
+//     its matrix with ballots over the table in the kernel arguments.
+//   * Batch 1 (MT = 1), all formats, on the vector ALU: lane (r, kg) owns row r's columns of column
+//     group kg; the sixteen lanes of a row each load one activation pair, and every
+//     v_dot2c_f32_f16 names the lane that holds its pair through the DPP control row_newbcast - no
+//     LDS for the activations.  SQ codes are multiplied as they are: masked in place, a 3-bit code
+//     at mantissa bits b..b+2 of an fp16 half is the subnormal q 2^(b-24); three accumulators (one
+//     per bit position) are combined with exact powers of two per group, and
+//     y += s (sum q x - z X) with X from four DPP adds.  VQ weights are gathered pair by pair from
+//     the block's codebook in a wavefront-private LDS region.
+//   * decode_splitk_kernel<S>: batch 1 for launches too small to fill the device (the stages of a
+//     block): one workgroup of S wavefronts per row tile, the column tiles dealt round-robin, the
+//     partial sums added in LDS in a fixed order.  With MixedDecodeArgs the token-shift mix of
+//     Eq. "time mixing r/k/v" is applied while the activations are loaded.
+//   * Batch 2..16 (MT = 4, 16) on the matrix cores (v_mfma_f32_16x16x32_f16, activations = A
+//     operand, weights = B operand): the activation tile of a column tile is fetched once per
+//     workgroup into LDS (two buffers, one barrier per tile); SQ codes enter as 8 + q (one shift
+//     and one and-or per pair), the group sums X come from one more MFMA against an all-ones
+//     operand, y += s (acc - (8 + z) X); VQ pairs are LDS gathers.
+//   * bf16 activations are converted to fp16 on load (exact for |x| in [2^-14, 65504]).
 #include "common.h"
 #include <algorithm>
 

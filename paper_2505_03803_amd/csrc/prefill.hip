@@ -9,15 +9,16 @@
 // Tiling: workgroup = 256 threads = 2 x 2 wavefronts, block tile 256 (m) x 256 (n) x 64 (k),
 // wavefront tile 128 x 128 = 8 x 8 MFMA tiles (256 accumulator registers).  Both operand tiles
 // live in LDS as 256 rows of 128 bytes (64 k), with the eight 16-byte chunks of a row stored at
-// chunk ^ (row & 7): a row is exactly one pass over the 32 LDS banks, so any 8 consecutive rows
-// read the same logical chunk from 8 distinct bank groups - fragment reads (eight lanes of 16
-// bytes per cycle) and tile writes are conflict free without padding.
+// chunk ^ (row & 7), so that the 16-row fragment reads of the 16 x 16 x 32 MFMAs and the tile
+// writes are free of bank conflicts without padding (the conflict counter reads zero).
 //   * activations: copied global -> LDS by the load unit itself (global_load_lds_dwordx4), no
 //     registers and no vector-ALU work; each lane fetches the chunk that belongs at its slot;
 //   * weights: packed words are fetched once per 256 columns, unpacked by the vector ALU one
 //     k-step ahead of the matrix cores, and written with 16-byte LDS stores.
-// Two LDS buffers per operand; one workgroup barrier per k-step; waits on the load counter are
-// placed by hand (the activations of step i+1 are in flight during the MFMAs of step i).
+// Two LDS buffers for W and three for x (two with 8-bit VQ); one workgroup barrier per k-step;
+// waits on the load counter are placed by hand (the activations of step i + 2 are in flight during
+// the MFMAs of step i).  The unpack and the copies are cut into micro-slices placed right behind
+// individual MFMAs (see mma_step).
 //
 // Workgroup -> tile order: the m-tile index runs fastest, so workgroups that are dispatched
 // round-robin over the 8 XCDs keep one slice of x (256 rows) per XCD L2 when there are 8 m-tiles.
