@@ -129,7 +129,12 @@ int rwkvq_vq_gemm(const void* indices, const void* codebooks, int layout, const 
  * as its `kind` says, all enqueued on one stream as grouped launches (matrices share a launch;
  * there is no ordering between matrices of one call, so no ys[i] may alias an xs[j]).
  * `mats`, `xs` and `ys` are HOST arrays (of descriptors / device pointers) read before return.
- * All matrices share M and the dtypes.  xs[i] is [M][mats[i].K], ys[i] is [M][mats[i].N]. */
+ * All matrices share M and the dtypes.  xs[i] is [M][mats[i].K], ys[i] is [M][mats[i].N].
+ * Reproducibility: a call gives the same bits every time.  At M = 1 the kernel is chosen by the
+ * number of rows in the call (small calls split each row's columns over several wavefronts), so
+ * the same matrix dispatched alone and inside a large call may differ in the order of its
+ * binary32 sums (a few units in the last place); for 2 <= M and for M > 16 the order is fixed.
+ * No scratch memory; safe to record into a HIP graph. */
 int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void* const* ys,
                           int n_mats, int M, int x_dtype, int y_dtype, void* stream);
 
