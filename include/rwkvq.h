@@ -249,6 +249,28 @@ typedef struct rwkvq_mix_input {
 int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input* mixes, void* const* ys,
                                 int n_mats, int x_dtype, int y_dtype, void* stream);
 
+/* ---- element-wise operators of the RWKV block between the projections (App. A.1) ----
+ *
+ * rwkvq_wkv: Eq. "time mixing wkv" and the gate of Eq. "time mixing o" for a chunk of M tokens:
+ *   out[t][c] = sigma(r[t][c]) * wkv_t[c], the vector that W_o multiplies, with
+ *   wkv_t = (sum_{i<t} exp(-(t-1-i) w + k_i) v_i + exp(u + k_t) v_t) / (the same sums without v).
+ *   The sums over earlier tokens are carried in `state`, 3 x d floats (a[d], b[d], p[d]): they equal
+ *   a exp(p) and b exp(p); the call reads the state of the tokens before the chunk and leaves that
+ *   after it.  A new sequence starts from a = b = 0, p = -1e38 (then wkv_1 = v_1).  r, k, v, out:
+ *   DEVICE [M][d] of x_dtype (fp16 or bf16; out may not alias them); w (decay, positive forgets),
+ *   u (bonus of the current token): DEVICE [d] floats.  Binary32 arithmetic, every exp() argument
+ *   <= 0.  Sigma is the logistic function.
+ * rwkvq_relu2: out[i] = max(x[i], 0)^2 (Eq. "channel mixing o", the vector that W'_v multiplies).
+ * rwkvq_sigmoid_gate: out[i] = sigma(r[i]) * y[i] (the gates of Eq. "time mixing o" and "channel
+ *   mixing o").  n values of x_dtype each; out may alias an input.
+ * r, k, v, x, y, out 16-byte aligned, w, u, state 4; asynchronous on `stream`; no scratch memory.
+ * Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_UNSUPPORTED (dtype), RWKVQ_ERR_SHAPE, RWKVQ_ERR_ALIGN,
+ * RWKVQ_ERR_DEVICE. */
+int rwkvq_wkv(const void* r, const void* k, const void* v, int x_dtype, int M, int d, const float* w,
+              const float* u, float* state, void* out, void* stream);
+int rwkvq_relu2(const void* x, int x_dtype, long long n, void* out, void* stream);
+int rwkvq_sigmoid_gate(const void* r, const void* y, int x_dtype, long long n, void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -6,7 +6,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, Structure, c_char_p, c_double, c_int, c_int32, c_size_t, c_void_p
+from ctypes import POINTER, Structure, c_char_p, c_double, c_int, c_int32, c_longlong, c_size_t, c_void_p
 from dataclasses import dataclass
 from typing import Optional, Sequence
 
@@ -21,7 +21,8 @@ DTYPES = {"f16": F16, "bf16": BF16, "f32": F32}
 EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq_prepack",
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
-           "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed"]
+           "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
+           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate"]
 
 
 class rwkvq_mix_input(Structure):
@@ -101,6 +102,13 @@ def lib() -> ctypes.CDLL:
                                             c_void_p, c_void_p]
         L.rwkvq_linear_dispatch_mixed.restype = c_int
         L.rwkvq_linear_dispatch_mixed.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]
+        L.rwkvq_wkv.restype = c_int
+        L.rwkvq_wkv.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                c_void_p, c_void_p]
+        L.rwkvq_relu2.restype = c_int
+        L.rwkvq_relu2.argtypes = [c_void_p, c_int, c_longlong, c_void_p, c_void_p]
+        L.rwkvq_sigmoid_gate.restype = c_int
+        L.rwkvq_sigmoid_gate.argtypes = [c_void_p, c_void_p, c_int, c_longlong, c_void_p, c_void_p]
         _lib = L
     return _lib
 
@@ -400,3 +408,19 @@ def vq_assign(w, w_dtype: int, codebooks, kbits: int, stream=None) -> DeviceMatr
     idx = torch.empty((N, K // 2 * kbits // 32), dtype=torch.int32, device=w.device)
     rwkvq_vq_assign(w, w_dtype, codebooks, N, K, 2, kbits, 256, 256, idx, stream)
     return DeviceMatrix(VQ, CANONICAL, N, K, kbits, idx, None, None, codebooks, idx.numel() * 4 + codebooks.numel() * 2)
+
+
+def rwkvq_wkv(r, k, v, x_dtype, M, d, w, u, state, out, stream=None, check=True):
+    st = lib().rwkvq_wkv(_ptr(r), _ptr(k), _ptr(v), x_dtype, M, d, _ptr(w), _ptr(u), _ptr(state), _ptr(out),
+                         _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_relu2(x, x_dtype, n, out, stream=None, check=True):
+    st = lib().rwkvq_relu2(_ptr(x), x_dtype, n, _ptr(out), _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_sigmoid_gate(r, y, x_dtype, n, out, stream=None, check=True):
+    st = lib().rwkvq_sigmoid_gate(_ptr(r), _ptr(y), x_dtype, n, _ptr(out), _stream(stream))
+    return _check(st) if check else st

@@ -303,4 +303,33 @@ int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input*
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 
+int rwkvq_wkv(const void* r, const void* k, const void* v, int x_dtype, int M, int d, const float* w, const float* u,
+              float* state, void* out, void* stream) {
+    if (!r || !k || !v || !w || !u || !state || !out) return RWKVQ_ERR_NULL;
+    if (x_dtype != RWKVQ_F16 && x_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    if (M < 1 || d < 1 || (long long)M * d > (1ll << 40)) return RWKVQ_ERR_SHAPE;
+    if (!aligned16(r) || !aligned16(k) || !aligned16(v) || !aligned16(out) || ((uintptr_t)w & 3u) || ((uintptr_t)u & 3u) ||
+        ((uintptr_t)state & 3u))
+        return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_wkv(r, k, v, x_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, M, d, w, u, state, out, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
+static int pointwise(int op, const void* x, const void* y, int x_dtype, long long n, void* out, void* stream) {
+    if (!x || !y || !out) return RWKVQ_ERR_NULL;
+    if (x_dtype != RWKVQ_F16 && x_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    if (n < 1 || n > (1ll << 40)) return RWKVQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(out)) return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_pointwise(op, x, y, x_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, n, out, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
+int rwkvq_relu2(const void* x, int x_dtype, long long n, void* out, void* stream) {
+    return pointwise(0, x, x, x_dtype, n, out, stream);
+}
+
+int rwkvq_sigmoid_gate(const void* r, const void* y, int x_dtype, long long n, void* out, void* stream) {
+    return pointwise(1, r, y, x_dtype, n, out, stream);
+}
+
 }  // extern "C"

@@ -148,6 +148,9 @@ hipError_t launch_mu_codebook(const void* const* mus, const float* const* xbars,
                               int dt, int kbits, int iters, void* const* cbs, uint8_t* const* idx, hipStream_t s);
 hipError_t launch_token_shift_mix(const void* x, const void* x_prev, int dt, int M, int d, const uint8_t* const* idx,
                                   const void* const* cbs, int kbits, int n_proj, void* const* outs, hipStream_t s);
+hipError_t launch_wkv(const void* r, const void* k, const void* v, int dt, int M, int d, const float* w, const float* u,
+                      float* state, void* out, hipStream_t s);
+hipError_t launch_pointwise(int op, const void* x, const void* y, int dt, long long n, void* out, hipStream_t s);
 
 constexpr int kDecodeMaxM = 16;    // native layout: M <= this goes to the streaming kernels
 constexpr int kDecodeMaxK = 20480; // ... whose per-group activation sums for K columns fit their LDS

@@ -205,3 +205,18 @@ def gen_calibration(rng: np.random.Generator, n_samples: int, n: int, dtype: str
 def gen_codebook(rng: np.random.Generator, entries: int, lo: float = 0.0, hi: float = 1.0) -> np.ndarray:
     """[entries][2] fp16 bit patterns drawn uniformly from [lo, hi): an initial codebook."""
     return f32_to_f16_bits(rng.uniform(lo, hi, size=(entries, 2)).astype(np.float32))
+
+
+def gen_block_inputs(rng: np.random.Generator, M: int, d: int, dtype: str):
+    """Inputs of the element-wise operators of an RWKV block (App. A.1) for a chunk of M tokens:
+    receptance, key, value [M][d] as 16-bit patterns (keys with a wider spread and a few large
+    entries, since they sit in an exponent), decay w [d] > 0 spread over e^-5 .. e^1 as in a trained
+    RWKV-4 (log-uniform), bonus u [d] ~ N(0, 0.5)."""
+    narrow = f32_to_f16_bits if dtype == "f16" else f32_to_bf16_bits
+    r = rng.standard_normal(size=(M, d), dtype=np.float32) * 2.0
+    k = rng.standard_normal(size=(M, d), dtype=np.float32) * 3.0
+    k[rng.random(size=(M, d)) < 0.01] *= 8.0
+    v = rng.standard_normal(size=(M, d), dtype=np.float32)
+    w = np.exp(rng.uniform(-5.0, 1.0, size=d)).astype(np.float32)
+    u = (rng.standard_normal(size=d) * 0.5).astype(np.float32)
+    return narrow(r), narrow(k), narrow(v), w, u

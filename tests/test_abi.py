@@ -208,3 +208,23 @@ def test_dispatch_mixed_rejects():
     assert call(m=mix(kbits=7)) == B.ERR_UNSUPPORTED and call(mat=canon) == B.ERR_UNSUPPORTED
     assert call(xdt=B.F32) == B.ERR_UNSUPPORTED
     assert call(m=mix(xp=FAKE + 2)) == B.ERR_ALIGN and call(y=FAKE + 4) == B.ERR_ALIGN
+
+
+def test_block_operators_reject():
+    L = B.lib()
+    wk = lambda **kw: L.rwkvq_wkv(*[kw.get(k, v) for k, v in
+                                    [("r", FAKE), ("k", FAKE), ("v", FAKE), ("dt", B.F16), ("M", 1), ("d", 4096), ("w", FAKE),
+                                     ("u", FAKE), ("state", FAKE), ("out", FAKE), ("stream", None)]])
+    for name in ("r", "k", "v", "w", "u", "state", "out"):
+        assert wk(**{name: None}) == B.ERR_NULL
+    assert wk(dt=B.F32) == B.ERR_UNSUPPORTED and wk(dt=9) == B.ERR_UNSUPPORTED
+    assert wk(M=0) == B.ERR_SHAPE and wk(d=0) == B.ERR_SHAPE
+    assert wk(r=FAKE + 2) == B.ERR_ALIGN and wk(out=FAKE + 8) == B.ERR_ALIGN and wk(state=FAKE + 2) == B.ERR_ALIGN
+    assert L.rwkvq_relu2(None, B.F16, 8, FAKE, None) == B.ERR_NULL
+    assert L.rwkvq_relu2(FAKE, B.F32, 8, FAKE, None) == B.ERR_UNSUPPORTED
+    assert L.rwkvq_relu2(FAKE, B.F16, 0, FAKE, None) == B.ERR_SHAPE
+    assert L.rwkvq_relu2(FAKE + 2, B.F16, 8, FAKE, None) == B.ERR_ALIGN
+    assert L.rwkvq_sigmoid_gate(FAKE, None, B.BF16, 8, FAKE, None) == B.ERR_NULL
+    assert L.rwkvq_sigmoid_gate(FAKE, FAKE, 7, 8, FAKE, None) == B.ERR_UNSUPPORTED
+    assert L.rwkvq_sigmoid_gate(FAKE, FAKE, B.BF16, -1, FAKE, None) == B.ERR_SHAPE
+    assert L.rwkvq_sigmoid_gate(FAKE, FAKE, B.BF16, 8, FAKE + 4, None) == B.ERR_ALIGN
