@@ -80,10 +80,10 @@ def sequential_step(dec, n_layers):
     """One token through the stack with the dependencies of an RWKV block between the launches:
     per layer  mix (4 projections) -> {receptance, key, value, gate} -> output -> mix (2) ->
     {channel key, channel receptance} -> channel value, each stage reading the buffer the stage
-    before wrote (6 launches per layer, recorded once into a HIP graph and replayed).  The
-    element-wise operators between the stages (WKV recurrence, sigmoid, squared ReLU, norms) are
-    not part of this build: the values that flow are not a model's, the launch structure and the
-    bytes are.  Reported next to the grouped figure to show what the dependencies cost."""
+    before wrote (6 launches per layer, recorded once into a HIP graph and replayed); then with the
+    mixes fused into the GEMVs (4 launches), and with the element-wise operators of the block between
+    them (7 launches).  The values that flow are not a model's, the launch structure and the bytes
+    are.  Reported next to the grouped figure to show what the dependencies cost."""
     import torch
     from paper_2505_03803_amd import binding as B
     from paper_2505_03803_amd import synth
@@ -138,6 +138,66 @@ def sequential_step(dec, n_layers):
             else:
                 B.rwkvq_linear_dispatch(table, 1, B.F16, B.F16)
 
+    # the whole block as App. A.1 chains it: the element-wise operators between the GEMVs as well
+    # (wkv recurrence with its gate, squared ReLU, output gate): 7 launches per layer.  The gate
+    # projection of the 7B stack (not in the appendix) still runs; nothing consumes its output.
+    block = []
+    ffn = dec["ys"][5].shape[1]
+    for layer in range(n_layers):
+        D = dec["descs"][8 * layer: 8 * layer + 8]
+        Y = dec["ys"][8 * layer: 8 * layer + 8]
+        m4, m2 = stages[6 * layer][1], stages[6 * layer + 3][1]
+        src4 = h if layer == 0 else block[-1][1][2]              # the previous block's output
+        _, _, _, w, u = synth.gen_block_inputs(rng, 1, d, "f16")
+        st = np.zeros((3, d), dtype=np.float32); st[2] = -1e38
+        wd, ud, state = torch.from_numpy(w).cuda(), torch.from_numpy(u).cuda(), torch.from_numpy(st).cuda()
+        gated, sq, outb = (torch.zeros((1, n), dtype=torch.int16, device="cuda") for n in (d, ffn, d))
+        block.append(("mixed", B.MixedDispatchTable(D[0:4], [(src4, hprev, m4.keep[0][p], m4.keep[1][p], 6) for p in range(4)], Y[0:4])))
+        block.append(("wkv", (Y[0], Y[1], Y[2], wd, ud, state, gated)))
+        block.append(("lin", B.DispatchTable([D[4]], [gated], [Y[4]])))
+        block.append(("mixed", B.MixedDispatchTable([D[5], D[7]], [(Y[4], hprev, m2.keep[0][p], m2.keep[1][p], 6) for p in range(2)], [Y[5], Y[7]])))
+        block.append(("relu2", (Y[5], sq)))
+        block.append(("lin", B.DispatchTable([D[6]], [sq], [Y[6]])))
+        block.append(("gate", (Y[7], Y[6], outb)))
+
+    def step_block():
+        for kind, a in block:
+            if kind == "mixed":
+                B.rwkvq_linear_dispatch_mixed(a, B.F16, B.F16)
+            elif kind == "lin":
+                B.rwkvq_linear_dispatch(a, 1, B.F16, B.F16)
+            elif kind == "wkv":
+                B.rwkvq_wkv(a[0], a[1], a[2], B.F16, 1, d, a[3], a[4], a[5], a[6])
+            elif kind == "relu2":
+                B.rwkvq_relu2(a[0], B.F16, ffn, a[1])
+            else:
+                B.rwkvq_sigmoid_gate(a[0], a[1], B.F16, d, a[2])
+
+    # the same block with the squared ReLU and the output gate applied by the GEMVs that produce
+    # their operands (rwkvq_linear_dispatch_post): 5 launches per layer, the same bits
+    block5 = []
+    for layer in range(n_layers):
+        D = dec["descs"][8 * layer: 8 * layer + 8]
+        Y = dec["ys"][8 * layer: 8 * layer + 8]
+        b7 = block[7 * layer: 7 * layer + 7]
+        m2 = stages[6 * layer + 3][1]
+        sq, outb = b7[4][1][1], b7[6][1][2]
+        block5.append(b7[0]); block5.append(b7[1]); block5.append(b7[2])
+        block5.append(("post", B.PostDispatchTable([D[5], D[7]], None, [(Y[4], hprev, m2.keep[0][p], m2.keep[1][p], 6) for p in range(2)],
+                                                   [(B.POST_RELU2, None), (B.POST_NONE, None)], [sq, Y[7]])))
+        block5.append(("post", B.PostDispatchTable([D[6]], [sq], None, [(B.POST_SIGMOID_GATE, Y[7])], [outb])))
+
+    def step_block5():
+        for kind, a in block5:
+            if kind == "mixed":
+                B.rwkvq_linear_dispatch_mixed(a, B.F16, B.F16)
+            elif kind == "lin":
+                B.rwkvq_linear_dispatch(a, 1, B.F16, B.F16)
+            elif kind == "wkv":
+                B.rwkvq_wkv(a[0], a[1], a[2], B.F16, 1, d, a[3], a[4], a[5], a[6])
+            else:
+                B.rwkvq_linear_dispatch_post(a, B.F16, B.F16)
+
     def timed(fn):
         fn()
         torch.cuda.synchronize()
@@ -149,13 +209,20 @@ def sequential_step(dec, n_layers):
 
     ms = timed(step)
     ms_fused = timed(step_fused)
+    ms_block7 = timed(step_block)
+    ms_block = timed(step_block5)
     eager_ms = time_steps(step, 200, 50)[0] / 200
     return {"ms_per_step": ms_fused, "tokens_per_s": 1e3 / ms_fused, "value": dec["wbytes"] / (ms_fused * 1e-3) / 1e9,
             "unit": "GB/s", "launches_per_step": len(fused),
             "unfused": {"ms_per_step": ms, "launches_per_step": len(stages), "eager_ms_per_step": eager_ms},
+            "block": {"ms_per_step": ms_block, "tokens_per_s": 1e3 / ms_block, "launches_per_step": len(block5),
+                      "separate_operators": {"ms_per_step": ms_block7, "launches_per_step": len(block)},
+                      "note": "with the element-wise operators of the block: wkv recurrence and its gate as one "
+                              "launch, squared ReLU and output gate applied by the GEMVs that produce their operands "
+                              "(5 launches per layer); separate_operators = each operator a launch of its own (7)"},
             "note": "same 256 matrices, data-flow order, 4 launches per layer (token-shift mixes fused into the "
                     "GEMVs) in one HIP graph; unfused = 6 launches per layer with separate mix passes; "
-                    "element-wise operators between the stages not built"}
+                    "block = the fused step plus the element-wise operators between the stages"}
 
 
 def time_steps(run, steps: int, warmup: int):

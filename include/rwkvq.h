@@ -271,6 +271,30 @@ int rwkvq_wkv(const void* r, const void* k, const void* v, int x_dtype, int M, i
 int rwkvq_relu2(const void* x, int x_dtype, long long n, void* out, void* stream);
 int rwkvq_sigmoid_gate(const void* r, const void* y, int x_dtype, long long n, void* out, void* stream);
 
+/* rwkvq_linear_dispatch_post: batch-1 projections with the element-wise operator that follows them
+ *   in the block (App. A.1) applied before the output is stored, and optionally the token-shift mix
+ *   in front (as rwkvq_linear_dispatch_mixed).  For matrix i, with y = Deq(W_i) . x_i rounded to
+ *   y_dtype:  RWKVQ_POST_NONE stores y;  RWKVQ_POST_RELU2 stores max(y, 0)^2 (the input of W'_v,
+ *   Eq. "channel mixing o");  RWKVQ_POST_SIGMOID_GATE stores sigma(gate[n]) * y[n] (Eq. "time mixing
+ *   o", "channel mixing o"), gate: DEVICE [N_i] values of y_dtype written by an EARLIER call or
+ *   launch (not by another matrix of this call).  The operator works in binary32 on the rounded y and
+ *   its result is rounded to y_dtype: bit for bit what rwkvq_linear_dispatch (or _mixed) followed by
+ *   rwkvq_relu2 / rwkvq_sigmoid_gate stores, without the launch and the pass in between.
+ *   mixes == NULL: xs[i] is the input of matrix i ([K_i] of x_dtype).  mixes != NULL: mixes[i]
+ *   describes it (x, x_prev and the quantized mix weight), xs is not read and may be NULL.
+ *   mats: native layout, K <= 20480; posts, mats, xs, ys, mixes: HOST arrays, read before return.
+ *   Errors as rwkvq_linear_dispatch_mixed; RWKVQ_ERR_UNSUPPORTED also for an unknown op,
+ *   RWKVQ_ERR_NULL for a missing gate. */
+enum { RWKVQ_POST_NONE = 0, RWKVQ_POST_RELU2 = 1, RWKVQ_POST_SIGMOID_GATE = 2 };
+typedef struct rwkvq_post_op {
+    int32_t op;         /* RWKVQ_POST_* */
+    int32_t reserved;
+    const void* gate;   /* DEVICE, RWKVQ_POST_SIGMOID_GATE only */
+} rwkvq_post_op;
+int rwkvq_linear_dispatch_post(const rwkvq_matrix* mats, const void* const* xs, const rwkvq_mix_input* mixes,
+                               const rwkvq_post_op* posts, void* const* ys, int n_mats, int x_dtype, int y_dtype,
+                               void* stream);
+
 #ifdef __cplusplus
 }
 #endif

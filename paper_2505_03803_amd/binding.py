@@ -22,12 +22,19 @@ EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
            "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
-           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate"]
+           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post"]
 
 
 class rwkvq_mix_input(Structure):
     _fields_ = [("x", c_void_p), ("x_prev", c_void_p), ("indices", c_void_p), ("codebook", c_void_p),
                 ("kbits", c_int32), ("reserved", c_int32)]
+
+
+class rwkvq_post_op(Structure):
+    _fields_ = [("op", c_int32), ("reserved", c_int32), ("gate", c_void_p)]
+
+
+POST_NONE, POST_RELU2, POST_SIGMOID_GATE = 0, 1, 2
 
 
 class rwkvq_matrix(Structure):
@@ -102,6 +109,9 @@ def lib() -> ctypes.CDLL:
                                             c_void_p, c_void_p]
         L.rwkvq_linear_dispatch_mixed.restype = c_int
         L.rwkvq_linear_dispatch_mixed.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]
+        L.rwkvq_linear_dispatch_post.restype = c_int
+        L.rwkvq_linear_dispatch_post.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
+                                                 c_void_p]
         L.rwkvq_wkv.restype = c_int
         L.rwkvq_wkv.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
                                 c_void_p, c_void_p]
@@ -423,4 +433,27 @@ def rwkvq_relu2(x, x_dtype, n, out, stream=None, check=True):
 
 def rwkvq_sigmoid_gate(r, y, x_dtype, n, out, stream=None, check=True):
     st = lib().rwkvq_sigmoid_gate(_ptr(r), _ptr(y), x_dtype, n, _ptr(out), _stream(stream))
+    return _check(st) if check else st
+
+
+class PostDispatchTable:
+    """Host arrays for rwkvq_linear_dispatch_post: descriptors, inputs (xs: device tensors, or mixes:
+    (x, x_prev, indices, codebook, kbits) per matrix), posts: (op, gate tensor or None) per matrix."""
+
+    def __init__(self, descs: Sequence, xs: Optional[Sequence], mixes: Optional[Sequence], posts: Sequence, ys: Sequence):
+        n = len(descs)
+        assert len(posts) == n and len(ys) == n and (xs is None or len(xs) == n) and (mixes is None or len(mixes) == n)
+        self.n = n
+        self.mats = (rwkvq_matrix * n)(*descs)
+        self.xs = _ptr_array(xs) if xs is not None else None
+        self.mixes = None if mixes is None else (rwkvq_mix_input * n)(
+            *[rwkvq_mix_input(_ptr(x), _ptr(xp), _ptr(ix), _ptr(cb), int(kb), 0) for x, xp, ix, cb, kb in mixes])
+        self.posts = (rwkvq_post_op * n)(*[rwkvq_post_op(int(op), 0, _ptr(g)) for op, g in posts])
+        self.ys = _ptr_array(ys)
+        self.keep = (xs, mixes, posts, ys)
+
+
+def rwkvq_linear_dispatch_post(table: PostDispatchTable, x_dtype, y_dtype, stream=None, check=True):
+    st = lib().rwkvq_linear_dispatch_post(table.mats, table.xs, table.mixes, table.posts, table.ys, table.n, x_dtype,
+                                          y_dtype, _stream(stream))
     return _check(st) if check else st

@@ -303,6 +303,43 @@ int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input*
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 
+int rwkvq_linear_dispatch_post(const rwkvq_matrix* mats, const void* const* xs, const rwkvq_mix_input* mixes,
+                               const rwkvq_post_op* posts, void* const* ys, int n_mats, int x_dtype, int y_dtype,
+                               void* stream) {
+    if (!mats || !posts || !ys || (!xs && !mixes)) return RWKVQ_ERR_NULL;
+    if (n_mats <= 0) return RWKVQ_ERR_SHAPE;
+    int st;
+    if ((st = check_dtype_x(x_dtype)) != RWKVQ_OK) return st;
+    if ((st = check_dtype_y(y_dtype)) != RWKVQ_OK) return st;
+    std::vector<MatDev> md((size_t)n_mats);
+    std::vector<MixDev> xd((size_t)n_mats);
+    std::vector<PostDev> pd((size_t)n_mats);
+    for (int i = 0; i < n_mats; ++i) {
+        const void* x = mixes ? mixes[i].x : xs[i];
+        if (!x || !ys[i]) return RWKVQ_ERR_NULL;
+        if (!aligned16(x) || !aligned16(ys[i])) return RWKVQ_ERR_ALIGN;
+        if (mixes) {
+            const rwkvq_mix_input& m = mixes[i];
+            if (!m.x_prev || !m.indices || !m.codebook) return RWKVQ_ERR_NULL;
+            if (m.kbits != 6 && m.kbits != 8) return RWKVQ_ERR_UNSUPPORTED;
+            if (!aligned16(m.x_prev) || !aligned16(m.indices) || !aligned16(m.codebook)) return RWKVQ_ERR_ALIGN;
+            xd[(size_t)i] = MixDev{m.x_prev, m.indices, (const uint16_t*)m.codebook, 1 << m.kbits};
+        }
+        const rwkvq_post_op& p = posts[i];
+        if (p.op != RWKVQ_POST_NONE && p.op != RWKVQ_POST_RELU2 && p.op != RWKVQ_POST_SIGMOID_GATE) return RWKVQ_ERR_UNSUPPORTED;
+        if (p.op == RWKVQ_POST_SIGMOID_GATE) {
+            if (!p.gate) return RWKVQ_ERR_NULL;
+            if (!aligned16(p.gate)) return RWKVQ_ERR_ALIGN;
+        }
+        pd[(size_t)i] = PostDev{p.op, p.op == RWKVQ_POST_SIGMOID_GATE ? p.gate : nullptr};
+        if ((st = to_dev(mats[i], x, ys[i], &md[(size_t)i])) != RWKVQ_OK) return st;
+        if (md[(size_t)i].layout != RWKVQ_NATIVE || md[(size_t)i].K > kDecodeMaxK) return RWKVQ_ERR_UNSUPPORTED;
+    }
+    hipError_t e = mixes ? launch_decode_mixed(md.data(), xd.data(), n_mats, x_dtype, y_dtype, (hipStream_t)stream, pd.data())
+                         : launch_decode(md.data(), n_mats, 1, x_dtype, y_dtype, (hipStream_t)stream, pd.data());
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
 int rwkvq_wkv(const void* r, const void* k, const void* v, int x_dtype, int M, int d, const float* w, const float* u,
               float* state, void* out, void* stream) {
     if (!r || !k || !v || !w || !u || !state || !out) return RWKVQ_ERR_NULL;

@@ -15,8 +15,6 @@
 
 namespace rwkvq {
 
-__device__ __forceinline__ float sigmoid_f32(float r) { return 1.0f / (1.0f + expf(-r)); }
-
 template <bool BF16>
 __device__ __forceinline__ float ld16(const uint16_t* p, size_t i) {
     return BF16 ? bf16_bits_to_f32(p[i]) : f16_bits_to_f32(p[i]);
@@ -54,7 +52,7 @@ __global__ void __launch_bounds__(64) wkv_kernel(const uint16_t* __restrict__ r,
                 const float q = fmaxf(p, ww);
                 const float e1 = expf(p - q), e2 = expf(ww - q);
                 const float wkv = (e1 * a + e2 * vv[j]) / (e1 * b + e2);
-                out[(size_t)(t0 + j) * d + c] = st16<BF16>(sigmoid_f32(rr[j]) * wkv);
+                out[(size_t)(t0 + j) * d + c] = st16<BF16>(gate_f32(rr[j], wkv));
                 // advance the sums: decay by exp(-w), add the current token without the bonus
                 const float pw = p - wc;
                 const float q2 = fmaxf(pw, kk[j]);
@@ -92,7 +90,7 @@ __global__ void __launch_bounds__(256) pointwise_kernel(const uint16_t* __restri
                     r[h] = m * m;
                 } else {
                     const float yf = BF16 ? bf16_bits_to_f32(yb) : f16_bits_to_f32(yb);
-                    r[h] = sigmoid_f32(xf) * yf;
+                    r[h] = gate_f32(xf, yf);
                 }
             }
             o[j] = (uint32_t)st16<BF16>(r[0]) | ((uint32_t)st16<BF16>(r[1]) << 16);
@@ -106,7 +104,7 @@ __global__ void __launch_bounds__(256) pointwise_kernel(const uint16_t* __restri
                 const float m = fmaxf(xf, 0.0f);
                 r = m * m;
             } else {
-                r = sigmoid_f32(xf) * ld16<BF16>(y, (size_t)i);
+                r = gate_f32(xf, ld16<BF16>(y, (size_t)i));
             }
             out[i] = st16<BF16>(r);
         }

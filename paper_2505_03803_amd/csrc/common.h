@@ -59,6 +59,17 @@ __device__ __forceinline__ void store_from_f32(void* p, size_t i, int dt, float 
     else ((float*)p)[i] = v;
 }
 
+// The logistic function of the block's gates (App. A.1), binary32.
+__device__ __forceinline__ float sigmoid_f32(float r) { return 1.0f / (1.0f + expf(-r)); }
+// sigma(r) * y as a binary32 product of its own.  The empty asm keeps the compiler from merging the
+// multiplication with the conversion to a 16-bit type that follows it (one mixed-precision
+// instruction, one rounding instead of two): every kernel that applies a gate must store the same bits.
+__device__ __forceinline__ float gate_f32(float r, float y) {
+    float p = sigmoid_f32(r) * y;
+    asm volatile("" : "+v"(p));
+    return p;
+}
+
 // The SQ inverse of Sec. 2.2 Eq. "SQ": subtract, round, multiply, round.  The intrinsics keep
 // the compiler from fusing the two steps.
 __device__ __forceinline__ float sq_deq(uint32_t q, float s, float z) {
@@ -127,10 +138,14 @@ hipError_t launch_ref_gemm(const MatDev& m, int M, int x_dtype, int y_dtype, hip
 // The token-shift mix in front of a batch-1 GEMV: the previous token's activations and the mix
 // weight (indices of 2-vectors, one per column pair, and its codebook of E fp16 pairs).
 struct MixDev { const void* x_prev; const uint8_t* idx; const uint16_t* cb; int E; };
+// Element-wise operator on a batch-1 projection's output (values as in rwkvq.h's RWKVQ_POST_*).
+enum PostOp : int { POST_NONE = 0, POST_RELU2 = 1, POST_SIGMOID_GATE = 2 };
+struct PostDev { int op; const void* gate; };
+// posts: nullptr, or one PostDev per matrix (M must be 1 then)
 hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_mats, int x_dtype, int y_dtype,
-                               hipStream_t s);
+                               hipStream_t s, const PostDev* posts = nullptr);
 hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype,
-                         hipStream_t s);
+                         hipStream_t s, const PostDev* posts = nullptr);
 hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype,
                           hipStream_t s);
 

@@ -58,7 +58,9 @@ struct DecodeMat {
     const uint16_t* aux;
     const void* x;
     void* y;
-    int N, K, fmt, pad;
+    int N, K, fmt;
+    int post;                         // PostOp applied to the output before it is stored (batch 1)
+    const void* gate;                 // POST_SIGMOID_GATE: [N] values of the output type
 };
 // A matrix whose input is mixed on the fly: x (of DecodeMat) is x_t.
 struct MixedMat : DecodeMat {
@@ -82,6 +84,25 @@ struct DecodeArgs {                   // 13 KB of kernel arguments
     DecodeMat m[kMaxGroupMats];
     int M, xdt, ydt, pad;
 };
+
+// Batch-1 output with the element-wise operator that follows the projection in the block (App. A.1)
+// applied on the way out.  The value is first rounded to the output type, as a separate pass would
+// have read it from memory, then max(y, 0)^2 (Eq. "channel mixing o", input of W'_v) or
+// sigma(gate) * y (the gates of Eq. "time mixing o" / "channel mixing o") in binary32, then rounded
+// for the store: the same bits as the projection followed by rwkvq_relu2 / rwkvq_sigmoid_gate.
+__device__ __forceinline__ void store_post(const DecodeMat& mt, size_t i, int ydt, float v) {
+    if (mt.post != POST_NONE) {
+        if (ydt == DT_F16) v = f16_bits_to_f32(f32_to_f16_bits(v));
+        else if (ydt == DT_BF16) v = bf16_bits_to_f32(f32_to_bf16_bits(v));
+        if (mt.post == POST_RELU2) {
+            const float m = fmaxf(v, 0.0f);
+            v = m * m;
+        } else {
+            v = gate_f32(load_as_f32(mt.gate, i, ydt), v);
+        }
+    }
+    store_from_f32(mt.y, i, ydt, v);
+}
 
 template <int P>
 __device__ __forceinline__ uint32_t sq_pair_f16(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t mask,
@@ -741,7 +762,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
             float v = part[rt];                    // sum the four column groups of each row
             v += __shfl_xor(v, 16, 64);
             v += __shfl_xor(v, 32, 64);
-            if (lane < 16) store_from_f32(mt.y, (size_t)16 * wp.R[rt] + lane, a.ydt, v);
+            if (lane < 16) store_post(mt, (size_t)16 * wp.R[rt] + lane, a.ydt, v);
         }
     } else {
         // every wavefront takes part in the shared activation tiles and their barriers; one
@@ -815,7 +836,7 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
         float t = red[0][lane];
 #pragma unroll
         for (int s = 1; s < S; ++s) t += red[s][lane];
-        store_from_f32(mt.y, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+        store_post(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
     }
 }
 
@@ -833,7 +854,7 @@ static hipError_t launch_splitk(int split, int wgs, const Args& a, hipStream_t s
 // Batch 1 with the token-shift mix fused into the activation load: always the split-K kernel
 // (these are the stages of a block; 64 matrices per launch).
 hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_mats, int x_dtype, int y_dtype,
-                               hipStream_t s) {
+                               hipStream_t s, const PostDev* posts) {
     for (int base = 0; base < n_mats; base += kMaxMixedMats) {
         MixedDecodeArgs a;
         const int cnt = n_mats - base < kMaxMixedMats ? n_mats - base : kMaxMixedMats;
@@ -846,7 +867,8 @@ hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_ma
                 const MixDev& x = mixes[base + i];
                 wgs += (m.N + 15) / 16;
                 MixedMat mm;
-                mm.codes = m.codes; mm.aux = m.aux; mm.x = m.x; mm.y = m.y; mm.N = m.N; mm.K = m.K; mm.fmt = m.fmt; mm.pad = 0;
+                mm.codes = m.codes; mm.aux = m.aux; mm.x = m.x; mm.y = m.y; mm.N = m.N; mm.K = m.K; mm.fmt = m.fmt;
+                mm.post = posts ? posts[base + i].op : POST_NONE; mm.gate = posts ? posts[base + i].gate : nullptr;
                 mm.xprev = (const uint16_t*)x.x_prev; mm.mix_idx = x.idx; mm.mix_cb = (const uint32_t*)x.cb; mm.mix_E = x.E; mm.pad2 = 0;
                 a.m[i] = mm;
                 a.wg_end[i] = wgs;
@@ -862,7 +884,8 @@ hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_ma
     return hipSuccess;
 }
 
-hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
+hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s,
+                         const PostDev* posts) {
     for (int base = 0; base < n_mats; base += kMaxGroupMats) {
         DecodeArgs a;
         int cnt = n_mats - base < kMaxGroupMats ? n_mats - base : kMaxGroupMats;
@@ -883,11 +906,12 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[order[i]];
             wgs += split ? (m.N + 15) / 16 : (m.N + kWgRows - 1) / kWgRows;
-            a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, 0};
+            a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, posts ? posts[order[i]].op : POST_NONE,
+                               posts ? posts[order[i]].gate : nullptr};
             a.wg_end[i] = wgs;
         }
         for (int i = cnt; i < kMaxGroupMats; ++i) {
-            a.m[i] = DecodeMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+            a.m[i] = DecodeMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, POST_NONE, nullptr};
             a.wg_end[i] = 0x7FFFFFFF;
         }
         a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;

@@ -228,3 +228,30 @@ def test_block_operators_reject():
     assert L.rwkvq_sigmoid_gate(FAKE, FAKE, 7, 8, FAKE, None) == B.ERR_UNSUPPORTED
     assert L.rwkvq_sigmoid_gate(FAKE, FAKE, B.BF16, -1, FAKE, None) == B.ERR_SHAPE
     assert L.rwkvq_sigmoid_gate(FAKE, FAKE, B.BF16, 8, FAKE + 4, None) == B.ERR_ALIGN
+
+
+def test_dispatch_post_rejects():
+    from ctypes import c_void_p
+    L = B.lib()
+    good = B.rwkvq_matrix(B.SQ, B.NATIVE, 256, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, None, None)
+    canon = B.rwkvq_matrix(B.SQ, B.CANONICAL, 256, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, FAKE, None)
+    mix = lambda **kw: B.rwkvq_mix_input(kw.get("x", FAKE), kw.get("xp", FAKE), kw.get("idx", FAKE), kw.get("cb", FAKE),
+                                         kw.get("kbits", 6), 0)
+
+    def call(mat=good, x=FAKE, m=None, op=B.POST_RELU2, gate=None, y=FAKE, n=1, xdt=B.F16, ydt=B.F16, no_x=False,
+             no_posts=False):
+        mats = (B.rwkvq_matrix * 1)(mat)
+        xs = None if no_x else (c_void_p * 1)(x)
+        mixes = None if m is None else (B.rwkvq_mix_input * 1)(m)
+        posts = None if no_posts else (B.rwkvq_post_op * 1)(B.rwkvq_post_op(op, 0, gate))
+        ys = (c_void_p * 1)(y)
+        return L.rwkvq_linear_dispatch_post(mats, xs, mixes, posts, ys, n, xdt, ydt, None)
+
+    assert call(no_posts=True) == B.ERR_NULL and call(no_x=True) == B.ERR_NULL and call(x=None) == B.ERR_NULL
+    assert call(y=None) == B.ERR_NULL and call(op=B.POST_SIGMOID_GATE, gate=None) == B.ERR_NULL
+    assert call(m=mix(xp=None), no_x=True) == B.ERR_NULL and call(m=mix(x=None)) == B.ERR_NULL
+    assert call(op=3) == B.ERR_UNSUPPORTED and call(op=-1) == B.ERR_UNSUPPORTED and call(mat=canon) == B.ERR_UNSUPPORTED
+    assert call(m=mix(kbits=5)) == B.ERR_UNSUPPORTED and call(xdt=B.F32) == B.ERR_UNSUPPORTED
+    assert call(n=0) == B.ERR_SHAPE
+    assert call(op=B.POST_SIGMOID_GATE, gate=FAKE + 2) == B.ERR_ALIGN and call(x=FAKE + 8) == B.ERR_ALIGN
+    assert call(m=mix(idx=FAKE + 1)) == B.ERR_ALIGN

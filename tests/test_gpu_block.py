@@ -148,3 +148,143 @@ def test_relu2_and_gate(n, dt):
     B.rwkvq_sigmoid_gate(xd, yd, B.DTYPES[dt], n, yd)
     torch.cuda.synchronize()
     assert torch.equal(yd, out[:n])
+
+
+def test_block_tokens_through_quantized_projections():
+    """A few tokens through one block as App. A.1 chains it, every projection quantized (SQ, 6- and
+    8-bit VQ mixed), batch 1, states carried on the device: fused mix + GEMV -> wkv and gate -> W_o ->
+    fused mix + GEMV -> squared ReLU -> W'_v -> gate.  Every stage is checked against the oracle fed
+    with the inputs the device held for that stage (stage bar), and the block output against the
+    oracle chain running on its own values (the roundings to fp16 between stages then differ now and
+    again, so that bar is the loose one)."""
+    torch = G.torch_()
+    rng = np.random.default_rng(9400)
+    d, ffn, T, dt = 512, 1024, 6, "f16"
+    mk = {"sq": lambda N, K: synth.gen_sq(rng, N, K), "vq6": lambda N, K: synth.gen_vq(rng, N, K, 6),
+          "vq8": lambda N, K: synth.gen_vq(rng, N, K, 8)}
+    names = ["r", "k", "v", "o", "ck", "cr", "cv"]
+    mats = dict(zip(names, [mk["sq"](d, d), mk["vq6"](d, d), mk["vq8"](d, d), mk["sq"](d, d), mk["vq6"](ffn, d),
+                            mk["sq"](d, d), mk["vq8"](d, ffn)]))
+    dms = {n: B.upload(m, native=True) for n, m in mats.items()}
+    mixes = {n: (rng.integers(0, 64, size=d // 2, dtype=np.uint8), synth.gen_codebook(rng, 64).reshape(64, 2))
+             for n in ("r", "k", "v", "ck", "cr")}
+    mixd = {n: (dev(i), dev(c)) for n, (i, c) in mixes.items()}
+    mu_hat = {n: orc.widen(c, "f16")[i].reshape(-1) for n, (i, c) in mixes.items()}
+    _, _, _, w, u = synth.gen_block_inputs(rng, 1, d, dt)
+    wd, ud = dev(w), dev(u)
+    xs = synth.gen_activations(rng, T + 1, d, dt)                # xs[0] is the token before the first
+    buf = lambda n: torch.zeros((1, n), dtype=torch.int16, device="cuda")
+    yb = {n: buf(mats[n].N) for n in names}
+    gated, sq, out = buf(d), buf(ffn), buf(d)
+    o_prev = buf(d)
+    state = fresh_state(d)
+    W = lambda t: orc.widen(t.cpu().numpy().view(np.uint16).reshape(-1), dt).astype(np.float64)
+    lin = lambda n, x: orc.linear(mats[n], x.astype(np.float32)[None, :], "f64")[0]
+    rel = lambda got, ref: float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+    # oracle chain on its own values
+    rt = lambda a: orc.widen(MO.narrow(np.asarray(a, dtype=np.float32), dt), dt).astype(np.float64)   # store as fp16
+    mixo = lambda n, x, xp: rt(MO.token_shift_mix(x[None, :], xp, mu_hat[n])[0])
+    hist_k, hist_v = [], []
+    o_prev_ref = np.zeros(d)
+    for t in range(1, T + 1):
+        print(f"block token {t}", flush=True)
+        x, xp = dev(xs[t]), dev(xs[t - 1])
+        B.rwkvq_linear_dispatch_mixed(B.MixedDispatchTable(
+            [dms[n].desc() for n in ("r", "k", "v")], [(x, xp, *mixd[n], 6) for n in ("r", "k", "v")],
+            [yb[n] for n in ("r", "k", "v")]), B.F16, B.F16)
+        s_before = state.clone()
+        B.rwkvq_wkv(yb["r"], yb["k"], yb["v"], B.F16, 1, d, wd, ud, state, gated)
+        B.rwkvq_linear_dispatch(B.DispatchTable([dms["o"].desc()], [gated], [yb["o"]]), 1, B.F16, B.F16)
+        B.rwkvq_linear_dispatch_mixed(B.MixedDispatchTable(
+            [dms[n].desc() for n in ("ck", "cr")], [(yb["o"], o_prev, *mixd[n], 6) for n in ("ck", "cr")],
+            [yb[n] for n in ("ck", "cr")]), B.F16, B.F16)
+        B.rwkvq_relu2(yb["ck"], B.F16, ffn, sq)
+        B.rwkvq_linear_dispatch(B.DispatchTable([dms["cv"].desc()], [sq], [yb["cv"]]), 1, B.F16, B.F16)
+        B.rwkvq_sigmoid_gate(yb["cr"], yb["cv"], B.F16, d, out)
+        torch.cuda.synchronize()
+        # stage bars, each stage fed with what the device held
+        xf, xpf = orc.widen(xs[t], dt), orc.widen(xs[t - 1], dt)
+        for n in ("r", "k", "v"):
+            assert rel(W(yb[n]), lin(n, mixo(n, xf, xpf))) <= 2e-3, n
+        hist_k.append(W(yb["k"])); hist_v.append(W(yb["v"]))
+        want = BO.time_mixing_gate(W(yb["r"]), BO.wkv_direct(np.array(hist_k), np.array(hist_v), w, u)[-1])
+        check_close(W(gated), want, dt, float(np.abs(np.array(hist_v)).max()))
+        assert rel(W(yb["o"]), lin("o", W(gated))) <= 2e-3
+        for n in ("ck", "cr"):
+            assert rel(W(yb[n]), lin(n, mixo(n, W(yb["o"]).astype(np.float32), W(o_prev).astype(np.float32)))) <= 2e-3, n
+        assert np.array_equal(W(sq), rt(BO.relu_squared(W(yb["ck"]))))
+        assert rel(W(yb["cv"]), lin("cv", W(sq))) <= 2e-3
+        check_close(W(out), BO.channel_mixing_gate(W(yb["cr"]), W(yb["cv"])), dt, 0.0)
+        # the oracle's own chain
+        if t == 1:
+            ref_k, ref_v = [], []
+        r_ = rt(lin("r", mixo("r", xf, xpf))); k_ = rt(lin("k", mixo("k", xf, xpf))); v_ = rt(lin("v", mixo("v", xf, xpf)))
+        ref_k.append(k_); ref_v.append(v_)
+        g_ = rt(BO.time_mixing_gate(r_, BO.wkv_direct(np.array(ref_k), np.array(ref_v), w, u)[-1]))
+        o_ = rt(lin("o", g_))
+        ck_ = rt(lin("ck", mixo("ck", o_.astype(np.float32), o_prev_ref.astype(np.float32))))
+        cr_ = rt(lin("cr", mixo("cr", o_.astype(np.float32), o_prev_ref.astype(np.float32))))
+        out_ = rt(BO.channel_mixing_gate(cr_, rt(lin("cv", rt(BO.relu_squared(ck_))))))
+        e2e = rel(W(out), out_)
+        print(f"  block output vs free-running oracle chain: {e2e:.2e}", flush=True)
+        assert e2e <= 2e-3
+        o_prev_ref = o_
+        o_prev.copy_(yb["o"])
+        del s_before
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("shapes", [[(256, 512), (512, 256), (48, 768)], [(4096, 512)], [(8192, 256), (256, 3584)],
+                                    [(16384, 256), (16384, 512), (4096, 256)]])
+@pytest.mark.parametrize("with_mix", [False, True])
+def test_post_operator_equals_separate_pass(dt, shapes, with_mix):
+    """rwkvq_linear_dispatch_post against the same projections followed by rwkvq_relu2 /
+    rwkvq_sigmoid_gate: bit for bit (same matrices per call, hence the same kernel shape and order of
+    summation; the operator is applied to the rounded output).  The shapes take 4, 8 and 16
+    wavefronts per row tile and, the last, the grouped kernel; matrix j gets operator j mod 3."""
+    torch = G.torch_()
+    if with_mix and sum((n + 15) // 16 for n, _ in shapes) >= 2048:
+        pytest.skip("covered without the mix: the mixed path always splits the columns")
+    rng = np.random.default_rng(9500 + len(shapes) + shapes[0][0])
+    mats = []
+    for j, (N, K) in enumerate(shapes):
+        kind = ("sq", "vq6", "vq8")[j % 3]
+        N_ = N if kind == "sq" else max(256, N // 256 * 256)
+        mats.append(synth.gen_sq(rng, N_, K) if kind == "sq" else synth.gen_vq(rng, N_, K, 6 if kind == "vq6" else 8))
+    dms = [B.upload(m, native=True) for m in mats]
+    descs = [m.desc() for m in dms]
+    xs = [dev(synth.gen_activations(rng, 1, m.K, dt)) for m in mats]
+    xps = [dev(synth.gen_activations(rng, 1, m.K, dt)[0]) for m in mats]
+    idx = [dev(rng.integers(0, 64, size=m.K // 2, dtype=np.uint8)) for m in mats]
+    cbs = [dev(synth.gen_codebook(rng, 64).reshape(64, 2)) for m in mats]
+    gates = [dev(synth.gen_activations(rng, 1, m.N, dt)[0]) for m in mats]
+    mixes = [(x, xp, i, c, 6) for x, xp, i, c in zip(xs, xps, idx, cbs)] if with_mix else None
+    plain = [torch.zeros((1, m.N), dtype=torch.int16, device="cuda") for m in mats]
+    if with_mix:
+        B.rwkvq_linear_dispatch_mixed(B.MixedDispatchTable(descs, mixes, plain), B.DTYPES[dt], B.DTYPES[dt])
+    else:
+        B.rwkvq_linear_dispatch(B.DispatchTable(descs, xs, plain), 1, B.DTYPES[dt], B.DTYPES[dt])
+    want = []
+    for j, (m, y, g) in enumerate(zip(mats, plain, gates)):
+        o = torch.zeros_like(y)
+        if j % 3 == 0:
+            B.rwkvq_relu2(y, B.DTYPES[dt], m.N, o)
+        elif j % 3 == 1:
+            B.rwkvq_sigmoid_gate(g, y, B.DTYPES[dt], m.N, o)
+        else:
+            o.copy_(y)
+        want.append(o)
+    posts = [((B.POST_RELU2, None), (B.POST_SIGMOID_GATE, g), (B.POST_NONE, None))[j % 3] for j, g in enumerate(gates)]
+    got = [torch.zeros((1, m.N), dtype=torch.int16, device="cuda") for m in mats]
+    print(f"post {dt} mix={with_mix} shapes={shapes}", flush=True)
+    B.rwkvq_linear_dispatch_post(B.PostDispatchTable(descs, None if with_mix else xs, mixes, posts, got), B.DTYPES[dt], B.DTYPES[dt])
+    torch.cuda.synchronize()
+    for j, (w_, g_) in enumerate(zip(want, got)):
+        assert torch.equal(w_, g_), (j, mats[j].kind, mats[j].N, mats[j].K)
+    # and against the oracle, fed with the plain projection the device stored
+    for j, (m, y, g, o) in enumerate(zip(mats, plain, gates, got)):
+        yf = host(y, dt).reshape(-1)
+        if j % 3 == 0:
+            assert np.array_equal(o.cpu().numpy().view(np.uint16).reshape(-1), MO.narrow(BO.relu_squared(yf).astype(np.float32), dt))
+        elif j % 3 == 1:
+            check_close(host(o, dt).reshape(-1), BO.channel_mixing_gate(host(g, dt), yf), dt, 0.0)
