@@ -259,7 +259,10 @@ int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input*
  *   after it.  A new sequence starts from a = b = 0, p = -1e38 (then wkv_1 = v_1).  r, k, v, out:
  *   DEVICE [M][d] of x_dtype (fp16 or bf16; out may not alias them); w (decay, positive forgets),
  *   u (bonus of the current token): DEVICE [d] floats.  Binary32 arithmetic, every exp() argument
- *   <= 0.  Sigma is the logistic function.
+ *   <= 0.  Sigma is the logistic function.  Chunks of fewer than 128 tokens run token by token, so
+ *   that splitting such a chunk into several calls gives the same bits; longer chunks are cut into
+ *   64 pieces that run side by side and are merged (the recurrence is linear in the carried sums),
+ *   which agrees with the token-by-token result to rounding, not bit for bit.
  * rwkvq_relu2: out[i] = max(x[i], 0)^2 (Eq. "channel mixing o", the vector that W'_v multiplies).
  * rwkvq_sigmoid_gate: out[i] = sigma(r[i]) * y[i] (the gates of Eq. "time mixing o" and "channel
  *   mixing o").  n values of x_dtype each; out may alias an input.

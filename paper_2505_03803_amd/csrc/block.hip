@@ -27,6 +27,7 @@ __device__ __forceinline__ uint16_t st16(float v) {
 // One thread per channel, tokens in order.  The loads of kTok tokens are issued together so that a
 // chunk (M > 1) is not one memory round trip per token.
 constexpr int kTok = 8;
+constexpr int kWkvChunkedMinTokens = 128;   // from here on the time-parallel kernel below
 template <bool BF16>
 __global__ void __launch_bounds__(64) wkv_kernel(const uint16_t* __restrict__ r, const uint16_t* __restrict__ k,
                                                  const uint16_t* __restrict__ v, int M, int d,
@@ -64,6 +65,98 @@ __global__ void __launch_bounds__(64) wkv_kernel(const uint16_t* __restrict__ r,
         }
     }
     state[c] = a; state[(size_t)d + c] = b; state[2 * (size_t)d + c] = p;
+}
+
+// Chunks of many tokens (prefill): the recurrence is linear in the carried sums, S_out = exp(-n w) S_in
+// + (the sums of the n tokens alone), so the tokens are cut into kChunks pieces that run side by side.
+// A workgroup owns 16 channels; thread (channel, piece) first runs its piece from the empty state,
+// 16 threads then chain the pieces (64 merges per channel) and leave the state in front of every
+// piece in LDS, and each thread runs its piece again from there, now with outputs.  Twice the
+// arithmetic, 64 times the parallelism.  The merges re-associate the sums: the result agrees with the
+// token-by-token kernel to rounding, not bit for bit.
+constexpr int kChunks = 64, kWgChannels = 16;
+
+// one token: output from (a, b, p) and the current (k, v), then the sums advanced
+__device__ __forceinline__ float wkv_out(float a, float b, float p, float uc, float kk, float vv) {
+    const float ww = uc + kk;
+    const float q = fmaxf(p, ww);
+    const float e1 = expf(p - q), e2 = expf(ww - q);
+    return (e1 * a + e2 * vv) / (e1 * b + e2);
+}
+__device__ __forceinline__ void wkv_advance(float& a, float& b, float& p, float wc, float kk, float vv) {
+    const float pw = p - wc;
+    const float q2 = fmaxf(pw, kk);
+    const float f1 = expf(pw - q2), f2 = expf(kk - q2);
+    a = f1 * a + f2 * vv;
+    b = f1 * b + f2;
+    p = q2;
+}
+
+template <bool BF16>
+__global__ void __launch_bounds__(kChunks * kWgChannels) wkv_chunked_kernel(
+    const uint16_t* __restrict__ r, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int M, int d,
+    const float* __restrict__ w, const float* __restrict__ u, float* __restrict__ state, uint16_t* __restrict__ out) {
+    __shared__ float loc[3][kChunks][kWgChannels];        // sums of piece i alone
+    __shared__ float in[3][kChunks][kWgChannels];         // sums in front of piece i
+    const int cc = threadIdx.x & (kWgChannels - 1), ch = threadIdx.x / kWgChannels;
+    const int c = blockIdx.x * kWgChannels + cc;
+    const bool live = c < d;
+    const int L = (M + kChunks - 1) / kChunks;
+    const int t0 = ch * L < M ? ch * L : M, t1 = t0 + L < M ? t0 + L : M;      // piece [t0, t1), may be empty
+    const float wc = live ? w[c] : 0.f, uc = live ? u[c] : 0.f;
+
+    float a = 0.f, b = 0.f, p = -1e38f;
+    if (live) {
+        for (int tb = t0; tb < t1; tb += kTok) {
+            float kk[kTok], vv[kTok];
+#pragma unroll
+            for (int j = 0; j < kTok; ++j) {
+                const int t = tb + j < t1 ? tb + j : t1 - 1;
+                kk[j] = ld16<BF16>(k, (size_t)t * d + c); vv[j] = ld16<BF16>(v, (size_t)t * d + c);
+            }
+#pragma unroll
+            for (int j = 0; j < kTok; ++j)
+                if (tb + j < t1) wkv_advance(a, b, p, wc, kk[j], vv[j]);
+        }
+    }
+    loc[0][ch][cc] = a; loc[1][ch][cc] = b; loc[2][ch][cc] = p;
+    __syncthreads();
+    if (ch == 0 && live) {
+        float A = state[c], Bs = state[(size_t)d + c], P = state[2 * (size_t)d + c];
+        for (int i = 0; i < kChunks; ++i) {
+            in[0][i][cc] = A; in[1][i][cc] = Bs; in[2][i][cc] = P;
+            const int s0 = i * L < M ? i * L : M, s1 = s0 + L < M ? s0 + L : M;
+            if (s1 > s0) {
+                const float Pd = P - (float)(s1 - s0) * wc;                     // n tokens of decay
+                const float lp = loc[2][i][cc];
+                const float q = fmaxf(Pd, lp);
+                const float e1 = expf(Pd - q), e2 = expf(lp - q);
+                A = e1 * A + e2 * loc[0][i][cc];
+                Bs = e1 * Bs + e2 * loc[1][i][cc];
+                P = q;
+            }
+        }
+        state[c] = A; state[(size_t)d + c] = Bs; state[2 * (size_t)d + c] = P;
+    }
+    __syncthreads();
+    if (!live) return;
+    a = in[0][ch][cc]; b = in[1][ch][cc]; p = in[2][ch][cc];
+    for (int tb = t0; tb < t1; tb += kTok) {
+        float rr[kTok], kk[kTok], vv[kTok];
+#pragma unroll
+        for (int j = 0; j < kTok; ++j) {
+            const int t = tb + j < t1 ? tb + j : t1 - 1;
+            const size_t at = (size_t)t * d + c;
+            rr[j] = ld16<BF16>(r, at); kk[j] = ld16<BF16>(k, at); vv[j] = ld16<BF16>(v, at);
+        }
+#pragma unroll
+        for (int j = 0; j < kTok; ++j) {
+            if (tb + j < t1) {
+                out[(size_t)(tb + j) * d + c] = st16<BF16>(gate_f32(rr[j], wkv_out(a, b, p, uc, kk[j], vv[j])));
+                wkv_advance(a, b, p, wc, kk[j], vv[j]);
+            }
+        }
+    }
 }
 
 // 8 values per thread (one 16-byte load per operand).  OP 0: max(x, 0)^2;  OP 1: sigmoid(x) * y.
@@ -113,6 +206,16 @@ __global__ void __launch_bounds__(256) pointwise_kernel(const uint16_t* __restri
 
 hipError_t launch_wkv(const void* r, const void* k, const void* v, int dt, int M, int d, const float* w, const float* u,
                       float* state, void* out, hipStream_t s) {
+    if (M >= kWkvChunkedMinTokens) {
+        const dim3 grid((d + kWgChannels - 1) / kWgChannels), block(kChunks * kWgChannels);
+        if (dt == DT_BF16)
+            hipLaunchKernelGGL(wkv_chunked_kernel<true>, grid, block, 0, s, (const uint16_t*)r, (const uint16_t*)k,
+                               (const uint16_t*)v, M, d, w, u, state, (uint16_t*)out);
+        else
+            hipLaunchKernelGGL(wkv_chunked_kernel<false>, grid, block, 0, s, (const uint16_t*)r, (const uint16_t*)k,
+                               (const uint16_t*)v, M, d, w, u, state, (uint16_t*)out);
+        return hipGetLastError();
+    }
     const dim3 grid((d + 63) / 64), block(64);
     if (dt == DT_BF16)
         hipLaunchKernelGGL(wkv_kernel<true>, grid, block, 0, s, (const uint16_t*)r, (const uint16_t*)k, (const uint16_t*)v,

@@ -100,6 +100,66 @@ def test_wkv_state_carries_across_calls(dt):
     check_close(host(one, dt), oracle_gated_wkv(r, k, v, w, u, dt), dt, float(np.abs(orc.widen(v, dt)).max()))
 
 
+@pytest.mark.parametrize("M,d", [(128, 48), (1000, 200), (2048, 64), (333, 16)])
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+def test_wkv_long_chunk_time_parallel(M, d, dt):
+    """Chunks of 128 tokens and more take the time-parallel kernel (64 pieces, merged).  Against the
+    explicit sums, then a second call that continues from the carried state.  The bar on top of half
+    an output ulp is 2e-5 of the largest |v| (measured: 5e-7; the exponent's rounding of 2^-18 per token acts
+    only over the tokens a channel still remembers, and mostly cancels).  The token-by-token kernel, run on
+    the same tokens in pieces of 100, rounds p once per token: a token of age 1 / w is off in weight by
+    about 2^-18 / w <= 5.7e-4 for the slowest decay e^-5, which moves a mean of values by <= 2.8e-4 of
+    max|v| in the worst case, whatever the length; measured <= 8.6e-5, held to the 1.5e-4 of the short cases.
+    The absolute exponent of the carried sums may drift by 2^-18 per token; only differences matter."""
+    torch = G.torch_()
+    rng = np.random.default_rng(9600 + M + d)
+    M2 = 150
+    r, k, v, w, u = synth.gen_block_inputs(rng, M + M2, d, dt)
+    rd, kd, vd, wd, ud = dev(r), dev(k), dev(v), dev(w), dev(u)
+    print(f"wkv time-parallel M={M}+{M2} d={d} {dt}", flush=True)
+    out = torch.zeros((M + M2, d), dtype=torch.int16, device="cuda")
+    state = fresh_state(d)
+    B.rwkvq_wkv(rd, kd, vd, B.DTYPES[dt], M, d, wd, ud, state, out)
+    B.rwkvq_wkv(rd[M:], kd[M:], vd[M:], B.DTYPES[dt], M2, d, wd, ud, state, out[M:])
+    torch.cuda.synchronize()
+    want = oracle_gated_wkv(r, k, v, w, u, dt)
+    got = host(out, dt)
+    vmax = float(np.abs(orc.widen(v, dt)).max())
+    tol = HALF_ULP[dt] * 1.01 * np.abs(want) + FLOOR[dt] + 2e-5 * vmax
+    bad = np.abs(got - want) > tol
+    excess = float((np.abs(got - want) - HALF_ULP[dt] * np.abs(want)).max() / vmax)
+    print(f"  largest error beyond half an ulp: {excess:.2e} of max|v|", flush=True)
+    assert not bad.any(), (int(bad.sum()), np.argwhere(bad)[:4])
+    # the token-by-token kernel on the same tokens (pieces of 100 < 128)
+    seq = torch.zeros((M + M2, d), dtype=torch.int16, device="cuda")
+    st2 = fresh_state(d)
+    for t0 in range(0, M + M2, 100):
+        n = min(100, M + M2 - t0)
+        if (t0 * d * 2) % 16 == 0:
+            B.rwkvq_wkv(rd[t0:], kd[t0:], vd[t0:], B.DTYPES[dt], n, d, wd, ud, st2, seq[t0:])
+        else:
+            pytest.skip("row offset not 16-byte aligned")
+    torch.cuda.synchronize()
+    excess = float((np.abs(host(seq, dt) - want) - HALF_ULP[dt] * np.abs(want)).max() / vmax)
+    print(f"  token-by-token kernel on the same tokens: {excess:.2e} of max|v|", flush=True)
+    check_close(host(seq, dt), want, dt, vmax)               # its own bar (one rounding of p per token)
+    # the carried sums a e^p, b e^p of both kernels against their definition (binary64): the weighted
+    # mean a / b and the log of the weight sum log b + p
+    T = M + M2
+    kf, vf = orc.widen(k, dt).astype(np.float64), orc.widen(v, dt).astype(np.float64)
+    e = -(T - 1 - np.arange(T))[:, None] * w.astype(np.float64)[None, :] + kf
+    m = e.max(axis=0)
+    den = np.exp(e - m).sum(axis=0)
+    mean_true, logw_true = (np.exp(e - m) * vf).sum(axis=0) / den, np.log(den) + m
+    for name, st, bar in (("time-parallel", state, 2e-5), ("token by token", st2, 1.5e-4)):
+        a_, b_, p_ = st.cpu().numpy().astype(np.float64)
+        err_mean = float(np.abs(a_ / b_ - mean_true).max() / vmax)
+        err_logw = float(np.abs(np.log(b_) + p_ - logw_true).max())
+        print(f"  carried state, {name}: mean off by {err_mean:.2e} of max|v|, log weight by {err_logw:.2e}", flush=True)
+        # every step rounds the exponent p (|p| < 128) by at most 2^-18, and w is constant: the roundings can add up
+        assert err_mean <= bar and err_logw <= T * 2.0 ** -18, name
+
+
 def test_wkv_extreme_keys_stay_finite():
     """Keys at the ends of the fp16 range (an exponent of +-65504): the running maximum keeps every
     exp() argument non-positive, so nothing overflows and a dominant key returns its own value."""
