@@ -348,3 +348,109 @@ def test_post_operator_equals_separate_pass(dt, shapes, with_mix):
             assert np.array_equal(o.cpu().numpy().view(np.uint16).reshape(-1), MO.narrow(BO.relu_squared(yf).astype(np.float32), dt))
         elif j % 3 == 1:
             check_close(host(o, dt).reshape(-1), BO.channel_mixing_gate(host(g, dt), yf), dt, 0.0)
+
+
+def test_block_chunk_through_quantized_projections():
+    """A chunk of 192 tokens through one block (the prefill path: separate mix pass, matrix-core GEMMs,
+    time-parallel wkv, element-wise passes), then 3 more tokens one by one (batch-1 path, fused mix,
+    operators applied by the GEMVs) continuing from the carried states.  Every stage against the
+    oracle fed with what the device held for that stage."""
+    torch = G.torch_()
+    rng = np.random.default_rng(9700)
+    d, ffn, T, T1, dt = 512, 1024, 192, 3, "bf16"
+    names = ["r", "k", "v", "o", "ck", "cr", "cv"]
+    mats = dict(zip(names, [synth.gen_sq(rng, d, d), synth.gen_vq(rng, d, d, 6), synth.gen_vq(rng, d, d, 8),
+                            synth.gen_sq(rng, d, d), synth.gen_vq(rng, ffn, d, 6), synth.gen_sq(rng, d, d),
+                            synth.gen_vq(rng, d, ffn, 8)]))
+    dms = {n: B.upload(m, native=True) for n, m in mats.items()}
+    mixes = {n: (rng.integers(0, 64, size=d // 2, dtype=np.uint8), synth.gen_codebook(rng, 64).reshape(64, 2))
+             for n in ("r", "k", "v", "ck", "cr")}
+    mixd = {n: (dev(i), dev(c)) for n, (i, c) in mixes.items()}
+    mu_hat = {n: orc.widen(c, "f16")[i].reshape(-1) for n, (i, c) in mixes.items()}
+    _, _, _, w, u = synth.gen_block_inputs(rng, 1, d, dt)
+    wd, ud = dev(w), dev(u)
+    xs = synth.gen_activations(rng, T + T1 + 1, d, dt)            # row 0: the token before the chunk
+    xd = dev(xs)
+    DT = B.DTYPES[dt]
+    W = lambda t: orc.widen(t.cpu().numpy().view(np.uint16), dt).astype(np.float64)
+    lin = lambda n, x: orc.linear(mats[n], np.asarray(x, dtype=np.float32), "f64", weight_round=dt)
+    rel = lambda got, ref: float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+    narrow = lambda a: orc.widen(MO.narrow(np.asarray(a, dtype=np.float32), dt), dt)
+    buf = lambda m, n: torch.zeros((m, n), dtype=torch.int16, device="cuda")
+    # ---- the chunk ----
+    mixed = {n: buf(T, d) for n in ("r", "k", "v")}
+    B.rwkvq_token_shift_mix(xd[1:T + 1], xd[0], DT, T, d, B.MixTable([mixd[n][0] for n in ("r", "k", "v")],
+                            [mixd[n][1] for n in ("r", "k", "v")], [mixed[n] for n in ("r", "k", "v")]), 6)
+    y = {n: buf(T, mats[n].N) for n in names}
+    B.rwkvq_linear_dispatch(B.DispatchTable([dms[n].desc() for n in ("r", "k", "v")], [mixed[n] for n in ("r", "k", "v")],
+                                            [y[n] for n in ("r", "k", "v")]), T, DT, DT)
+    state = fresh_state(d)
+    gated = buf(T, d)
+    B.rwkvq_wkv(y["r"], y["k"], y["v"], DT, T, d, wd, ud, state, gated)
+    B.rwkvq_linear_dispatch(B.DispatchTable([dms["o"].desc()], [gated], [y["o"]]), T, DT, DT)
+    o_before = buf(1, d)                                          # o of the token before the chunk: zeros
+    mixed2 = {n: buf(T, d) for n in ("ck", "cr")}
+    B.rwkvq_token_shift_mix(y["o"], o_before, DT, T, d, B.MixTable([mixd[n][0] for n in ("ck", "cr")],
+                            [mixd[n][1] for n in ("ck", "cr")], [mixed2[n] for n in ("ck", "cr")]), 6)
+    B.rwkvq_linear_dispatch(B.DispatchTable([dms[n].desc() for n in ("ck", "cr")], [mixed2[n] for n in ("ck", "cr")],
+                                            [y[n] for n in ("ck", "cr")]), T, DT, DT)
+    sq = buf(T, ffn)
+    B.rwkvq_relu2(y["ck"], DT, T * ffn, sq)
+    B.rwkvq_linear_dispatch(B.DispatchTable([dms["cv"].desc()], [sq], [y["cv"]]), T, DT, DT)
+    out = buf(T, d)
+    B.rwkvq_sigmoid_gate(y["cr"], y["cv"], DT, T * d, out)
+    torch.cuda.synchronize()
+    print("block chunk: stages", flush=True)
+    xf = orc.widen(xs, dt)
+    for n in ("r", "k", "v"):
+        want_mix = MO.narrow(MO.token_shift_mix(xf[1:T + 1], xf[0], mu_hat[n]), dt)
+        assert np.array_equal(mixed[n].cpu().numpy().view(np.uint16), want_mix), n
+        assert rel(W(y[n]), lin(n, orc.widen(want_mix, dt))) <= 4e-3, n
+    want_g = BO.time_mixing_gate(W(y["r"]), BO.wkv_direct(W(y["k"]), W(y["v"]), w, u))
+    vmax = float(np.abs(W(y["v"])).max())
+    tol = HALF_ULP[dt] * 1.01 * np.abs(want_g) + FLOOR[dt] + 2e-5 * vmax
+    assert not (np.abs(W(gated) - want_g) > tol).any()
+    assert rel(W(y["o"]), lin("o", W(gated))) <= 4e-3
+    of = W(y["o"]).astype(np.float32)
+    for n in ("ck", "cr"):
+        want_mix = MO.narrow(MO.token_shift_mix(of, np.zeros(d, np.float32), mu_hat[n]), dt)
+        assert np.array_equal(mixed2[n].cpu().numpy().view(np.uint16), want_mix), n
+        assert rel(W(y[n]), lin(n, orc.widen(want_mix, dt))) <= 4e-3, n
+    assert np.array_equal(sq.cpu().numpy().view(np.uint16), MO.narrow(BO.relu_squared(W(y["ck"])).astype(np.float32), dt))
+    assert rel(W(y["cv"]), lin("cv", W(sq))) <= 4e-3
+    check_close(W(out), BO.channel_mixing_gate(W(y["cr"]), W(y["cv"])), dt, 0.0)
+    # ---- three more tokens, one by one, from the carried states ----
+    hist_k, hist_v = list(W(y["k"])), list(W(y["v"]))
+    o_prev = y["o"][T - 1:T].clone()
+    for t in range(T + 1, T + T1 + 1):
+        print(f"block chunk: token {t}", flush=True)
+        x, xp = xd[t], xd[t - 1]
+        y1 = {n: buf(1, mats[n].N) for n in names}
+        g1, s1, out1 = buf(1, d), buf(1, ffn), buf(1, d)
+        B.rwkvq_linear_dispatch_mixed(B.MixedDispatchTable([dms[n].desc() for n in ("r", "k", "v")],
+                                      [(x, xp, *mixd[n], 6) for n in ("r", "k", "v")], [y1[n] for n in ("r", "k", "v")]), DT, DT)
+        B.rwkvq_wkv(y1["r"], y1["k"], y1["v"], DT, 1, d, wd, ud, state, g1)
+        B.rwkvq_linear_dispatch(B.DispatchTable([dms["o"].desc()], [g1], [y1["o"]]), 1, DT, DT)
+        B.rwkvq_linear_dispatch_post(B.PostDispatchTable([dms[n].desc() for n in ("ck", "cr")], None,
+                                     [(y1["o"], o_prev, *mixd[n], 6) for n in ("ck", "cr")],
+                                     [(B.POST_RELU2, None), (B.POST_NONE, None)], [s1, y1["cr"]]), DT, DT)
+        B.rwkvq_linear_dispatch_post(B.PostDispatchTable([dms["cv"].desc()], [s1], None, [(B.POST_SIGMOID_GATE, y1["cr"])],
+                                                         [out1]), DT, DT)
+        torch.cuda.synchronize()
+        for n in ("r", "k", "v"):
+            xm = narrow(MO.token_shift_mix(xf[t][None, :], xf[t - 1], mu_hat[n]))
+            assert rel(W(y1[n]), lin(n, xm)) <= 4e-3, n
+        hist_k.append(W(y1["k"])[0]); hist_v.append(W(y1["v"])[0])
+        want = BO.time_mixing_gate(W(y1["r"])[0], BO.wkv_direct(np.array(hist_k), np.array(hist_v), w, u)[-1])
+        check_close(W(g1)[0], want, dt, float(np.abs(np.array(hist_v)).max()))
+        assert rel(W(y1["o"]), lin("o", W(g1))) <= 4e-3
+        xm = {n: narrow(MO.token_shift_mix(W(y1["o"]).astype(np.float32), W(o_prev)[0].astype(np.float32), mu_hat[n])) for n in ("ck", "cr")}
+        assert rel(W(y1["cr"]), lin("cr", xm["cr"])) <= 4e-3
+        ck = narrow(lin("ck", xm["ck"]))                          # k' as the GEMV would have stored it
+        # the GEMV stored max(k', 0)^2 directly (k' itself is not kept): where the oracle's k' rounds to the
+        # neighbouring bf16 value (2^-8 relative) the square differs by twice that
+        assert rel(W(s1), BO.relu_squared(ck)) <= 2e-2
+        y_cv = lin("cv", W(s1))
+        want_out = BO.channel_mixing_gate(W(y1["cr"]), narrow(y_cv))
+        assert rel(W(out1), want_out) <= 1e-2
+        o_prev = y1["o"]
