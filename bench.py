@@ -225,6 +225,61 @@ def sequential_step(dec, n_layers):
                     "block = the fused step plus the element-wise operators between the stages"}
 
 
+def prefill_block_step(pf, n_layers, M):
+    """A chunk of M tokens through the stack in data-flow order with the block's element-wise operators
+    (App. A.1): per layer  mix pass (4 projections) -> {r, k, v, g} -> wkv with its gate -> W_o -> mix
+    pass (2) -> {k', r'} -> squared ReLU -> W'_v -> gate.  Same matrices as the grouped prefill figure;
+    shows what the dependencies and the element-wise passes cost on top of it."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    from paper_2505_03803_amd import synth
+    d = 4096
+    ffn = pf["ys"][5].shape[1]
+    rng = np.random.default_rng(4100)
+    t16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda()
+    buf = lambda n: torch.zeros((M, n), dtype=torch.int16, device="cuda")
+    h = t16(synth.gen_activations(rng, M, d, "bf16"))
+    hprev = t16(synth.gen_activations(rng, 1, d, "bf16")[0])
+    mix4, mix2, gated, sq = [buf(d) for _ in range(4)], [buf(d) for _ in range(2)], buf(d), buf(ffn)
+    outs = [buf(d), buf(d)]                                   # block outputs, alternating
+    stages = []
+    src = h
+    for layer in range(n_layers):
+        D = pf["descs"][8 * layer: 8 * layer + 8]
+        Y = pf["ys"][8 * layer: 8 * layer + 8]
+        mk = lambda P, o: B.MixTable([torch.from_numpy(rng.integers(0, 64, size=d // 2, dtype=np.uint8)).cuda() for _ in range(P)],
+                                     [t16(synth.gen_codebook(rng, 64)) for _ in range(P)], o)
+        _, _, _, w, u = synth.gen_block_inputs(rng, 1, d, "bf16")
+        st = np.zeros((3, d), dtype=np.float32); st[2] = -1e38
+        out = outs[layer & 1]
+        stages += [("mix", (src, mk(4, mix4))), ("lin", B.DispatchTable(D[0:4], mix4, Y[0:4])),
+                   ("wkv", (Y[0], Y[1], Y[2], torch.from_numpy(w).cuda(), torch.from_numpy(u).cuda(), torch.from_numpy(st).cuda(), gated)),
+                   ("lin", B.DispatchTable([D[4]], [gated], [Y[4]])),
+                   ("mix", (Y[4], mk(2, mix2))), ("lin", B.DispatchTable([D[5], D[7]], mix2, [Y[5], Y[7]])),
+                   ("relu2", (Y[5], sq)), ("lin", B.DispatchTable([D[6]], [sq], [Y[6]])), ("gate", (Y[7], Y[6], out))]
+        src = out
+
+    def step():
+        for kind, a in stages:
+            if kind == "mix":
+                B.rwkvq_token_shift_mix(a[0], hprev, B.BF16, M, d, a[1], 6)
+            elif kind == "lin":
+                B.rwkvq_linear_dispatch(a, M, B.BF16, B.BF16)
+            elif kind == "wkv":
+                B.rwkvq_wkv(a[0], a[1], a[2], B.BF16, M, d, a[3], a[4], a[5], a[6])
+            elif kind == "relu2":
+                B.rwkvq_relu2(a[0], B.BF16, M * ffn, a[1])
+            else:
+                B.rwkvq_sigmoid_gate(a[0], a[1], B.BF16, M * d, a[2])
+
+    total, _, _ = time_steps(step, 10, 3)
+    ms = total / 10
+    return {"ms_per_step": ms, "tokens_per_s": M * 1e3 / ms, "value": pf["flops"] / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+            "calls_per_step": len(stages),
+            "note": "the same matrices in data-flow order, 9 calls per layer: token-shift mix passes, matrix-core GEMMs, "
+                    "time-parallel wkv with its gate, squared ReLU, output gate; value counts the GEMM FLOP only"}
+
+
 def time_steps(run, steps: int, warmup: int):
     """W untimed steps, then exactly K steps bracketed by synchronize + HIP events on the current
     stream.  Returns (total ms over K steps, per-step ms list)."""
@@ -364,6 +419,8 @@ def main():
                                    # FETCH_SIZE x 2 + WRITE_SIZE per launch, mean of the four launches of a step
                                    # (profiles/prefill_and_mix_hbm_traffic.txt)
                                    "traffic": 8.87e9 if args.layers == 32 else None}
+        if not args.skip_sequential:
+            out["prefill"]["block"] = prefill_block_step(pf, args.layers, 2048)
         del pf, runp
         torch.cuda.empty_cache()
 
