@@ -7,7 +7,9 @@
 // binary32; VQ: the fp16 codebook entry) rounded once, to nearest even, to the type of x.
 //
 // Tiling: workgroup = 256 threads = 2 x 2 wavefronts, block tile 256 (m) x 256 (n) x 64 (k),
-// wavefront tile 128 x 128 = 8 x 8 MFMA tiles (256 accumulator registers).  Both operand tiles
+// wavefront tile 128 x 128 = 8 x 8 MFMA tiles (256 accumulator registers).  A second instance
+// with 128 rows of x per workgroup (wavefront tile 64 x 128) serves launches that would otherwise
+// leave compute units without a tile; the launcher picks per launch (pick_bm).  Both operand tiles
 // live in LDS as 256 rows of 128 bytes (64 k), with the eight 16-byte chunks of a row stored at
 // chunk ^ (row & 7), so that the 16-row fragment reads of the 16 x 16 x 32 MFMAs and the tile
 // writes are free of bank conflicts without padding (the conflict counter reads zero).
@@ -25,6 +27,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <vector>
 
 namespace rwkvq {
@@ -56,6 +59,7 @@ struct PfArgs {
 // s_waitcnt immediates (gfx9 encoding): only the named counter is waited for.
 #define RWKVQ_WAIT_VM0_LGKM0() __builtin_amdgcn_s_waitcnt(0x0070)   /* vmcnt(0) lgkmcnt(0) */
 #define RWKVQ_WAIT_VM8_LGKM0() __builtin_amdgcn_s_waitcnt(0x0078)   /* vmcnt(8) lgkmcnt(0) */
+#define RWKVQ_WAIT_VM4_LGKM0() __builtin_amdgcn_s_waitcnt(0x0074)   /* vmcnt(4) lgkmcnt(0) */
 // Publish LDS writes (ds_write and load-unit copies) to the workgroup: the caller has waited for
 // its own writes; the barrier orders them against the other wavefronts' reads.
 #define RWKVQ_BARRIER() asm volatile("s_barrier" ::: "memory")
@@ -339,9 +343,10 @@ __device__ __forceinline__ void x_tile_dma_one(const char* xk, const uint32_t (&
                                      (__attribute__((address_space(3))) void*)(xt + (256 * I + 64 * wave) * 16),
                                      16, 0, 0);
 }
+template <int MF>
 __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff)[8], char* xt, int wave) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < MF; ++i)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xk + xoff[i]),
                                          (__attribute__((address_space(3))) void*)(xt + (256 * i + 64 * wave) * 16),
                                          16, 0, 0);
@@ -356,37 +361,43 @@ __device__ __forceinline__ void x_tile_dma(const char* xk, const uint32_t (&xoff
 constexpr int kAhead = 3;
 template <int S> struct SliceTag { static constexpr int value = S; };
 
-template <bool BF16, int F, int NI, class Slice>
-__device__ __forceinline__ void mma_one(const uint4_t (&b)[8], const uint4_t af, float4_t (&acc)[8][8], Slice& slice) {
+template <bool BF16, int MF, int F, int NI, class Slice>
+__device__ __forceinline__ void mma_one(const uint4_t (&b)[8], const uint4_t af, float4_t (&acc)[MF][8], Slice& slice) {
     // One MFMA of x fragment F, then one micro-slice of vector-ALU work, fenced so that the
     // instruction scheduler leaves it there: a wavefront issues in order, and only the two or
     // three instructions placed right behind an MFMA run while the matrix core is busy with it
     // (left alone, the scheduler gathers the unpack work into long runs before its stores, and
     // the matrix core idles through them).
-    Elem<BF16>::mfma(b[NI], af, acc[F & 7][NI]);
+    Elem<BF16>::mfma(b[NI], af, acc[F % MF][NI]);
     __builtin_amdgcn_sched_barrier(0);
-    slice(SliceTag<8 * F + NI>{});
+    if constexpr (MF == 8) {
+        slice(SliceTag<8 * F + NI>{});
+    } else {                                       // half as many MFMAs per k-step: two micro-slices behind each
+        slice(SliceTag<2 * (8 * F + NI)>{});
+        slice(SliceTag<2 * (8 * F + NI) + 1>{});
+    }
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (NI < 7) mma_one<BF16, F, NI + 1>(b, af, acc, slice);
+    if constexpr (NI < 7) mma_one<BF16, MF, F, NI + 1>(b, af, acc, slice);
 }
-template <bool BF16, int F, class Slice>
-__device__ __forceinline__ void mma_row(const uint4_t (&b)[8], const uint4_t af, float4_t (&acc)[8][8], Slice& slice) {
-    mma_one<BF16, F, 0>(b, af, acc, slice);
+template <bool BF16, int MF, int F, class Slice>
+__device__ __forceinline__ void mma_row(const uint4_t (&b)[8], const uint4_t af, float4_t (&acc)[MF][8], Slice& slice) {
+    mma_one<BF16, MF, F, 0>(b, af, acc, slice);
 }
 
-template <bool BF16, int F, class Slice>
+template <bool BF16, int MF, int F, class Slice>
 __device__ __forceinline__ void mma_rows(const char* const (&xa)[2], const char* wb1, uint4_t (&b)[8], uint4_t (&b1)[8],
-                                         uint4_t (&a)[kAhead + 1], float4_t (&acc)[8][8], Slice& slice) {
-    if constexpr (F < 16) {
-        if constexpr (F + kAhead < 16)
-            a[(F + kAhead) % (kAhead + 1)] = *(const uint4_t*)(xa[(F + kAhead) >> 3] + 16 * ((F + kAhead) & 7) * kRowBytes);
-        if constexpr (F >= 4 && F < 8) {
-            b1[2 * (F - 4)] = *(const uint4_t*)(wb1 + 16 * (2 * (F - 4)) * kRowBytes);
-            b1[2 * (F - 4) + 1] = *(const uint4_t*)(wb1 + 16 * (2 * (F - 4) + 1) * kRowBytes);
+                                         uint4_t (&a)[kAhead + 1], float4_t (&acc)[MF][8], Slice& slice) {
+    if constexpr (F < 2 * MF) {
+        if constexpr (F + kAhead < 2 * MF)
+            a[(F + kAhead) % (kAhead + 1)] = *(const uint4_t*)(xa[(F + kAhead) / MF] + 16 * ((F + kAhead) % MF) * kRowBytes);
+        if constexpr (F >= MF - 4 && F < MF) {                  // the last four rows of the first half
+            constexpr int J = F - (MF - 4);
+            b1[2 * J] = *(const uint4_t*)(wb1 + 16 * (2 * J) * kRowBytes);
+            b1[2 * J + 1] = *(const uint4_t*)(wb1 + 16 * (2 * J + 1) * kRowBytes);
         }
-        if constexpr (F < 8) mma_row<BF16, F>(b, a[F % (kAhead + 1)], acc, slice);
-        else mma_row<BF16, F>(b1, a[F % (kAhead + 1)], acc, slice);
-        mma_rows<BF16, F + 1>(xa, wb1, b, b1, a, acc, slice);
+        if constexpr (F < MF) mma_row<BF16, MF, F>(b, a[F % (kAhead + 1)], acc, slice);
+        else mma_row<BF16, MF, F>(b1, a[F % (kAhead + 1)], acc, slice);
+        mma_rows<BF16, MF, F + 1>(xa, wb1, b, b1, a, acc, slice);
     }
 }
 
@@ -395,11 +406,11 @@ __device__ __forceinline__ void mma_rows(const char* const (&xa)[2], const char*
 // read kAhead rows ahead of their use and the W fragments of the second half during rows 4..7,
 // so that an LDS round trip is hidden behind several rows of MFMAs.  `slice(SliceTag<S>)`, S =
 // 0..127, is called after MFMA S: the unpacking of the next k-step goes there.
-template <bool BF16, class Slice>
+template <bool BF16, int MF, class Slice>
 __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm, int wn, int lane,
-                                         float4_t (&acc)[8][8], Slice slice) {
+                                         float4_t (&acc)[MF][8], Slice slice) {
     const int r = lane & 15, kg = lane >> 4;
-    const char* const xa[2] = {xt + tile_off(128 * wm + r, kg), xt + tile_off(128 * wm + r, 4 + kg)};
+    const char* const xa[2] = {xt + tile_off(16 * MF * wm + r, kg), xt + tile_off(16 * MF * wm + r, 4 + kg)};
     const char* wb0 = wt + tile_off(128 * wn + r, kg);
     const char* wb1 = wt + tile_off(128 * wn + r, 4 + kg);
     uint4_t b[8], b1[8], a[kAhead + 1];
@@ -407,7 +418,7 @@ __device__ __forceinline__ void mma_step(const char* xt, const char* wt, int wm,
     for (int ni = 0; ni < 8; ++ni) b[ni] = *(const uint4_t*)(wb0 + 16 * ni * kRowBytes);
 #pragma unroll
     for (int f = 0; f < kAhead; ++f) a[f] = *(const uint4_t*)(xa[0] + 16 * f * kRowBytes);
-    mma_rows<BF16, 0>(xa, wb1, b, b1, a, acc, slice);
+    mma_rows<BF16, MF, 0>(xa, wb1, b, b1, a, acc, slice);
 }
 
 // Convert and stage the 8-bit-index codebook of a tile (256 entries) into LDS.
@@ -422,8 +433,11 @@ __device__ __forceinline__ void cb8_store(const WRegs<FMT_VQ8>& r, uint32_t* cb8
 
 // All matrices of one launch have the format FMT.  The k loop has no conditionals: past the last
 // column tile the prefetches simply fetch the last tile again (never used).
-template <bool BF16, int FMT>
+// MF = 16-row m-subtiles per wavefront: 8 (block tile 256 x 256) or 4 (128 x 256, for launches that
+// would leave compute units without a tile: the same W work per workgroup on half the MFMAs).
+template <bool BF16, int FMT, int MF>
 __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
+    constexpr int BMk = 32 * MF;                           // rows of x per workgroup
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     constexpr int XB = x_buffers(FMT), LA = XB - 1;       // LA = k-steps between a copy and its use
     char* const wt0 = lds;
@@ -437,7 +451,7 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     const int mi_ = __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[threadIdx.x & 63]));
     const PfMat mt = a.m[mi_];
     const int local = wg - (mi_ ? a.wg_end[mi_ - 1] : 0);
-    const int m0 = (local % a.m_tiles) * BM, n0 = (local / a.m_tiles) * BN;
+    const int m0 = (local % a.m_tiles) * BMk, n0 = (local / a.m_tiles) * BN;
     const int M = a.M, K = mt.K, KT = K >> 8, R0 = n0 >> 4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave >> 1, wn = wave & 1;
@@ -445,7 +459,7 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     // per-lane activation offsets (rows past M repeat row M - 1)
     uint32_t xoff[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < MF; ++i) {
         const int p = 256 * i + 64 * wave + lane;
         const int row = p >> 3, c = (p & 7) ^ (row & 7);
         const int rr = m0 + row < M ? row : M - 1 - m0;
@@ -462,9 +476,9 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     else if constexpr (FMT == FMT_VQ6) src.aux = (const uint16_t*)((const uint32_t*)mt.aux + (size_t)(R0 >> 4) * KT * 64);
     else src.aux = (const uint16_t*)((const uint4_t*)mt.aux + (size_t)(R0 >> 4) * KT * 64);
 
-    float4_t acc[8][8];
+    float4_t acc[MF][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < MF; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = float4_t{0, 0, 0, 0};
 
@@ -476,14 +490,17 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     const int hmax = 4 * KT - 1;                           // last k-step
     auto xk = [&](int h) { return xrow0 + (size_t)(h < hmax ? h : hmax) * kRowBytes; };
     auto rotate = [&] { if (XB == 3) { const int t = x0; x0 = x1; x1 = x2; x2 = t; } else { const int t = x0; x0 = x1; x1 = t; } };
-    auto wait_step = [&] { if (LA == 2) RWKVQ_WAIT_VM8_LGKM0(); else RWKVQ_WAIT_VM0_LGKM0(); };
+    auto wait_step = [&] {                                 // all but the newest copy (MF instructions per thread)
+        if (LA == 2) { if (MF == 8) RWKVQ_WAIT_VM8_LGKM0(); else RWKVQ_WAIT_VM4_LGKM0(); }
+        else RWKVQ_WAIT_VM0_LGKM0();
+    };
 
     // prologue: packed words of tile 0, k-step 0 (and 1) of the activations, k-step 0 of W
     WRegs<FMT> wr;
     UnpackState<FMT> us;
     w_load<FMT>(wr, src, 0, lane);
-    x_tile_dma(xk(0), xoff, xbase + x0, wave);
-    if (LA == 2) x_tile_dma(xk(1), xoff, xbase + x1, wave);
+    x_tile_dma<MF>(xk(0), xoff, xbase + x0, wave);
+    if (LA == 2) x_tile_dma<MF>(xk(1), xoff, xbase + x1, wave);
     if constexpr (FMT == FMT_VQ8) {
         cb8_store<BF16>(wr, CB8(0), wave, lane);
         RWKVQ_WAIT_VM0_LGKM0();
@@ -503,9 +520,9 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
             const char* xsrc = xk(g + LA);
             char* xdst = xbase + (LA == 2 ? x2 : x1);
             unpack_begin<BF16, FMT>(us, wr, wt1, wave, lane);
-            mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc, [&](auto tag) {
+            mma_step<BF16, MF>(xbase + x0, wt0, wm, wn, lane, acc, [&](auto tag) {
                 constexpr int S = decltype(tag)::value;
-                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                if constexpr (S % 8 == 4 && S / 8 < MF) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
                 unpack_micro<BF16, FMT, 1, S>(us, wr, CB8(T));
             });
         }
@@ -517,9 +534,9 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
             const char* xsrc = xk(g + 1 + LA);
             char* xdst = xbase + (LA == 2 ? x2 : x1);
             unpack_begin<BF16, FMT>(us, wr, wt0, wave, lane);
-            mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc, [&](auto tag) {
+            mma_step<BF16, MF>(xbase + x0, wt1, wm, wn, lane, acc, [&](auto tag) {
                 constexpr int S = decltype(tag)::value;
-                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                if constexpr (S % 8 == 4 && S / 8 < MF) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
                 unpack_micro<BF16, FMT, 2, S>(us, wr, CB8(T));
             });
         }
@@ -531,9 +548,9 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
             const char* xsrc = xk(g + 2 + LA);
             char* xdst = xbase + (LA == 2 ? x2 : x1);
             unpack_begin<BF16, FMT>(us, wr, wt1, wave, lane);
-            mma_step<BF16>(xbase + x0, wt0, wm, wn, lane, acc, [&](auto tag) {
+            mma_step<BF16, MF>(xbase + x0, wt0, wm, wn, lane, acc, [&](auto tag) {
                 constexpr int S = decltype(tag)::value;
-                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                if constexpr (S % 8 == 4 && S / 8 < MF) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
                 unpack_micro<BF16, FMT, 3, S>(us, wr, CB8(T));
             });
         }
@@ -548,9 +565,9 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
         {
             const char* xsrc = xk(g + 3 + LA);
             char* xdst = xbase + (LA == 2 ? x2 : x1);
-            mma_step<BF16>(xbase + x0, wt1, wm, wn, lane, acc, [&](auto tag) {
+            mma_step<BF16, MF>(xbase + x0, wt1, wm, wn, lane, acc, [&](auto tag) {
                 constexpr int S = decltype(tag)::value;
-                if constexpr (S % 8 == 4 && S < 64) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
+                if constexpr (S % 8 == 4 && S / 8 < MF) x_tile_dma_one<S / 8>(xsrc, xoff, xdst, wave);
             });
         }
         if constexpr (FMT == FMT_VQ8) {
@@ -575,8 +592,8 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
     // one 8-byte (or 16-byte for fp32) store per tile.
     const int N = mt.N;
 #pragma unroll
-    for (int mi = 0; mi < 8; ++mi) {
-        const int m = m0 + 128 * wm + 16 * mi + (lane & 15);
+    for (int mi = 0; mi < MF; ++mi) {
+        const int m = m0 + 16 * MF * wm + 16 * mi + (lane & 15);
         if (m < M) {
 #pragma unroll
             for (int ni = 0; ni < 8; ++ni) {
@@ -596,21 +613,41 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 #undef CB8
 }
 
-template <bool BF16, int FMT>
-static hipError_t launch_fmt(const PfArgs& a, int wgs, hipStream_t s) {
+template <bool BF16, int FMT, int MF>
+static hipError_t launch_fmt_mf(const PfArgs& a, int wgs, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<BF16, FMT>,
+        hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<BF16, FMT, MF>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, pf_lds_bytes(FMT));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_kernel<BF16, FMT>), dim3(wgs), dim3(256), pf_lds_bytes(FMT), s, a);
+    hipLaunchKernelGGL((prefill_kernel<BF16, FMT, MF>), dim3(wgs), dim3(256), pf_lds_bytes(FMT), s, a);
     return hipGetLastError();
+}
+template <bool BF16, int FMT>
+static hipError_t launch_fmt(const PfArgs& a, int wgs, int mf, hipStream_t s) {
+    return mf == 8 ? launch_fmt_mf<BF16, FMT, 8>(a, wgs, s) : launch_fmt_mf<BF16, FMT, 4>(a, wgs, s);
+}
+
+// Rows of x per workgroup for a launch whose matrices have `n_tiles` tiles of 256 rows of W in all.
+// One workgroup runs per compute unit, so a launch takes about ceil(workgroups / 256) rounds; a round
+// of 128-row workgroups does half the MFMAs of a 256-row round at 0.71 of its rate (measured on the
+// 7B stack: the W tile is unpacked once per workgroup either way), i.e. costs 0.705 of it.  The
+// cheaper of the two wins: 128 rows for launches that would leave compute units without a tile
+// (one 4096 x 4096 matrix at M = 2048 is 128 tiles) and for short M.
+// RWKVQ_PREFILL_BM=128|256 in the environment overrides the choice (tests run both kernels).
+static int pick_bm(int M, long long n_tiles) {
+    if (const char* e = std::getenv("RWKVQ_PREFILL_BM")) {
+        if (e[0] == '1') return 128;
+        if (e[0] == '2') return 256;
+    }
+    const long long wg256 = n_tiles * ((M + 255) / 256), wg128 = n_tiles * ((M + 127) / 128);
+    const double t256 = (double)((wg256 + 255) / 256), t128 = 0.705 * (double)((wg128 + 255) / 256);
+    return t128 < t256 ? 128 : 256;
 }
 
 hipError_t launch_prefill(const MatDev* mats_in, int n_mats, int M, int x_dtype, int y_dtype, hipStream_t s) {
-    const int m_tiles = (M + BM - 1) / BM;
     // Workgroups of a matrix with a long K run long: put those matrices first so that the end of
     // a launch is filled by short workgroups.
     std::vector<MatDev> sorted(mats_in, mats_in + n_mats);
@@ -622,6 +659,11 @@ hipError_t launch_prefill(const MatDev* mats_in, int n_mats, int M, int x_dtype,
         while (i < n_mats) {
             PfArgs a;
             int cnt = 0, wgs = 0;
+            long long n_tiles = 0;                              // tiles along N of the launch's matrices
+            for (int j = i, c = 0; j < n_mats && c < kPfMaxMats; ++j)
+                if (mats[j].fmt == fmt) { n_tiles += mats[j].N / BN; ++c; }
+            const int bm = pick_bm(M, n_tiles);
+            const int m_tiles = (M + bm - 1) / bm;
             for (; i < n_mats && cnt < kPfMaxMats; ++i) {
                 const MatDev& m = mats[i];
                 if (m.fmt != fmt) continue;
@@ -638,9 +680,9 @@ hipError_t launch_prefill(const MatDev* mats_in, int n_mats, int M, int x_dtype,
             a.M = M; a.ydt = y_dtype; a.m_tiles = m_tiles; a.pad = 0;
             hipError_t e;
             const bool bf = x_dtype == DT_BF16;
-            if (fmt == FMT_SQ3) e = bf ? launch_fmt<true, FMT_SQ3>(a, wgs, s) : launch_fmt<false, FMT_SQ3>(a, wgs, s);
-            else if (fmt == FMT_VQ6) e = bf ? launch_fmt<true, FMT_VQ6>(a, wgs, s) : launch_fmt<false, FMT_VQ6>(a, wgs, s);
-            else e = bf ? launch_fmt<true, FMT_VQ8>(a, wgs, s) : launch_fmt<false, FMT_VQ8>(a, wgs, s);
+            if (fmt == FMT_SQ3) e = bf ? launch_fmt<true, FMT_SQ3>(a, wgs, bm / 32, s) : launch_fmt<false, FMT_SQ3>(a, wgs, bm / 32, s);
+            else if (fmt == FMT_VQ6) e = bf ? launch_fmt<true, FMT_VQ6>(a, wgs, bm / 32, s) : launch_fmt<false, FMT_VQ6>(a, wgs, bm / 32, s);
+            else e = bf ? launch_fmt<true, FMT_VQ8>(a, wgs, bm / 32, s) : launch_fmt<false, FMT_VQ8>(a, wgs, bm / 32, s);
             if (e != hipSuccess) return e;
         }
     }

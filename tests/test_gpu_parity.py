@@ -269,3 +269,26 @@ def test_config5_decode_layer(M):
 def test_config5_prefill_layer_sampled_rows():
     rows = np.sort(np.random.default_rng(1).choice(4096, size=4, replace=False))
     print("config5 prefill", _stack_layer_check(5, 4096, n_layers=1, rows=rows, fed="bf16", tight=2e-5), flush=True)
+
+
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+@pytest.mark.parametrize("xdt", ["bf16", "f16"])
+@pytest.mark.parametrize("N,K,M", [(256, 512, 64), (512, 768, 200), (256, 1024, 256), (512, 512, 300), (768, 256, 129)])
+def test_prefill_both_tile_heights(fmt, xdt, N, K, M, monkeypatch):
+    """The matrix-core kernel exists with 256 and with 128 rows of x per workgroup (the launcher picks
+    by how many tiles a launch has); both are forced in turn through the library's environment
+    override.  Same order of summation over k: the same bits, and each against the oracle."""
+    torch = G.torch_()
+    mat = make(fmt, N, K, 7)
+    x = acts(M, K, xdt, M + 1)
+    dm = B.upload(mat, native=True)
+    ys = {}
+    for bm in ("128", "256"):
+        print(f"prefill tile height {bm}: {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+        monkeypatch.setenv("RWKVQ_PREFILL_BM", bm)
+        ys[bm] = G.gpu_gemm(dm, x, xdt)
+    assert np.array_equal(ys["128"], ys["256"])
+    # against the oracle fed the rounding of the weights the kernel declares (the gate against exact
+    # binary32 weights is a statistical one for bf16 and is held by the other prefill tests)
+    asfed = orc.linear(mat, orc.widen(x, xdt), "f64", weight_round=xdt)
+    assert G.err_g2(ys["128"], asfed) <= 2e-5
