@@ -116,7 +116,11 @@ int rwkvq_vq_dequant(const void* indices, const void* codebooks, int layout, int
  *   canonical layout: a plain reference kernel (any M);
  *   native layout, M <= 16: streaming dequant-GEMV kernels bound by HBM bandwidth;
  *   native layout, M  > 16: tiles dequantized into LDS and multiplied on the matrix cores in
- *                           the type of x, weights rounded to that type.
+ *                           the type of x, weights rounded to that type;
+ *   native layout, 16 < M <= 128: the matrix cores (M padded to 128 rows), or ceil(M / 16) passes
+ *                           of the streaming kernels over blocks of 16 rows of x (weights exact),
+ *                           whichever is estimated cheaper for the matrices of the call: a call
+ *                           of few matrices gives the matrix-core kernel few tiles.
  * x and y must not overlap. */
 int rwkvq_sq_gemm(const void* codes, const void* scales, const void* zeros, int layout,
                   const void* x, void* y, int M, int N, int K, int bits, int group, int x_dtype,
@@ -133,7 +137,9 @@ int rwkvq_vq_gemm(const void* indices, const void* codebooks, int layout, const 
  * Reproducibility: a call gives the same bits every time.  At M = 1 the kernel is chosen by the
  * number of rows in the call (small calls split each row's columns over several wavefronts), so
  * the same matrix dispatched alone and inside a large call may differ in the order of its
- * binary32 sums (a few units in the last place); for 2 <= M and for M > 16 the order is fixed.
+ * binary32 sums (a few units in the last place); for 2 <= M <= 16 and for M > 128 the order is
+ * fixed; for 16 < M <= 128 the path (see rwkvq_sq_gemm) is chosen from the sizes of the call's
+ * matrices, not from their values.
  * No scratch memory; safe to record into a HIP graph. */
 int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void* const* ys,
                           int n_mats, int M, int x_dtype, int y_dtype, void* stream);

@@ -4,6 +4,8 @@
 #include "../../include/rwkvq.h"
 
 #include <cmath>
+#include <algorithm>
+#include <cstdlib>
 #include <vector>
 
 using namespace rwkvq;
@@ -70,6 +72,31 @@ rwkvq_matrix vq_desc(const void* indices, const void* codebooks, int layout, int
     m.kind = RWKVQ_VQ; m.layout = layout; m.N = N; m.K = K; m.vdim = vdim; m.kbits = kbits;
     m.block_rows = br; m.block_cols = bc; m.codes = indices; m.codebooks = codebooks;
     return m;
+}
+
+// Estimated cost, in microseconds, of the two ways to run native-layout matrices at 16 < M <= 128
+// (constants measured on the 7B shapes: a streaming pass moves 3.5 TB/s and costs at least 10 us;
+// a k-step of a 128-row matrix-core workgroup takes 1.35 us, one workgroup per compute unit).
+// RWKVQ_SMALL_BATCH_PATH=stream|mfma in the environment overrides the estimate (tests run both).
+constexpr int kStreamPassesMaxM = 128;
+bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
+    for (const MatDev& d : mats)
+        if (d.K > kDecodeMaxK) return false;
+    if (const char* e = std::getenv("RWKVQ_SMALL_BATCH_PATH")) {
+        if (e[0] == 's') return true;
+        if (e[0] == 'm') return false;
+    }
+    double bytes = 0.0, work = 0.0, longest = 0.0;
+    for (const MatDev& d : mats) {
+        const double nk = (double)d.N * d.K;
+        bytes += d.fmt == FMT_SQ3 ? nk * 3 / 8 + nk / kGroup * 4 : nk * (d.fmt == FMT_VQ8 ? 8 : 6) / 16;
+        work += (double)(d.N / 256) * (d.K / 64);
+        longest = std::max(longest, (double)(d.K / 64));
+    }
+    const int passes = (M + kDecodeMaxM - 1) / kDecodeMaxM;
+    const double t_stream = passes * (std::max(bytes / 3.5e6, 10.0) + 2.0);
+    const double t_mfma = 1.35 * std::max(work / 256.0, longest);
+    return t_stream < t_mfma;
 }
 
 }  // namespace
@@ -161,6 +188,22 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
     if (!decode.empty()) {
         hipError_t e = launch_decode(decode.data(), (int)decode.size(), M, x_dtype, y_dtype, s);
         if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
+    }
+    // 16 < M <= 128: the matrix-core kernel pads M to 128 rows, and a call of a few matrices gives
+    // it few tiles; ceil(M / 16) passes of the streaming kernels over row blocks of x can be cheaper.
+    if (!prefill.empty() && M <= kStreamPassesMaxM && stream_passes_cheaper(prefill, M)) {
+        const size_t ysz = y_dtype == RWKVQ_F32 ? 4 : 2;
+        std::vector<MatDev> blk(prefill);
+        for (int m0 = 0; m0 < M; m0 += kDecodeMaxM) {
+            for (size_t i = 0; i < blk.size(); ++i) {
+                blk[i].x = (const char*)prefill[i].x + (size_t)m0 * prefill[i].K * 2;
+                blk[i].y = (char*)prefill[i].y + (size_t)m0 * prefill[i].N * ysz;
+            }
+            hipError_t e = launch_decode(blk.data(), (int)blk.size(), M - m0 < kDecodeMaxM ? M - m0 : kDecodeMaxM, x_dtype,
+                                         y_dtype, s);
+            if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
+        }
+        return RWKVQ_OK;
     }
     if (!prefill.empty()) {
         hipError_t e = launch_prefill(prefill.data(), (int)prefill.size(), M, x_dtype, y_dtype, s);

@@ -292,3 +292,31 @@ def test_prefill_both_tile_heights(fmt, xdt, N, K, M, monkeypatch):
     # binary32 weights is a statistical one for bf16 and is held by the other prefill tests)
     asfed = orc.linear(mat, orc.widen(x, xdt), "f64", weight_round=xdt)
     assert G.err_g2(ys["128"], asfed) <= 2e-5
+
+
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+@pytest.mark.parametrize("xdt", ["bf16", "f16"])
+@pytest.mark.parametrize("N,K,M", [(512, 2048, 17), (256, 4096, 40), (768, 1024, 128), (256, 512, 100)])
+def test_small_batch_both_paths(fmt, xdt, N, K, M, monkeypatch):
+    """16 < M <= 128 runs either on the matrix cores (M padded to 128 rows) or as ceil(M / 16) passes
+    of the streaming kernels over row blocks of x, whichever the dispatcher estimates cheaper.  Both
+    are forced in turn; each against the oracle with the weights as that path feeds them (matrix
+    cores: rounded to the type of x; streaming: exact), and the free choice equals one of them."""
+    mat = make(fmt, N, K, 9)
+    x = acts(M, K, xdt, M + 2)
+    dm = B.upload(mat, native=True)
+    ys = {}
+    for path, fed in (("stream", None), ("mfma", xdt)):
+        print(f"small batch via {path}: {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+        monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", path)
+        ys[path] = G.gpu_gemm(dm, x, xdt)
+        asfed = orc.linear(mat, orc.widen(x, xdt), "f64", weight_round=fed)
+        assert G.err_g2(ys[path], asfed) <= 2e-5, path
+    monkeypatch.delenv("RWKVQ_SMALL_BATCH_PATH")
+    free = G.gpu_gemm(dm, x, xdt)
+    assert np.array_equal(free, ys["stream"]) or np.array_equal(free, ys["mfma"])
+    # fp16 output as well (the row blocks of y are addressed in its element size)
+    monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", "stream")
+    y16 = G.gpu_gemm(dm, x, xdt, B.F16)
+    back = orc.widen(y16, "f16").astype(np.float64)
+    assert np.abs(back - ys["stream"]).max() <= 2.0 ** -10 * np.abs(ys["stream"]).max()
