@@ -75,7 +75,7 @@ rwkvq_matrix vq_desc(const void* indices, const void* codebooks, int layout, int
 }
 
 // Estimated cost, in microseconds, of the two ways to run native-layout matrices at 16 < M <= 128
-// (constants measured on the 7B shapes: a streaming pass moves 3.5 TB/s and costs at least 10 us;
+// (constants measured on the 7B shapes: a streaming pass moves 4 TB/s and costs at least 10 us;
 // a k-step of a 128-row matrix-core workgroup takes 1.35 us, one workgroup per compute unit).
 // RWKVQ_SMALL_BATCH_PATH=stream|mfma in the environment overrides the estimate (tests run both).
 constexpr int kStreamPassesMaxM = 128;
@@ -94,7 +94,7 @@ bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
         longest = std::max(longest, (double)(d.K / 64));
     }
     const int passes = (M + kDecodeMaxM - 1) / kDecodeMaxM;
-    const double t_stream = passes * (std::max(bytes / 3.5e6, 10.0) + 2.0);
+    const double t_stream = passes * (std::max(bytes / 4.0e6, 10.0) + 2.0);
     const double t_mfma = 1.35 * std::max(work / 256.0, longest);
     return t_stream < t_mfma;
 }

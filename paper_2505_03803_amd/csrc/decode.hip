@@ -49,9 +49,18 @@ constexpr int kSplitTarget = RWKVQ_SPLIT_TARGET;   // wavefronts a batch-1 launc
 #ifndef RWKVQ_DECODE_RT
 #define RWKVQ_DECODE_RT 1
 #endif
-constexpr int kRT = RWKVQ_DECODE_RT;  // 16-row tiles per wavefront (1 or 2)
-constexpr int kWaveRows = 16 * kRT;
-constexpr int kWgRows = 4 * kWaveRows;
+constexpr int kRT = RWKVQ_DECODE_RT;  // batch 1: 16-row tiles per wavefront
+static_assert(kRT == 1, "the batch-1 tile loops hold one row tile per wavefront");
+#ifndef RWKVQ_DECODE_BATCH_RT
+#define RWKVQ_DECODE_BATCH_RT 2
+#endif
+// Batch 2..16: row tiles per wavefront.  Every wavefront reads the whole activation tile from LDS as
+// its A operands; with two row tiles those reads serve twice the weights (the batched path is bound
+// by LDS traffic: M = 16 gained 12-16 % per format over one row tile).
+constexpr int kBRT = RWKVQ_DECODE_BATCH_RT;
+static_assert(kBRT == 1 || kBRT == 2 || kBRT == 4, "row tiles of a wavefront share a 256-row codebook block");
+constexpr int rt_of(int MT) { return MT == 1 ? kRT : kBRT; }
+constexpr int wg_rows(int MT) { return 64 * rt_of(MT); }   // rows of W per workgroup of four wavefronts
 
 struct DecodeMat {
     const uint32_t* codes;
@@ -258,14 +267,14 @@ __device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_
     return v;
 }
 
-struct SqRegs { uint4_t a[kRT]; uint2_t b[kRT]; uint2_t sz[kRT]; XShared x; };
-struct Vq6Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XShared x; };
-struct Vq8Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XShared x; };
+struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x; };
+struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x; };
+struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x; };
 
-// Everything a tile loop needs about its wavefront's position; R0, R1 are the two row tiles
-// (R1 == R0 when the matrix has an odd number of row tiles and this is the last wavefront).
+// Everything a tile loop needs about its wavefront's position; R[i] are its row tiles (R[i] == R[0]
+// for the tiles past the end of the matrix: worked on again, not stored).
 struct WavePos {
-    int R[2], M, lane, tid;
+    int R[4], M, lane, tid;
     bool xbf16;
     int t0, ts, nt;      // split-K (batch 1): this wavefront's column tiles are t0, t0 + ts, ... (nt of them)
     // fused token-shift mix (batch 1): the previous token's activations, the mix weight's indices
@@ -284,11 +293,14 @@ struct WavePos {
 // activations come from the matrix cores too: one more MFMA per k-step with an all-ones B operand
 // leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
 template <int MT, int DEPTH>
-__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float4_t (&out)[kRT]) {
+__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float4_t (&out)[kBRT]) {
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
-    const uint2_t* sz[2] = {(const uint2_t*)mt.aux + (size_t)wp.R[0] * KT * 16,
-                            (const uint2_t*)mt.aux + (size_t)wp.R[1] * KT * 16};
+    const uint32_t* codes[kBRT];
+#pragma unroll
+    for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 384;
+    const uint2_t* sz[kBRT];
+#pragma unroll
+    for (int rt = 0; rt < kBRT; ++rt) sz[rt] = (const uint2_t*)mt.aux + (size_t)wp.R[rt] * KT * 16;
     const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
     // The and-or that builds 8 + q takes its mask from a VGPR and the fp16 pattern of 8.0 from an
     // SGPR: a VOP3 instruction of this ISA takes no literal and at most one scalar operand.
@@ -299,7 +311,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     const half8_t ones = __builtin_bit_cast(half8_t, ones4);
     auto load = [&](SqRegs& r, int T) {
 #pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
+        for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 384;
             r.a[rt] = *(const uint4_t*)(t + 4 * lane);
             r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
@@ -323,7 +335,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
 #pragma unroll
             for (int t = 0; t < 4; ++t) X = RWKVQ_MFMA(xa[u][t], ones, X);
 #pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
+            for (int rt = 0; rt < kBRT; ++rt) {
                 const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
                                w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
                 float4_t acc = {0, 0, 0, 0};
@@ -346,9 +358,11 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
 // slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
 template <int MT, int DEPTH>
 __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                        float4_t (&out)[kRT]) {
+                                        float4_t (&out)[kBRT]) {
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
+    const uint32_t* codes[kBRT];
+#pragma unroll
+    for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 384;
     const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
     const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
     const uint32_t base0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
@@ -356,7 +370,7 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
     auto load = [&](Vq6Regs& r, int T) {
 #pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
+        for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 384;
             r.a[rt] = *(const uint4_t*)(t + 4 * lane);
             r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
@@ -379,7 +393,7 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
 #pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
+            for (int rt = 0; rt < kBRT; ++rt) {
                 const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
                                w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
                 out[rt] = RWKVQ_MFMA(xa[u][0], __builtin_bit_cast(half8_t, vq6_gather4<0>(w0, w1, w2, m, base)), out[rt]);
@@ -396,14 +410,16 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
 // workgroup barrier that publishes the activations also orders that store before the gathers.
 template <int MT, int DEPTH>
 __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                        float4_t (&out)[kRT]) {
+                                        float4_t (&out)[kBRT]) {
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 512, mt.codes + (size_t)wp.R[1] * KT * 512};
+    const uint32_t* codes[kBRT];
+#pragma unroll
+    for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 512;
     const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
     const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
     auto load = [&](Vq8Regs& r, int T) {
 #pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
+        for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 512;
             r.a[rt] = *(const uint4_t*)(t + 4 * lane);
             r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
@@ -425,7 +441,7 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
             const half8_t xa2 = *(const half8_t*)(xrow + 128 * u + 64);
             const half8_t xa3 = *(const half8_t*)(xrow + 128 * u + 96);
 #pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) {
+            for (int rt = 0; rt < kBRT; ++rt) {
                 const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
                 out[rt] = RWKVQ_MFMA(xa0, vq8_operand(w.x, cbuf), out[rt]);
                 out[rt] = RWKVQ_MFMA(xa1, vq8_operand(w.y, cbuf), out[rt]);
@@ -743,13 +759,14 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
 
     const int NR = mt.N >> 4;
     WavePos wp;
-    wp.R[0] = kRT * (4 * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
-    const bool live = wp.R[0] < NR;                // rows beyond N (N not a multiple of kWgRows)
+    constexpr int RT = rt_of(MT);
+    wp.R[0] = RT * (4 * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
+    const bool live = wp.R[0] < NR;                // rows beyond N (N not a multiple of the workgroup's rows)
     wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xbf16;
 
     if constexpr (MT == 1) {
         if (!live) return;
-        wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
+        wp.R[1] = wp.R[2] = wp.R[3] = wp.R[0];
         float part[kRT];
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) part[rt] = 0.f;
@@ -758,7 +775,6 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
         else run_vq8_m1<DEPTH>(mt, wp, cb_all[wave], part);
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
-            if (rt == 1 && wp.R[1] == wp.R[0]) break;
             float v = part[rt];                    // sum the four column groups of each row
             v += __shfl_xor(v, 16, 64);
             v += __shfl_xor(v, 32, 64);
@@ -768,18 +784,19 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
         // every wavefront takes part in the shared activation tiles and their barriers; one
         // beyond the last row tile works on the last tile again and stores nothing
         if (!live) wp.R[0] = NR - 1;
-        wp.R[1] = (kRT == 2 && wp.R[0] + 1 < NR) ? wp.R[0] + 1 : wp.R[0];
-        float4_t out[kRT];
 #pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) out[rt] = float4_t{0, 0, 0, 0};
+        for (int rt = 1; rt < 4; ++rt) wp.R[rt] = (rt < RT && wp.R[0] + rt < NR) ? wp.R[0] + rt : wp.R[0];
+        float4_t out[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) out[rt] = float4_t{0, 0, 0, 0};
         if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH>(mt, wp, xs, out);
         else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
         else run_vq8<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
         if (!live) return;
         // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 of output column n
 #pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) {
-            if (rt == 1 && wp.R[1] == wp.R[0]) break;
+        for (int rt = 0; rt < RT; ++rt) {
+            if (rt > 0 && wp.R[rt] == wp.R[0]) break;
             const int n = 16 * wp.R[rt] + (lane & 15);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -813,7 +830,7 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KT = mt.K >> 8;
     WavePos wp;
-    wp.R[0] = wp.R[1] = wg - (mi ? a.wg_end[mi - 1] : 0);      // here wg_end counts row tiles
+    wp.R[0] = wp.R[1] = wp.R[2] = wp.R[3] = wg - (mi ? a.wg_end[mi - 1] : 0);      // here wg_end counts row tiles
     wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
     wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
     if constexpr (MIXED) {
@@ -905,7 +922,7 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[order[i]];
-            wgs += split ? (m.N + 15) / 16 : (m.N + kWgRows - 1) / kWgRows;
+            wgs += split ? (m.N + 15) / 16 : (m.N + wg_rows(M) - 1) / wg_rows(M);
             a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, posts ? posts[order[i]].op : POST_NONE,
                                posts ? posts[order[i]].gate : nullptr};
             a.wg_end[i] = wgs;
