@@ -32,12 +32,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 DECODE_KERNEL = "rwkvq::decode_kernel<1>"
-PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT>"   # bf16; one instantiation per weight format
+PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT, 8>"   # bf16; one instantiation per weight format
 PROXY_KERNEL = "rwkvq::proxy_set_kernel"
 DECODE_MATS_PER_LAUNCH = 256
 # HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
 # scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic_config3.txt.
-DECODE_TRAFFIC_BYTES_PER_LAUNCH = 2806.4e6
+DECODE_TRAFFIC_BYTES_PER_LAUNCH = 2806.7e6
 
 
 def log(*a):
