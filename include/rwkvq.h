@@ -117,8 +117,8 @@ int rwkvq_vq_dequant(const void* indices, const void* codebooks, int layout, int
  *   native layout, M <= 16: streaming dequant-GEMV kernels bound by HBM bandwidth;
  *   native layout, M  > 16: tiles dequantized into LDS and multiplied on the matrix cores in
  *                           the type of x, weights rounded to that type;
- *   native layout, 16 < M <= 128: the matrix cores (M padded to 128 rows), or ceil(M / 16) passes
- *                           of the streaming kernels over blocks of 16 rows of x (weights exact),
+ *   native layout, 16 < M <= 128: the matrix cores (M padded to 128 rows), or ceil(M / 32) passes
+ *                           of the streaming kernels over blocks of 32 rows of x (weights exact),
  *                           whichever is estimated cheaper for the matrices of the call: a call
  *                           of few matrices gives the matrix-core kernel few tiles.
  * x and y must not overlap. */

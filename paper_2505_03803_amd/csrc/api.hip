@@ -74,11 +74,13 @@ rwkvq_matrix vq_desc(const void* indices, const void* codebooks, int layout, int
     return m;
 }
 
-// Estimated cost, in microseconds, of the two ways to run native-layout matrices at 16 < M <= 128
-// (constants measured on the 7B shapes: a streaming pass moves 4 TB/s and costs at least 10 us;
-// a k-step of a 128-row matrix-core workgroup takes 1.35 us, one workgroup per compute unit).
+// Estimated cost, in microseconds, of the two ways to run native-layout matrices at 16 < M <= 128.
+// Constants measured on the 7B shapes: a streaming pass over 17..32 batch rows moves 2.8 TB/s of
+// packed weights and costs at least 24 us, one over <= 16 rows 4.1 TB/s and at least 12 us; a k-step
+// of a 128-row matrix-core workgroup takes 1.5 us, one workgroup per compute unit.
 // RWKVQ_SMALL_BATCH_PATH=stream|mfma in the environment overrides the estimate (tests run both).
 constexpr int kStreamPassesMaxM = 128;
+constexpr int kStreamPassRows = 32;    // batch rows per pass of the streaming kernels (their largest instance)
 bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
     for (const MatDev& d : mats)
         if (d.K > kDecodeMaxK) return false;
@@ -93,9 +95,10 @@ bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
         work += (double)(d.N / 256) * (d.K / 64);
         longest = std::max(longest, (double)(d.K / 64));
     }
-    const int passes = (M + kDecodeMaxM - 1) / kDecodeMaxM;
-    const double t_stream = passes * (std::max(bytes / 4.0e6, 10.0) + 2.0);
-    const double t_mfma = 1.35 * std::max(work / 256.0, longest);
+    const double wide = std::max(bytes / 2.8e6, 24.0), narrow = std::max(bytes / 4.1e6, 12.0);
+    const int full = M / kStreamPassRows, rest = M % kStreamPassRows;
+    const double t_stream = full * wide + (rest == 0 ? 0.0 : rest <= kDecodeMaxM ? narrow : wide);
+    const double t_mfma = 1.5 * std::max(work / 256.0, longest);
     return t_stream < t_mfma;
 }
 
@@ -190,17 +193,17 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
         if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
     }
     // 16 < M <= 128: the matrix-core kernel pads M to 128 rows, and a call of a few matrices gives
-    // it few tiles; ceil(M / 16) passes of the streaming kernels over row blocks of x can be cheaper.
+    // it few tiles; ceil(M / 32) passes of the streaming kernels over row blocks of x can be cheaper.
     if (!prefill.empty() && M <= kStreamPassesMaxM && stream_passes_cheaper(prefill, M)) {
         const size_t ysz = y_dtype == RWKVQ_F32 ? 4 : 2;
         std::vector<MatDev> blk(prefill);
-        for (int m0 = 0; m0 < M; m0 += kDecodeMaxM) {
+        for (int m0 = 0; m0 < M; m0 += kStreamPassRows) {
             for (size_t i = 0; i < blk.size(); ++i) {
                 blk[i].x = (const char*)prefill[i].x + (size_t)m0 * prefill[i].K * 2;
                 blk[i].y = (char*)prefill[i].y + (size_t)m0 * prefill[i].N * ysz;
             }
-            hipError_t e = launch_decode(blk.data(), (int)blk.size(), M - m0 < kDecodeMaxM ? M - m0 : kDecodeMaxM, x_dtype,
-                                         y_dtype, s);
+            hipError_t e = launch_decode(blk.data(), (int)blk.size(), M - m0 < kStreamPassRows ? M - m0 : kStreamPassRows,
+                                         x_dtype, y_dtype, s);
             if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
         }
         return RWKVQ_OK;

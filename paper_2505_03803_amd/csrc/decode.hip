@@ -21,11 +21,13 @@
 //     block): one workgroup of S wavefronts per row tile, the column tiles dealt round-robin, the
 //     partial sums added in LDS in a fixed order.  With MixedDecodeArgs the token-shift mix of
 //     Eq. "time mixing r/k/v" is applied while the activations are loaded.
-//   * Batch 2..16 (MT = 4, 16) on the matrix cores (v_mfma_f32_16x16x32_f16, activations = A
+//   * Batch 2..32 (MT = 4, 16, 32) on the matrix cores (v_mfma_f32_16x16x32_f16, activations = A
 //     operand, weights = B operand): the activation tile of a column tile is fetched once per
 //     workgroup into LDS (two buffers, one barrier per tile); SQ codes enter as 8 + q (one shift
 //     and one and-or per pair), the group sums X come from one more MFMA against an all-ones
-//     operand, y += s (acc - (8 + z) X); VQ pairs are LDS gathers.
+//     operand, y += s (acc - (8 + z) X); VQ pairs are LDS gathers.  A wavefront takes two row
+//     tiles of W, and with MT = 32 two groups of 16 batch rows: every unpacked weight operand
+//     feeds one MFMA per group.
 //   * bf16 activations are converted to fp16 on load (exact for |x| in [2^-14, 65504]).
 #include "common.h"
 #include <algorithm>
@@ -158,8 +160,8 @@ __device__ __forceinline__ void wave_lds_sync() {
 // into one of two LDS buffers.
 struct XShared { uint4_t a, b; };
 
-__device__ __forceinline__ void x_load_wg(XShared& r, const uint16_t* x, int M, int K, int T, int tid) {
-    const int row = (tid >> 4) < M ? (tid >> 4) : M - 1;
+__device__ __forceinline__ void x_load_wg(XShared& r, const uint16_t* x, int M, int K, int T, int tid, int g = 0) {
+    const int row = 16 * g + (tid >> 4) < M ? 16 * g + (tid >> 4) : M - 1;
     const uint16_t* p = x + (size_t)row * K + 256 * T + 16 * (tid & 15);
     r.a = *(const uint4_t*)p;
     r.b = *(const uint4_t*)(p + 8);
@@ -172,14 +174,14 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
 }
 
 template <int MT>
-__device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, int tid, bool bf16) {
-    if ((tid >> 4) < MT) {
+__device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, int tid, bool bf16, int g = 0) {
+    if (16 * g + (tid >> 4) < MT) {
         uint4_t a = r.a, b = r.b;
         if (bf16) {
             a.x = bf16x2_to_f16x2(a.x); a.y = bf16x2_to_f16x2(a.y); a.z = bf16x2_to_f16x2(a.z); a.w = bf16x2_to_f16x2(a.w);
             b.x = bf16x2_to_f16x2(b.x); b.y = bf16x2_to_f16x2(b.y); b.z = bf16x2_to_f16x2(b.z); b.w = bf16x2_to_f16x2(b.w);
         }
-        half_t* d = xs + (tid >> 4) * kXStride + 16 * (tid & 15);
+        half_t* d = xs + (16 * g + (tid >> 4)) * kXStride + 16 * (tid & 15);
         *(uint4_t*)d = a;
         *(uint4_t*)(d + 8) = b;
     }
@@ -267,9 +269,11 @@ __device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_
     return v;
 }
 
-struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x; };
-struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x; };
-struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x; };
+// G = groups of 16 batch rows (1 for batch <= 16, 2 for batch 17..32)
+constexpr int groups_of(int MT) { return MT <= 16 ? 1 : MT / 16; }
+template <int G> struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x[G]; };
+template <int G> struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x[G]; };
+template <int G> struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x[G]; };
 
 // Everything a tile loop needs about its wavefront's position; R[i] are its row tiles (R[i] == R[0]
 // for the tiles past the end of the matrix: worked on again, not stored).
@@ -293,7 +297,10 @@ struct WavePos {
 // activations come from the matrix cores too: one more MFMA per k-step with an all-ones B operand
 // leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
 template <int MT, int DEPTH>
-__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float4_t (&out)[kBRT]) {
+__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs,
+                                       float4_t (&out)[groups_of(MT)][kBRT]) {
+    constexpr int G = groups_of(MT), UB = G == 1 ? 2 : 1;   // one group: the fragments of both column halves up front
+    using Regs = SqRegs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
     const uint32_t* codes[kBRT];
 #pragma unroll
@@ -301,7 +308,9 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     const uint2_t* sz[kBRT];
 #pragma unroll
     for (int rt = 0; rt < kBRT; ++rt) sz[rt] = (const uint2_t*)mt.aux + (size_t)wp.R[rt] * KT * 16;
-    const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    int xoff[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
     // The and-or that builds 8 + q takes its mask from a VGPR and the fp16 pattern of 8.0 from an
     // SGPR: a VOP3 instruction of this ISA takes no literal and at most one scalar operand.
     uint32_t mask, magic;
@@ -309,7 +318,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
     const uint4_t ones4 = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
     const half8_t ones = __builtin_bit_cast(half8_t, ones4);
-    auto load = [&](SqRegs& r, int T) {
+    auto load = [&](Regs& r, int T) {
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 384;
@@ -317,58 +326,78 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
             r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
             r.sz[rt] = (sz[rt] + (size_t)T * 16)[lane & 15];
         }
-        x_load_wg(r.x, (const uint16_t*)mt.x, M, mt.K, T, wp.tid);
+#pragma unroll
+        for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
     };
-    auto compute = [&](const SqRegs& r, int T) {
+    auto compute = [&](const Regs& r, int T) {
         half_t* buf = xs + (T & 1) * (MT * kXStride);
-        x_store_wg<MT>(r.x, buf, wp.tid, wp.xbf16);
+#pragma unroll
+        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, wp.tid, wp.xbf16, g);
         __syncthreads();
-        const half_t* xrow = buf + xoff;
-        half8_t xa[2][4];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int ub = 0; ub < 2; ub += UB) {
+            half8_t xa[UB][G][4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+            for (int uu = 0; uu < UB; ++uu)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            float4_t X = {0, 0, 0, 0};               // X_g[m] for the lane's batch rows
+                for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) X = RWKVQ_MFMA(xa[u][t], ones, X);
+                    for (int t = 0; t < 4; ++t) xa[uu][g][t] = *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
 #pragma unroll
-            for (int rt = 0; rt < kBRT; ++rt) {
-                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
-                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
-                float4_t acc = {0, 0, 0, 0};
-                acc = RWKVQ_MFMA(xa[u][0], sq_operand<0>(w0, w1, w2, mask, magic), acc);
-                acc = RWKVQ_MFMA(xa[u][1], sq_operand<1>(w0, w1, w2, mask, magic), acc);
-                acc = RWKVQ_MFMA(xa[u][2], sq_operand<2>(w0, w1, w2, mask, magic), acc);
-                acc = RWKVQ_MFMA(xa[u][3], sq_operand<3>(w0, w1, w2, mask, magic), acc);
-                const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
-                const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
-                const float z8 = f16_bits_to_f32((uint16_t)(szw >> 16)) + 8.0f;
+            for (int uu = 0; uu < UB; ++uu) {
+                const int u = ub + uu;
+                float4_t X[G];                       // X_g[m] for the lane's batch rows
 #pragma unroll
-                for (int i = 0; i < 4; ++i) out[rt][i] = fmaf(s, fmaf(-z8, X[i], acc[i]), out[rt][i]);
+                for (int g = 0; g < G; ++g) {
+                    X[g] = float4_t{0, 0, 0, 0};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) X[g] = RWKVQ_MFMA(xa[uu][g][t], ones, X[g]);
+                }
+#pragma unroll
+                for (int rt = 0; rt < kBRT; ++rt) {
+                    const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                                   w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                    const half8_t op0 = sq_operand<0>(w0, w1, w2, mask, magic), op1 = sq_operand<1>(w0, w1, w2, mask, magic),
+                                  op2 = sq_operand<2>(w0, w1, w2, mask, magic), op3 = sq_operand<3>(w0, w1, w2, mask, magic);
+                    const uint32_t szw = u == 0 ? r.sz[rt].x : r.sz[rt].y;
+                    const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
+                    const float z8 = f16_bits_to_f32((uint16_t)(szw >> 16)) + 8.0f;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        float4_t acc = {0, 0, 0, 0};
+                        acc = RWKVQ_MFMA(xa[uu][g][0], op0, acc);
+                        acc = RWKVQ_MFMA(xa[uu][g][1], op1, acc);
+                        acc = RWKVQ_MFMA(xa[uu][g][2], op2, acc);
+                        acc = RWKVQ_MFMA(xa[uu][g][3], op3, acc);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(s, fmaf(-z8, X[g][i], acc[i]), out[g][rt][i]);
+                    }
+                }
             }
         }
     };
-    tile_pipeline<DEPTH, SqRegs>(KT, load, compute);
+    tile_pipeline<DEPTH, Regs>(KT, load, compute);
 }
 
 // 6-bit VQ: the codebook of a tile (64 entries, one per lane) goes through a wavefront-private LDS
 // slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
 template <int MT, int DEPTH>
 __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                        float4_t (&out)[kBRT]) {
+                                        float4_t (&out)[groups_of(MT)][kBRT]) {
+    constexpr int G = groups_of(MT), UB = G == 1 ? 2 : 1;
+    using Regs = Vq6Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
     const uint32_t* codes[kBRT];
 #pragma unroll
     for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 384;
     const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
-    const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    int xoff[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
     const uint32_t base0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
     uint32_t m;
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
-    auto load = [&](Vq6Regs& r, int T) {
+    auto load = [&](Regs& r, int T) {
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 384;
@@ -376,48 +405,66 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
             r.b[rt] = *(const uint2_t*)(t + 256 + 2 * lane);
         }
         r.cb = (cbs + (size_t)T * 64)[lane];
-        x_load_wg(r.x, (const uint16_t*)mt.x, M, mt.K, T, wp.tid);
+#pragma unroll
+        for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
     };
-    auto compute = [&](const Vq6Regs& r, int T) {
+    auto compute = [&](const Regs& r, int T) {
         half_t* buf = xs + (T & 1) * (MT * kXStride);
-        x_store_wg<MT>(r.x, buf, wp.tid, wp.xbf16);
+#pragma unroll
+        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, wp.tid, wp.xbf16, g);
         cb_lds[(T & 1) * 256 + lane] = r.cb;         // two slots, 1 KB apart (the gather address ORs the index in)
         __syncthreads();
         const uint32_t base = base0 + (T & 1) * 1024;
-        const half_t* xrow = buf + xoff;
-        half8_t xa[2][4];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int ub = 0; ub < 2; ub += UB) {
+            half8_t xa[UB][G][4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) xa[u][t] = *(const half8_t*)(xrow + 128 * u + 32 * t);
+            for (int uu = 0; uu < UB; ++uu)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+                for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int rt = 0; rt < kBRT; ++rt) {
-                const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
-                               w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
-                out[rt] = RWKVQ_MFMA(xa[u][0], __builtin_bit_cast(half8_t, vq6_gather4<0>(w0, w1, w2, m, base)), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa[u][1], __builtin_bit_cast(half8_t, vq6_gather4<1>(w0, w1, w2, m, base)), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa[u][2], __builtin_bit_cast(half8_t, vq6_gather4<2>(w0, w1, w2, m, base)), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa[u][3], __builtin_bit_cast(half8_t, vq6_gather4<3>(w0, w1, w2, m, base)), out[rt]);
+                    for (int t = 0; t < 4; ++t) xa[uu][g][t] = *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
+#pragma unroll
+            for (int uu = 0; uu < UB; ++uu) {
+                const int u = ub + uu;
+#pragma unroll
+                for (int rt = 0; rt < kBRT; ++rt) {
+                    const uint32_t w0 = u == 0 ? r.a[rt].x : r.a[rt].w, w1 = u == 0 ? r.a[rt].y : r.b[rt].x,
+                                   w2 = u == 0 ? r.a[rt].z : r.b[rt].y;
+                    const half8_t op0 = __builtin_bit_cast(half8_t, vq6_gather4<0>(w0, w1, w2, m, base)),
+                                  op1 = __builtin_bit_cast(half8_t, vq6_gather4<1>(w0, w1, w2, m, base)),
+                                  op2 = __builtin_bit_cast(half8_t, vq6_gather4<2>(w0, w1, w2, m, base)),
+                                  op3 = __builtin_bit_cast(half8_t, vq6_gather4<3>(w0, w1, w2, m, base));
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][0], op0, out[g][rt]);
+                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][1], op1, out[g][rt]);
+                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][2], op2, out[g][rt]);
+                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][3], op3, out[g][rt]);
+                    }
+                }
             }
         }
     };
-    tile_pipeline<DEPTH, Vq6Regs>(KT, load, compute);
+    tile_pipeline<DEPTH, Regs>(KT, load, compute);
 }
 
 // 8-bit VQ: the codebook of a tile (256 entries) goes through a wavefront-private LDS region; the
 // workgroup barrier that publishes the activations also orders that store before the gathers.
 template <int MT, int DEPTH>
 __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
-                                        float4_t (&out)[kBRT]) {
+                                        float4_t (&out)[groups_of(MT)][kBRT]) {
+    constexpr int G = groups_of(MT);
+    using Regs = Vq8Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
     const uint32_t* codes[kBRT];
 #pragma unroll
     for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 512;
     const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
-    const int xoff = ((lane & 15) < M ? (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    auto load = [&](Vq8Regs& r, int T) {
+    int xoff[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    auto load = [&](Regs& r, int T) {
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[rt] + (size_t)T * 512;
@@ -425,32 +472,39 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
             r.b[rt] = *(const uint4_t*)(t + 256 + 4 * lane);
         }
         r.cb = (cbs + (size_t)T * 64)[lane];
-        x_load_wg(r.x, (const uint16_t*)mt.x, M, mt.K, T, wp.tid);
+#pragma unroll
+        for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
     };
-    auto compute = [&](const Vq8Regs& r, int T) {
+    auto compute = [&](const Regs& r, int T) {
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         uint32_t* cbuf = cb_lds + (T & 1) * 256;     // two codebook slots, like the activations
-        x_store_wg<MT>(r.x, buf, wp.tid, wp.xbf16);
+#pragma unroll
+        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, wp.tid, wp.xbf16, g);
         *(uint4_t*)(cbuf + 4 * lane) = r.cb;
         __syncthreads();
-        const half_t* xrow = buf + xoff;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const half8_t xa0 = *(const half8_t*)(xrow + 128 * u + 0);
-            const half8_t xa1 = *(const half8_t*)(xrow + 128 * u + 32);
-            const half8_t xa2 = *(const half8_t*)(xrow + 128 * u + 64);
-            const half8_t xa3 = *(const half8_t*)(xrow + 128 * u + 96);
+            half8_t xa[G][4];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) xa[g][t] = *(const half8_t*)(buf + xoff[g] + 128 * u + 32 * t);
 #pragma unroll
             for (int rt = 0; rt < kBRT; ++rt) {
                 const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
-                out[rt] = RWKVQ_MFMA(xa0, vq8_operand(w.x, cbuf), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa1, vq8_operand(w.y, cbuf), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa2, vq8_operand(w.z, cbuf), out[rt]);
-                out[rt] = RWKVQ_MFMA(xa3, vq8_operand(w.w, cbuf), out[rt]);
+                const half8_t op0 = vq8_operand(w.x, cbuf), op1 = vq8_operand(w.y, cbuf), op2 = vq8_operand(w.z, cbuf),
+                              op3 = vq8_operand(w.w, cbuf);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    out[g][rt] = RWKVQ_MFMA(xa[g][0], op0, out[g][rt]);
+                    out[g][rt] = RWKVQ_MFMA(xa[g][1], op1, out[g][rt]);
+                    out[g][rt] = RWKVQ_MFMA(xa[g][2], op2, out[g][rt]);
+                    out[g][rt] = RWKVQ_MFMA(xa[g][3], op3, out[g][rt]);
+                }
             }
         }
     };
-    tile_pipeline<DEPTH, Vq8Regs>(KT, load, compute);
+    tile_pipeline<DEPTH, Regs>(KT, load, compute);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -736,7 +790,7 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
 // (its unpack is the cheapest per weight) while the VQ matrices use the vector-ALU path above,
 // whose LDS gathers are cheaper than ds_bpermute.
 template <int MT>
-__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : 2) decode_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : MT == 16 ? 2 : 1) decode_kernel(DecodeArgs a) {
     constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : 2;
     // batch > 1: two activation tiles shared by the workgroup; codebook slots per wavefront
     __shared__ __attribute__((aligned(16))) half_t xs[MT == 1 ? 8 : 2 * MT * kXStride];
@@ -786,23 +840,28 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
         if (!live) wp.R[0] = NR - 1;
 #pragma unroll
         for (int rt = 1; rt < 4; ++rt) wp.R[rt] = (rt < RT && wp.R[0] + rt < NR) ? wp.R[0] + rt : wp.R[0];
-        float4_t out[RT];
+        constexpr int G = groups_of(MT);
+        float4_t out[G][RT];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) out[rt] = float4_t{0, 0, 0, 0};
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) out[g][rt] = float4_t{0, 0, 0, 0};
         if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH>(mt, wp, xs, out);
         else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
         else run_vq8<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
         if (!live) return;
-        // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 of output column n
+        // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 (of its group) of output column n
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             if (rt > 0 && wp.R[rt] == wp.R[0]) break;
             const int n = 16 * wp.R[rt] + (lane & 15);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = 4 * (lane >> 4) + i;
-                if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, out[rt][i]);
-            }
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int m = 16 * g + 4 * (lane >> 4) + i;
+                    if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, out[g][rt][i]);
+                }
         }
     }
 }
@@ -935,7 +994,8 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         if (split) { hipError_t e = launch_splitk(split, wgs, a, s); if (e != hipSuccess) return e; }
         else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
         else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
-        else hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(256), 0, s, a);
+        else if (M <= 16) hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(decode_kernel<32>, dim3(wgs), dim3(256), 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

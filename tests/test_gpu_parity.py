@@ -96,8 +96,9 @@ def test_decode_batch1_launch_shapes(fmt, N, K):
 @pytest.mark.parametrize("fmt,N,K", [("sq", 256, 768), ("vq6", 256, 768), ("vq8", 512, 512)])
 @pytest.mark.parametrize("M", [17, 256, 300])
 @pytest.mark.parametrize("xdt", ["bf16", "f16"])
-def test_prefill_small(fmt, N, K, M, xdt):
+def test_prefill_small(fmt, N, K, M, xdt, monkeypatch):
     print(f"prefill {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+    monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", "mfma")     # M = 17 on the matrix cores, whatever the estimate says
     mat = make(fmt, N, K, 4)
     x = acts(M, K, xdt, M)
     y = G.gpu_gemm(B.upload(mat, native=True), x, xdt)
@@ -298,8 +299,9 @@ def test_prefill_both_tile_heights(fmt, xdt, N, K, M, monkeypatch):
 @pytest.mark.parametrize("xdt", ["bf16", "f16"])
 @pytest.mark.parametrize("N,K,M", [(512, 2048, 17), (256, 4096, 40), (768, 1024, 128), (256, 512, 100)])
 def test_small_batch_both_paths(fmt, xdt, N, K, M, monkeypatch):
-    """16 < M <= 128 runs either on the matrix cores (M padded to 128 rows) or as ceil(M / 16) passes
-    of the streaming kernels over row blocks of x, whichever the dispatcher estimates cheaper.  Both
+    """16 < M <= 128 runs either on the matrix cores (M padded to 128 rows) or as ceil(M / 32) passes
+    of the streaming kernels over row blocks of x (the 17..32-row instance, then one for the rest),
+    whichever the dispatcher estimates cheaper.  Both
     are forced in turn; each against the oracle with the weights as that path feeds them (matrix
     cores: rounded to the type of x; streaming: exact), and the free choice equals one of them."""
     mat = make(fmt, N, K, 9)
