@@ -225,6 +225,26 @@ def sequential_step(dec, n_layers):
                     "block = the fused step plus the element-wise operators between the stages"}
 
 
+def batched_decode(dec):
+    """The decode stack at batches 4, 16 (streaming kernels, 2..16 rows), 32 (their 17..32-row instance) and
+    64 (two passes of it, or the matrix cores: whichever the dispatcher estimates cheaper)."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    res = {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    for M in (4, 16, 32, 64):
+        xs = [torch.randn((M, int(d.K)), device="cuda", generator=gen).to(torch.float16).view(torch.int16) for d in dec["descs"]]
+        ys = [torch.empty((M, int(d.N)), dtype=torch.int16, device="cuda") for d in dec["descs"]]
+        table = B.DispatchTable(dec["descs"], xs, ys)
+        total, _, _ = time_steps(lambda: B.rwkvq_linear_dispatch(table, M, B.F16, B.F16), 300, 150)
+        ms = total / 300
+        res[f"M{M}"] = {"ms_per_step": ms, "weight_GBps": dec["wbytes"] / (ms * 1e-3) / 1e9, "tokens_per_s": M * 1e3 / ms}
+        del xs, ys, table
+    res["note"] = "same 256 matrices, one rwkvq_linear_dispatch call per step; weight_GBps counts the packed weights once per step"
+    return res
+
+
 def prefill_block_step(pf, n_layers, M):
     """A chunk of M tokens through the stack in data-flow order with the block's element-wise operators
     (App. A.1): per layer  mix pass (4 projections) -> {r, k, v, g} -> wkv with its gate -> W_o -> mix
@@ -334,6 +354,7 @@ def main():
     ap.add_argument("--skip-proxy", action="store_true", help="skip the proxy and encoder legs")
     ap.add_argument("--skip-encode", action="store_true")
     ap.add_argument("--skip-mu", action="store_true", help="skip the element-wise multiplication leg")
+    ap.add_argument("--skip-batched", action="store_true", help="skip the small-batch decode figures")
     ap.add_argument("--skip-sequential", action="store_true", help="skip the dependency-ordered token step")
     ap.add_argument("--proxy-layers", type=int, default=8, help="layers of dense bf16 weights the proxy leg scans per call")
     ap.add_argument("--cpu-layers", type=int, default=32)
@@ -391,6 +412,9 @@ def main():
                      "algorithmic_bytes_per_launch": dec["wbytes"] / launches,
                      "avg_launch_ms": ms / launches},
     }
+    # ---------------- the same matrices at small batches (one grouped call per step)
+    if not args.skip_batched:
+        out["decode_batched"] = batched_decode(dec)
     # ---------------- the same matrices in data-flow order, one HIP graph per token step
     if not args.skip_sequential:
         out["sequential_step"] = sequential_step(dec, args.layers)
