@@ -120,7 +120,9 @@ int rwkvq_vq_dequant(const void* indices, const void* codebooks, int layout, int
  *   native layout, 16 < M <= 128: the matrix cores (M padded to 128 rows), or ceil(M / 32) passes
  *                           of the streaming kernels over blocks of 32 rows of x (weights exact),
  *                           whichever is estimated cheaper for the matrices of the call: a call
- *                           of few matrices gives the matrix-core kernel few tiles.
+ *                           of few matrices gives the matrix-core kernel few tiles.  A matrix
+ *                           whose N is not a multiple of 256 has no matrix-core tiles: streaming
+ *                           passes up to M = 128, beyond that the plain reference kernel.
  * x and y must not overlap. */
 int rwkvq_sq_gemm(const void* codes, const void* scales, const void* zeros, int layout,
                   const void* x, void* y, int M, int N, int K, int bits, int group, int x_dtype,

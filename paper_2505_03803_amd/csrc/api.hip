@@ -172,7 +172,7 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
     int st;
     if ((st = check_dtype_x(x_dtype)) != RWKVQ_OK) return st;
     if ((st = check_dtype_y(y_dtype)) != RWKVQ_OK) return st;
-    std::vector<MatDev> decode, prefill, ref;
+    std::vector<MatDev> decode, prefill, passes, ref;
     for (int i = 0; i < n_mats; ++i) {
         if (!xs[i] || !ys[i]) return RWKVQ_ERR_NULL;
         if (!aligned16(xs[i]) || !aligned16(ys[i])) return RWKVQ_ERR_ALIGN;
@@ -181,6 +181,7 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
         if (d.layout == RWKVQ_CANONICAL) ref.push_back(d);
         else if (M <= kDecodeMaxM && d.K <= kDecodeMaxK) decode.push_back(d);
         else if (M > kDecodeMaxM && d.N % 256 == 0) prefill.push_back(d);
+        else if (M <= kStreamPassesMaxM && d.K <= kDecodeMaxK) passes.push_back(d);   // N not a multiple of 256: no matrix-core tiles
         else ref.push_back(d);   // matrix-core tiles are 256 rows of W wide
     }
     hipStream_t s = (hipStream_t)stream;
@@ -195,18 +196,21 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
     // 16 < M <= 128: the matrix-core kernel pads M to 128 rows, and a call of a few matrices gives
     // it few tiles; ceil(M / 32) passes of the streaming kernels over row blocks of x can be cheaper.
     if (!prefill.empty() && M <= kStreamPassesMaxM && stream_passes_cheaper(prefill, M)) {
+        passes.insert(passes.end(), prefill.begin(), prefill.end());
+        prefill.clear();
+    }
+    if (!passes.empty()) {
         const size_t ysz = y_dtype == RWKVQ_F32 ? 4 : 2;
-        std::vector<MatDev> blk(prefill);
+        std::vector<MatDev> blk(passes);
         for (int m0 = 0; m0 < M; m0 += kStreamPassRows) {
             for (size_t i = 0; i < blk.size(); ++i) {
-                blk[i].x = (const char*)prefill[i].x + (size_t)m0 * prefill[i].K * 2;
-                blk[i].y = (char*)prefill[i].y + (size_t)m0 * prefill[i].N * ysz;
+                blk[i].x = (const char*)passes[i].x + (size_t)m0 * passes[i].K * 2;
+                blk[i].y = (char*)passes[i].y + (size_t)m0 * passes[i].N * ysz;
             }
             hipError_t e = launch_decode(blk.data(), (int)blk.size(), M - m0 < kStreamPassRows ? M - m0 : kStreamPassRows,
                                          x_dtype, y_dtype, s);
             if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
         }
-        return RWKVQ_OK;
     }
     if (!prefill.empty()) {
         hipError_t e = launch_prefill(prefill.data(), (int)prefill.size(), M, x_dtype, y_dtype, s);

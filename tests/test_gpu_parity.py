@@ -322,3 +322,26 @@ def test_small_batch_both_paths(fmt, xdt, N, K, M, monkeypatch):
     y16 = G.gpu_gemm(dm, x, xdt, B.F16)
     back = orc.widen(y16, "f16").astype(np.float64)
     assert np.abs(back - ys["stream"]).max() <= 2.0 ** -10 * np.abs(ys["stream"]).max()
+
+
+@pytest.mark.parametrize("M", [17, 50, 128])
+def test_small_batch_rows_not_multiple_of_256(M):
+    """A native-layout matrix whose N is not a multiple of 256 has no matrix-core tiles; up to M = 128
+    it runs as passes of the streaming kernels (exact weights), together with ordinary matrices of
+    the same call."""
+    torch = G.torch_()
+    mats = [make("sq", 48, 768, 11), make("vq6", 256, 768, 12), make("sq", 400, 512, 13)]
+    xs = [acts(M, m.K, "bf16", M + i) for i, m in enumerate(mats)]
+    dms = [B.upload(m, native=True) for m in mats]
+    xd = [G.to_dev_bits(x) for x in xs]
+    ys = [torch.zeros((M, m.N), dtype=torch.float32, device="cuda") for m in mats]
+    print(f"small batch, ragged N, M={M}", flush=True)
+    B.rwkvq_linear_dispatch(B.DispatchTable([d.desc() for d in dms], xd, ys), M, B.BF16, B.F32)
+    torch.cuda.synchronize()
+    for i, (m, x, y) in enumerate(zip(mats, xs, ys)):
+        exact = orc.linear(m, orc.widen(x, "bf16"), "f64")
+        got = y.cpu().numpy().astype(np.float64)
+        if m.N % 256:
+            assert G.err_g2(got, exact) <= 2e-5, i          # streaming passes: exact weights
+        elif G.err_g2(got, exact) > 2e-5:                   # the dispatcher chose the matrix cores for this one
+            G.check_outputs(got, m, x, "bf16", fed="bf16")
