@@ -146,6 +146,19 @@ int rwkvq_vq_gemm(const void* indices, const void* codebooks, int layout, const 
 int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void* const* ys,
                           int n_mats, int M, int x_dtype, int y_dtype, void* stream);
 
+/* Which kernels rwkvq_linear_dispatch would run for each matrix of such a call (no launch, no device
+ * access; the weight pointers of the descriptors must be non-NULL and aligned but are not read).
+ * paths[i], HOST, one of:
+ *   RWKVQ_PATH_REFERENCE     plain reference kernel (canonical layout; shapes no other path takes);
+ *   RWKVQ_PATH_STREAM        streaming kernels, M <= 16: weights exact;
+ *   RWKVQ_PATH_STREAM_PASSES ceil(M / 32) passes of the streaming kernels, 16 < M <= 128: weights exact;
+ *   RWKVQ_PATH_MATRIX_CORES  matrix-core kernels: weights rounded once to the type of x.
+ * The path depends on M and on the sizes and layouts of the call's matrices only (see rwkvq_sq_gemm),
+ * so a caller can learn beforehand how the weights of a call will be fed.  Errors: RWKVQ_ERR_NULL,
+ * RWKVQ_ERR_SHAPE, and those of the descriptors. */
+enum { RWKVQ_PATH_REFERENCE = 0, RWKVQ_PATH_STREAM = 1, RWKVQ_PATH_STREAM_PASSES = 2, RWKVQ_PATH_MATRIX_CORES = 3 };
+int rwkvq_linear_dispatch_plan(const rwkvq_matrix* mats, int n_mats, int M, int32_t* paths);
+
 /* ---- the SQ / VQ decision (Sec. 3.1, "Coarse-grained Proxy" and "Fine-grained Proxy") ----------
  *
  * For each of n_mats dense weight matrices ws[i] (DEVICE pointers in a HOST array; matrix i is

@@ -22,7 +22,7 @@ EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
            "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
-           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post"]
+           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan"]
 
 
 class rwkvq_mix_input(Structure):
@@ -112,6 +112,8 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_linear_dispatch_post.restype = c_int
         L.rwkvq_linear_dispatch_post.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
                                                  c_void_p]
+        L.rwkvq_linear_dispatch_plan.restype = c_int
+        L.rwkvq_linear_dispatch_plan.argtypes = [c_void_p, c_int, c_int, c_void_p]
         L.rwkvq_wkv.restype = c_int
         L.rwkvq_wkv.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
                                 c_void_p, c_void_p]
@@ -457,3 +459,18 @@ def rwkvq_linear_dispatch_post(table: PostDispatchTable, x_dtype, y_dtype, strea
     st = lib().rwkvq_linear_dispatch_post(table.mats, table.xs, table.mixes, table.posts, table.ys, table.n, x_dtype,
                                           y_dtype, _stream(stream))
     return _check(st) if check else st
+
+
+PATH_REFERENCE, PATH_STREAM, PATH_STREAM_PASSES, PATH_MATRIX_CORES = 0, 1, 2, 3
+
+
+def rwkvq_linear_dispatch_plan(descs: Sequence, M: int, check=True):
+    """The path (PATH_*) each matrix of a dispatch call with these descriptors and this M would take."""
+    n = len(descs)
+    mats = (rwkvq_matrix * n)(*descs)
+    paths = (c_int32 * n)()
+    st = lib().rwkvq_linear_dispatch_plan(mats, n, M, paths)
+    if check:
+        _check(st)
+        return list(paths)
+    return st

@@ -102,6 +102,25 @@ bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
     return t_stream < t_mfma;
 }
 
+// Which kernels run each matrix of a call (values of RWKVQ_PATH_*): the one place that decides.
+void plan_paths(const std::vector<MatDev>& devs, int M, std::vector<int>* path) {
+    path->assign(devs.size(), RWKVQ_PATH_REFERENCE);
+    std::vector<MatDev> mfma;
+    for (size_t i = 0; i < devs.size(); ++i) {
+        const MatDev& d = devs[i];
+        if (d.layout == RWKVQ_CANONICAL) continue;
+        if (M <= kDecodeMaxM && d.K <= kDecodeMaxK) (*path)[i] = RWKVQ_PATH_STREAM;
+        else if (M > kDecodeMaxM && d.N % 256 == 0) { (*path)[i] = RWKVQ_PATH_MATRIX_CORES; mfma.push_back(d); }
+        else if (M > kDecodeMaxM && M <= kStreamPassesMaxM && d.K <= kDecodeMaxK)
+            (*path)[i] = RWKVQ_PATH_STREAM_PASSES;        // N not a multiple of 256: no matrix-core tiles
+    }
+    // 16 < M <= 128: the matrix-core kernel pads M to 128 rows, and a call of a few matrices gives
+    // it few tiles; ceil(M / 32) passes of the streaming kernels over row blocks of x can be cheaper.
+    if (!mfma.empty() && M <= kStreamPassesMaxM && stream_passes_cheaper(mfma, M))
+        for (int& p : *path)
+            if (p == RWKVQ_PATH_MATRIX_CORES) p = RWKVQ_PATH_STREAM_PASSES;
+}
+
 }  // namespace
 
 extern "C" {
@@ -172,18 +191,18 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
     int st;
     if ((st = check_dtype_x(x_dtype)) != RWKVQ_OK) return st;
     if ((st = check_dtype_y(y_dtype)) != RWKVQ_OK) return st;
-    std::vector<MatDev> decode, prefill, passes, ref;
+    std::vector<MatDev> devs((size_t)n_mats);
     for (int i = 0; i < n_mats; ++i) {
         if (!xs[i] || !ys[i]) return RWKVQ_ERR_NULL;
         if (!aligned16(xs[i]) || !aligned16(ys[i])) return RWKVQ_ERR_ALIGN;
-        MatDev d;
-        if ((st = to_dev(mats[i], xs[i], ys[i], &d)) != RWKVQ_OK) return st;
-        if (d.layout == RWKVQ_CANONICAL) ref.push_back(d);
-        else if (M <= kDecodeMaxM && d.K <= kDecodeMaxK) decode.push_back(d);
-        else if (M > kDecodeMaxM && d.N % 256 == 0) prefill.push_back(d);
-        else if (M <= kStreamPassesMaxM && d.K <= kDecodeMaxK) passes.push_back(d);   // N not a multiple of 256: no matrix-core tiles
-        else ref.push_back(d);   // matrix-core tiles are 256 rows of W wide
+        if ((st = to_dev(mats[i], xs[i], ys[i], &devs[(size_t)i])) != RWKVQ_OK) return st;
     }
+    std::vector<int> path;
+    plan_paths(devs, M, &path);
+    std::vector<MatDev> decode, prefill, passes, ref;
+    for (size_t i = 0; i < devs.size(); ++i)
+        (path[i] == RWKVQ_PATH_STREAM ? decode : path[i] == RWKVQ_PATH_MATRIX_CORES ? prefill
+         : path[i] == RWKVQ_PATH_STREAM_PASSES ? passes : ref).push_back(devs[i]);
     hipStream_t s = (hipStream_t)stream;
     for (const MatDev& d : ref) {
         hipError_t e = launch_ref_gemm(d, M, x_dtype, y_dtype, s);
@@ -192,12 +211,6 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
     if (!decode.empty()) {
         hipError_t e = launch_decode(decode.data(), (int)decode.size(), M, x_dtype, y_dtype, s);
         if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
-    }
-    // 16 < M <= 128: the matrix-core kernel pads M to 128 rows, and a call of a few matrices gives
-    // it few tiles; ceil(M / 32) passes of the streaming kernels over row blocks of x can be cheaper.
-    if (!prefill.empty() && M <= kStreamPassesMaxM && stream_passes_cheaper(prefill, M)) {
-        passes.insert(passes.end(), prefill.begin(), prefill.end());
-        prefill.clear();
     }
     if (!passes.empty()) {
         const size_t ysz = y_dtype == RWKVQ_F32 ? 4 : 2;
@@ -216,6 +229,20 @@ int rwkvq_linear_dispatch(const rwkvq_matrix* mats, const void* const* xs, void*
         hipError_t e = launch_prefill(prefill.data(), (int)prefill.size(), M, x_dtype, y_dtype, s);
         if (e != hipSuccess) return RWKVQ_ERR_DEVICE;
     }
+    return RWKVQ_OK;
+}
+
+int rwkvq_linear_dispatch_plan(const rwkvq_matrix* mats, int n_mats, int M, int32_t* paths) {
+    if (!mats || !paths) return RWKVQ_ERR_NULL;
+    if (n_mats <= 0 || M <= 0 || M > (1 << 19)) return RWKVQ_ERR_SHAPE;
+    std::vector<MatDev> devs((size_t)n_mats);
+    for (int i = 0; i < n_mats; ++i) {
+        int st = to_dev(mats[i], nullptr, nullptr, &devs[(size_t)i]);
+        if (st != RWKVQ_OK) return st;
+    }
+    std::vector<int> path;
+    plan_paths(devs, M, &path);
+    for (int i = 0; i < n_mats; ++i) paths[i] = path[(size_t)i];
     return RWKVQ_OK;
 }
 
