@@ -76,6 +76,35 @@ def build_stack(config: int, M: int, n_layers, gpu_activations: bool, y_dtype):
                 n_mats=len(descs), x_dtype=B.DTYPES[xdt], descs=descs, ys=ys)
 
 
+def scale_weights(dm, a: float):
+    """Deq(W) <- a * Deq(W) for a matrix on the device (SQ: the fp16 scales; VQ: the codebook entries)."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    if dm.kind == B.SQ:
+        dm.scales.view(torch.float16)[0::2] *= a           # native layout: (scale, zero) pairs
+    else:
+        dm.codebooks.view(torch.float16).mul_(a)
+
+
+def rms16(t, bf16=False):
+    import torch
+    return float(t.view(torch.bfloat16 if bf16 else torch.float16).float().pow(2).mean().sqrt())
+
+
+def unit_gain(stack, M, bf16=False):
+    """Rescale every matrix of a resident stack so that N(0, 1) activations give outputs of unit rms.  The
+    synthetic weights are not a trained model's and App. A.1 prints no normalisation: left as drawn, the
+    values that flow from block to block overflow after two blocks and the legs that chain the stages would be
+    timed on NaNs.  Done after the grouped legs, which keep the weights as the recipe draws them."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    B.rwkvq_linear_dispatch(stack["table"], M, stack["x_dtype"], B.BF16 if bf16 else B.F16)
+    torch.cuda.synchronize()
+    for dm, y in zip(stack["keep"][0], stack["keep"][2]):
+        scale_weights(dm, 1.0 / max(rms16(y, bf16), 1e-6))
+    torch.cuda.synchronize()
+
+
 def sequential_step(dec, n_layers):
     """One token through the stack with the dependencies of an RWKV block between the launches:
     per layer  mix (4 projections) -> {receptance, key, value, gate} -> output -> mix (2) ->
@@ -160,6 +189,36 @@ def sequential_step(dec, n_layers):
         block.append(("lin", B.DispatchTable([D[6]], [sq], [Y[6]])))
         block.append(("gate", (Y[7], Y[6], outb)))
 
+    def launch(kind, a):
+        if kind == "mixed":
+            B.rwkvq_linear_dispatch_mixed(a, B.F16, B.F16)
+        elif kind == "lin":
+            B.rwkvq_linear_dispatch(a, 1, B.F16, B.F16)
+        elif kind == "wkv":
+            B.rwkvq_wkv(a[0], a[1], a[2], B.F16, 1, d, a[3], a[4], a[5], a[6])
+        elif kind == "relu2":
+            B.rwkvq_relu2(a[0], B.F16, ffn, a[1])
+        else:
+            B.rwkvq_sigmoid_gate(a[0], a[1], B.F16, d, a[2])
+
+    # every block's output back to unit rms (a per-layer factor on W'_v, found block by block on this
+    # token): with unit-gain matrices alone the squared ReLU and the gates shrink the values tenfold per
+    # block, and after a few blocks the step would run on zeros
+    flow = []
+    for layer in range(n_layers):
+        for kind, a in block[7 * layer: 7 * layer + 7]:
+            launch(kind, a)
+        torch.cuda.synchronize()
+        outb = block[7 * layer + 6][1][2]
+        scale_weights(dec["keep"][0][8 * layer + 6], 1.0 / max(rms16(outb), 1e-6))
+        for kind, a in block[7 * layer + 5: 7 * layer + 7]:
+            launch(kind, a)
+        torch.cuda.synchronize()
+        flow.append(rms16(outb))
+    for layer in range(n_layers):                              # the wkv states back to the empty sums
+        st = block[7 * layer + 1][1][5]
+        st[:2].zero_(); st[2].fill_(-1e38)
+
     def step_block():
         for kind, a in block:
             if kind == "mixed":
@@ -211,11 +270,14 @@ def sequential_step(dec, n_layers):
     ms_fused = timed(step_fused)
     ms_block7 = timed(step_block)
     ms_block = timed(step_block5)
+    last = block[-1][1][2].view(torch.float16).float()
+    final_ok = bool(torch.isfinite(last).all()) and float(last.abs().max()) > 0.0
     eager_ms = time_steps(step, 200, 50)[0] / 200
     return {"ms_per_step": ms_fused, "tokens_per_s": 1e3 / ms_fused, "value": dec["wbytes"] / (ms_fused * 1e-3) / 1e9,
             "unit": "GB/s", "launches_per_step": len(fused),
             "unfused": {"ms_per_step": ms, "launches_per_step": len(stages), "eager_ms_per_step": eager_ms},
             "block": {"ms_per_step": ms_block, "tokens_per_s": 1e3 / ms_block, "launches_per_step": len(block5),
+                      "block_output_rms_min_max": [min(flow), max(flow)], "final_output_finite": final_ok,
                       "separate_operators": {"ms_per_step": ms_block7, "launches_per_step": len(block)},
                       "note": "with the element-wise operators of the block: wkv recurrence and its gate as one "
                               "launch, squared ReLU and output gate applied by the GEMVs that produce their operands "
@@ -279,23 +341,41 @@ def prefill_block_step(pf, n_layers, M):
                    ("relu2", (Y[5], sq)), ("lin", B.DispatchTable([D[6]], [sq], [Y[6]])), ("gate", (Y[7], Y[6], out))]
         src = out
 
+    def launch(kind, a):
+        if kind == "mix":
+            B.rwkvq_token_shift_mix(a[0], hprev, B.BF16, M, d, a[1], 6)
+        elif kind == "lin":
+            B.rwkvq_linear_dispatch(a, M, B.BF16, B.BF16)
+        elif kind == "wkv":
+            B.rwkvq_wkv(a[0], a[1], a[2], B.BF16, M, d, a[3], a[4], a[5], a[6])
+        elif kind == "relu2":
+            B.rwkvq_relu2(a[0], B.BF16, M * ffn, a[1])
+        else:
+            B.rwkvq_sigmoid_gate(a[0], a[1], B.BF16, M * d, a[2])
+
+    # every block's output back to unit rms (a per-layer factor on W'_v), as in the token step
+    flow = []
+    for layer in range(n_layers):
+        for kind, a in stages[9 * layer: 9 * layer + 9]:
+            launch(kind, a)
+        torch.cuda.synchronize()
+        out = stages[9 * layer + 8][1][2]
+        scale_weights(pf["keep"][0][8 * layer + 6], 1.0 / max(rms16(out, True), 1e-6))
+        for kind, a in stages[9 * layer + 7: 9 * layer + 9]:
+            launch(kind, a)
+        torch.cuda.synchronize()
+        flow.append(rms16(out, True))
+
     def step():
         for kind, a in stages:
-            if kind == "mix":
-                B.rwkvq_token_shift_mix(a[0], hprev, B.BF16, M, d, a[1], 6)
-            elif kind == "lin":
-                B.rwkvq_linear_dispatch(a, M, B.BF16, B.BF16)
-            elif kind == "wkv":
-                B.rwkvq_wkv(a[0], a[1], a[2], B.BF16, M, d, a[3], a[4], a[5], a[6])
-            elif kind == "relu2":
-                B.rwkvq_relu2(a[0], B.BF16, M * ffn, a[1])
-            else:
-                B.rwkvq_sigmoid_gate(a[0], a[1], B.BF16, M * d, a[2])
+            launch(kind, a)
 
     total, _, _ = time_steps(step, 10, 3)
+    last = stages[-1][1][2].view(torch.bfloat16).float()
+    final_ok = bool(torch.isfinite(last).all()) and float(last.abs().max()) > 0.0
     ms = total / 10
     return {"ms_per_step": ms, "tokens_per_s": M * 1e3 / ms, "value": pf["flops"] / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
-            "calls_per_step": len(stages),
+            "calls_per_step": len(stages), "block_output_rms_min_max": [min(flow), max(flow)], "final_output_finite": final_ok,
             "note": "the same matrices in data-flow order, 9 calls per layer: token-shift mix passes, matrix-core GEMMs, "
                     "time-parallel wkv with its gate, squared ReLU, output gate; value counts the GEMM FLOP only"}
 
@@ -417,6 +497,7 @@ def main():
         out["decode_batched"] = batched_decode(dec)
     # ---------------- the same matrices in data-flow order, one HIP graph per token step
     if not args.skip_sequential:
+        unit_gain(dec, 1)
         out["sequential_step"] = sequential_step(dec, args.layers)
     del dec, run
     torch.cuda.empty_cache()
@@ -444,6 +525,7 @@ def main():
                                    # (profiles/prefill_and_mix_hbm_traffic.txt)
                                    "traffic": 8.87e9 if args.layers == 32 else None}
         if not args.skip_sequential:
+            unit_gain(pf, 2048, bf16=True)
             out["prefill"]["block"] = prefill_block_step(pf, args.layers, 2048)
         del pf, runp
         torch.cuda.empty_cache()
