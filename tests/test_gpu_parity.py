@@ -345,3 +345,42 @@ def test_small_batch_rows_not_multiple_of_256(M):
             assert G.err_g2(got, exact) <= 2e-5, i          # streaming passes: exact weights
         elif G.err_g2(got, exact) > 2e-5:                   # the dispatcher chose the matrix cores for this one
             G.check_outputs(got, m, x, "bf16", fed="bf16")
+
+
+def test_dispatch_randomized_batches_and_paths(monkeypatch):
+    """Seeded sweep over batch sizes 1..300, call compositions and the small-batch override: every
+    output against the oracle with the weights as the reported path feeds them (rwkvq_linear_dispatch_plan:
+    exact for the streaming kernels and the reference kernel, rounded to the type of x on the matrix
+    cores).  Catches row-block offsets, ragged last passes (M = 33: 32 rows + 1) and mixed calls."""
+    torch = G.torch_()
+    rng = np.random.default_rng(4242)
+    shapes = [(256, 512), (512, 256), (256, 1024), (768, 768), (48, 512), (1024, 256)]
+    for case in range(36):
+        M = int(rng.choice([1, 2, 5, 16, 17, 31, 32, 33, 47, 64, 65, 96, 100, 128, 129, 200, 300]))
+        xdt = ("f16", "bf16")[case % 2]
+        n = int(rng.integers(1, 4))
+        mats = []
+        for j in range(n):
+            N, K = shapes[int(rng.integers(0, len(shapes)))]
+            fmt = ("sq", "vq6", "vq8")[int(rng.integers(0, 3))]
+            if fmt != "sq" and N % 256:
+                N = 256
+            mats.append(make(fmt, N, K, 100 + 7 * case + j))
+        override = (None, "stream", "mfma")[int(rng.integers(0, 3))]
+        if override:
+            monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", override)
+        else:
+            monkeypatch.delenv("RWKVQ_SMALL_BATCH_PATH", raising=False)
+        dms = [B.upload(m, native=True) for m in mats]
+        descs = [d.desc() for d in dms]
+        xs = [acts(M, m.K, xdt, 1000 + case * 10 + j) for j, m in enumerate(mats)]
+        ys = [torch.full((M, m.N), 7.0, dtype=torch.float32, device="cuda") for m in mats]
+        paths = B.rwkvq_linear_dispatch_plan(descs, M)
+        print(f"randomized case {case}: M={M} x={xdt} override={override} "
+              f"mats={[(m.kind, m.N, m.K) for m in mats]} paths={paths}", flush=True)
+        B.rwkvq_linear_dispatch(B.DispatchTable(descs, [G.to_dev_bits(x) for x in xs], ys), M, B.DTYPES[xdt], B.F32)
+        torch.cuda.synchronize()
+        for m, x, y, p in zip(mats, xs, ys, paths):
+            fed = xdt if p == B.PATH_MATRIX_CORES else None
+            ref = orc.linear(m, orc.widen(x, xdt), "f64", weight_round=fed)
+            assert G.err_g2(y.cpu().numpy().astype(np.float64), ref) <= 2e-5, (case, m.kind, m.N, m.K, p)
