@@ -306,14 +306,30 @@ int rwkvq_sigmoid_gate(const void* r, const void* y, int x_dtype, long long n, v
  *   rwkvq_relu2 / rwkvq_sigmoid_gate stores, without the launch and the pass in between.
  *   mixes == NULL: xs[i] is the input of matrix i ([K_i] of x_dtype).  mixes != NULL: mixes[i]
  *   describes it (x, x_prev and the quantized mix weight), xs is not read and may be NULL.
+ *   n_mix > 0: besides z = op(y) in ys[i], the call stores, for p < n_mix,
+ *   mix[p].out[n] = mu_p[n] z[n] + (1 - mu_p[n]) x_prev[n], mu_p[n] = codebook_p[indices_p[n / 2]][n % 2]:
+ *   the token-shift mixes of Eq. "time mixing r/k/v" / "channel mixing r/k" that the NEXT stage's
+ *   projections read, taken where the vector is produced (the mix is element-wise) instead of by every
+ *   workgroup of the stage that consumes it; arithmetic and bits as rwkvq_token_shift_mix on the stored
+ *   z.  Needs mixes == NULL (plain inputs) and a 16-bit y_dtype, else RWKVQ_ERR_UNSUPPORTED; x_prev and
+ *   the mix outputs must not alias ys[i].
  *   mats: native layout, K <= 20480; posts, mats, xs, ys, mixes: HOST arrays, read before return.
  *   Errors as rwkvq_linear_dispatch_mixed; RWKVQ_ERR_UNSUPPORTED also for an unknown op,
  *   RWKVQ_ERR_NULL for a missing gate. */
 enum { RWKVQ_POST_NONE = 0, RWKVQ_POST_RELU2 = 1, RWKVQ_POST_SIGMOID_GATE = 2 };
+typedef struct rwkvq_post_mix {  /* one token-shift mix of the stage that follows */
+    const uint8_t* indices;  /* DEVICE: [N / 2] indices of the mix weight's 2-vectors */
+    const void* codebook;    /* DEVICE: 2^kbits x 2 fp16 entries */
+    void* out;               /* DEVICE: [N] values of y_dtype */
+    int32_t kbits;           /* 6 or 8 */
+    int32_t reserved;
+} rwkvq_post_mix;
 typedef struct rwkvq_post_op {
     int32_t op;         /* RWKVQ_POST_* */
-    int32_t reserved;
+    int32_t n_mix;      /* 0..4: the stored output z (after `op`) also leaves as n_mix token-shift mixes */
     const void* gate;   /* DEVICE, RWKVQ_POST_SIGMOID_GATE only */
+    const void* x_prev; /* DEVICE, n_mix > 0: [N] values of y_dtype, the previous token's z */
+    rwkvq_post_mix mix[4];
 } rwkvq_post_op;
 int rwkvq_linear_dispatch_post(const rwkvq_matrix* mats, const void* const* xs, const rwkvq_mix_input* mixes,
                                const rwkvq_post_op* posts, void* const* ys, int n_mats, int x_dtype, int y_dtype,

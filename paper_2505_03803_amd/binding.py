@@ -30,8 +30,12 @@ class rwkvq_mix_input(Structure):
                 ("kbits", c_int32), ("reserved", c_int32)]
 
 
+class rwkvq_post_mix(Structure):
+    _fields_ = [("indices", c_void_p), ("codebook", c_void_p), ("out", c_void_p), ("kbits", c_int32), ("reserved", c_int32)]
+
+
 class rwkvq_post_op(Structure):
-    _fields_ = [("op", c_int32), ("reserved", c_int32), ("gate", c_void_p)]
+    _fields_ = [("op", c_int32), ("n_mix", c_int32), ("gate", c_void_p), ("x_prev", c_void_p), ("mix", rwkvq_post_mix * 4)]
 
 
 POST_NONE, POST_RELU2, POST_SIGMOID_GATE = 0, 1, 2
@@ -438,9 +442,21 @@ def rwkvq_sigmoid_gate(r, y, x_dtype, n, out, stream=None, check=True):
     return _check(st) if check else st
 
 
+def _post_op(p) -> rwkvq_post_op:
+    """(op, gate) or (op, gate, x_prev, [(indices, codebook, kbits, out), ...]) -> rwkvq_post_op."""
+    o = rwkvq_post_op()
+    o.op, o.gate = int(p[0]), _ptr(p[1])
+    if len(p) > 2 and p[3]:
+        o.x_prev, o.n_mix = _ptr(p[2]), len(p[3])
+        for q, (ix, cb, kb, out) in enumerate(p[3]):
+            o.mix[q] = rwkvq_post_mix(_ptr(ix), _ptr(cb), _ptr(out), int(kb), 0)
+    return o
+
+
 class PostDispatchTable:
     """Host arrays for rwkvq_linear_dispatch_post: descriptors, inputs (xs: device tensors, or mixes:
-    (x, x_prev, indices, codebook, kbits) per matrix), posts: (op, gate tensor or None) per matrix."""
+    (x, x_prev, indices, codebook, kbits) per matrix), posts: (op, gate tensor or None) per matrix, or
+    (op, gate, x_prev, [(indices, codebook, kbits, out), ...]) to have the output also stored as mixes."""
 
     def __init__(self, descs: Sequence, xs: Optional[Sequence], mixes: Optional[Sequence], posts: Sequence, ys: Sequence):
         n = len(descs)
@@ -450,7 +466,7 @@ class PostDispatchTable:
         self.xs = _ptr_array(xs) if xs is not None else None
         self.mixes = None if mixes is None else (rwkvq_mix_input * n)(
             *[rwkvq_mix_input(_ptr(x), _ptr(xp), _ptr(ix), _ptr(cb), int(kb), 0) for x, xp, ix, cb, kb in mixes])
-        self.posts = (rwkvq_post_op * n)(*[rwkvq_post_op(int(op), 0, _ptr(g)) for op, g in posts])
+        self.posts = (rwkvq_post_op * n)(*[_post_op(p) for p in posts])
         self.ys = _ptr_array(ys)
         self.keep = (xs, mixes, posts, ys)
 

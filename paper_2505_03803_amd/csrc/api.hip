@@ -391,6 +391,8 @@ int rwkvq_linear_dispatch_post(const rwkvq_matrix* mats, const void* const* xs, 
     std::vector<MatDev> md((size_t)n_mats);
     std::vector<MixDev> xd((size_t)n_mats);
     std::vector<PostDev> pd((size_t)n_mats);
+    std::vector<PostMixDev> pmd((size_t)n_mats);
+    bool any_mix = false;
     for (int i = 0; i < n_mats; ++i) {
         const void* x = mixes ? mixes[i].x : xs[i];
         if (!x || !ys[i]) return RWKVQ_ERR_NULL;
@@ -409,11 +411,30 @@ int rwkvq_linear_dispatch_post(const rwkvq_matrix* mats, const void* const* xs, 
             if (!aligned16(p.gate)) return RWKVQ_ERR_ALIGN;
         }
         pd[(size_t)i] = PostDev{p.op, p.op == RWKVQ_POST_SIGMOID_GATE ? p.gate : nullptr};
+        if (p.n_mix < 0 || p.n_mix > 4) return RWKVQ_ERR_UNSUPPORTED;
+        PostMixDev& pm = pmd[(size_t)i];
+        pm = PostMixDev{};
+        pm.n_mix = p.n_mix;
+        if (p.n_mix > 0) {
+            any_mix = true;
+            if (mixes || (y_dtype != RWKVQ_F16 && y_dtype != RWKVQ_BF16)) return RWKVQ_ERR_UNSUPPORTED;
+            if (!p.x_prev) return RWKVQ_ERR_NULL;
+            if (!aligned16(p.x_prev)) return RWKVQ_ERR_ALIGN;
+            pm.x_prev = p.x_prev;
+            for (int q = 0; q < p.n_mix; ++q) {
+                const rwkvq_post_mix& m = p.mix[q];
+                if (!m.indices || !m.codebook || !m.out) return RWKVQ_ERR_NULL;
+                if (m.kbits != 6 && m.kbits != 8) return RWKVQ_ERR_UNSUPPORTED;
+                if (!aligned16(m.indices) || !aligned16(m.codebook) || !aligned16(m.out)) return RWKVQ_ERR_ALIGN;
+                pm.idx[q] = m.indices; pm.cb[q] = (const uint16_t*)m.codebook; pm.out[q] = m.out;
+            }
+        }
         if ((st = to_dev(mats[i], x, ys[i], &md[(size_t)i])) != RWKVQ_OK) return st;
         if (md[(size_t)i].layout != RWKVQ_NATIVE || md[(size_t)i].K > kDecodeMaxK) return RWKVQ_ERR_UNSUPPORTED;
     }
-    hipError_t e = mixes ? launch_decode_mixed(md.data(), xd.data(), n_mats, x_dtype, y_dtype, (hipStream_t)stream, pd.data())
-                         : launch_decode(md.data(), n_mats, 1, x_dtype, y_dtype, (hipStream_t)stream, pd.data());
+    hipError_t e = mixes     ? launch_decode_mixed(md.data(), xd.data(), n_mats, x_dtype, y_dtype, (hipStream_t)stream, pd.data())
+                   : any_mix ? launch_decode_postmix(md.data(), pd.data(), pmd.data(), n_mats, x_dtype, y_dtype, (hipStream_t)stream)
+                             : launch_decode(md.data(), n_mats, 1, x_dtype, y_dtype, (hipStream_t)stream, pd.data());
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 

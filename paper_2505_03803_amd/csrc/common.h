@@ -141,6 +141,10 @@ struct MixDev { const void* x_prev; const uint8_t* idx; const uint16_t* cb; int 
 // Element-wise operator on a batch-1 projection's output (values as in rwkvq.h's RWKVQ_POST_*).
 enum PostOp : int { POST_NONE = 0, POST_RELU2 = 1, POST_SIGMOID_GATE = 2 };
 struct PostDev { int op; const void* gate; };
+// The output of a batch-1 projection also written as up to four token-shift mixes (next stage's inputs).
+struct PostMixDev { const void* x_prev; int n_mix; const uint8_t* idx[4]; const uint16_t* cb[4]; void* out[4]; };
+hipError_t launch_decode_postmix(const MatDev* mats, const PostDev* posts, const PostMixDev* pm, int n_mats,
+                                 int x_dtype, int y_dtype, hipStream_t s);
 // posts: nullptr, or one PostDev per matrix (M must be 1 then)
 hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_mats, int x_dtype, int y_dtype,
                                hipStream_t s, const PostDev* posts = nullptr);

@@ -81,15 +81,33 @@ struct MixedMat : DecodeMat {
     int mix_E, pad2;
 };
 constexpr int kMaxMixedMats = 64;
+// A matrix whose output also leaves as the token-shift mixes of the stage that follows (up to four
+// projections): out_p[n] = mu_p[n] y[n] + (1 - mu_p[n]) xprev[n].
+struct PostMix { const uint8_t* idx; const uint32_t* cb; void* out; };
+struct PostMixMat : DecodeMat {
+    const void* xprev;                // the previous token's y, type of y
+    PostMix mix[4];
+    int n_mix, pad2;
+};
+struct PostMixArgs {
+    static constexpr bool kMixed = false;
+    static constexpr bool kPostMix = true;
+    static constexpr int kMats = kMaxMixedMats;
+    int wg_end[kMaxMixedMats];
+    PostMixMat m[kMaxMixedMats];
+    int M, xdt, ydt, pad;
+};
 struct MixedDecodeArgs {
     static constexpr bool kMixed = true;
+    static constexpr bool kPostMix = false;
     static constexpr int kMats = kMaxMixedMats;
     int wg_end[kMaxMixedMats];
     MixedMat m[kMaxMixedMats];
     int M, xdt, ydt, pad;
 };
-struct DecodeArgs {                   // 13 KB of kernel arguments
+struct DecodeArgs {                   // 15 KB of kernel arguments
     static constexpr bool kMixed = false;
+    static constexpr bool kPostMix = false;
     static constexpr int kMats = kMaxGroupMats;
     int wg_end[kMaxGroupMats];        // first workgroup index after matrix i (INT_MAX when unused)
     DecodeMat m[kMaxGroupMats];
@@ -101,7 +119,7 @@ struct DecodeArgs {                   // 13 KB of kernel arguments
 // have read it from memory, then max(y, 0)^2 (Eq. "channel mixing o", input of W'_v) or
 // sigma(gate) * y (the gates of Eq. "time mixing o" / "channel mixing o") in binary32, then rounded
 // for the store: the same bits as the projection followed by rwkvq_relu2 / rwkvq_sigmoid_gate.
-__device__ __forceinline__ void store_post(const DecodeMat& mt, size_t i, int ydt, float v) {
+__device__ __forceinline__ float store_post(const DecodeMat& mt, size_t i, int ydt, float v) {
     if (mt.post != POST_NONE) {
         if (ydt == DT_F16) v = f16_bits_to_f32(f32_to_f16_bits(v));
         else if (ydt == DT_BF16) v = bf16_bits_to_f32(f32_to_bf16_bits(v));
@@ -113,6 +131,25 @@ __device__ __forceinline__ void store_post(const DecodeMat& mt, size_t i, int yd
         }
     }
     store_from_f32(mt.y, i, ydt, v);
+    return v;
+}
+
+// The same, and the stored value again as the token-shift mixes of the stage that follows (Eq. "time
+// mixing r/k/v", "channel mixing r/k"): the mix is element-wise, so it can be taken where the vector is
+// produced, once, instead of by every workgroup of the stage that consumes it.  Arithmetic as the mix
+// pass and the fused mix: the stored (rounded) y, binary32, one rounding per operation, rounded to the type.
+__device__ __forceinline__ void store_post_mix(const PostMixMat& mt, size_t i, int ydt, float v) {
+    v = store_post(mt, i, ydt, v);
+    if (mt.n_mix > 0) {
+        const float xt = ydt == DT_F16 ? f16_bits_to_f32(f32_to_f16_bits(v)) : bf16_bits_to_f32(f32_to_bf16_bits(v));
+        const float xp = load_as_f32(mt.xprev, i, ydt);
+        for (int p = 0; p < mt.n_mix; ++p) {
+            const uint32_t e = mt.mix[p].cb[mt.mix[p].idx[i >> 1]];
+            const float m = f16_bits_to_f32((uint16_t)((i & 1) ? e >> 16 : e & 0xFFFFu));
+            const float o = __fadd_rn(__fmul_rn(m, xt), __fmul_rn(__fsub_rn(1.0f, m), xp));
+            store_from_f32(mt.mix[p].out, i, ydt, o);
+        }
+    }
 }
 
 template <int P>
@@ -912,7 +949,8 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
         float t = red[0][lane];
 #pragma unroll
         for (int s = 1; s < S; ++s) t += red[s][lane];
-        store_post(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+        if constexpr (Args::kPostMix) store_post_mix(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+        else store_post(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
     }
 }
 
@@ -952,6 +990,40 @@ hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_ma
                 a.m[i] = MixedMat{};
                 a.wg_end[i] = 0x7FFFFFFF;
             }
+        }
+        a.M = 1; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
+        hipError_t e = launch_splitk(pick_split(tiles), wgs, a, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Batch 1 with the outputs also leaving as the mixes of the next stage: the split-K kernel (these are
+// single projections of a block).
+hipError_t launch_decode_postmix(const MatDev* mats, const PostDev* posts, const PostMixDev* pm, int n_mats,
+                                 int x_dtype, int y_dtype, hipStream_t s) {
+    for (int base = 0; base < n_mats; base += kMaxMixedMats) {
+        PostMixArgs a;
+        const int cnt = n_mats - base < kMaxMixedMats ? n_mats - base : kMaxMixedMats;
+        int tiles = 0;
+        for (int i = 0; i < cnt; ++i) tiles += (mats[base + i].N + 15) / 16;
+        int wgs = 0;
+        for (int i = 0; i < kMaxMixedMats; ++i) {
+            PostMixMat mm{};
+            if (i < cnt) {
+                const MatDev& m = mats[base + i];
+                const PostMixDev& x = pm[base + i];
+                wgs += (m.N + 15) / 16;
+                mm.codes = m.codes; mm.aux = m.aux; mm.x = m.x; mm.y = m.y; mm.N = m.N; mm.K = m.K; mm.fmt = m.fmt;
+                mm.post = posts[base + i].op; mm.gate = posts[base + i].gate;
+                mm.xprev = x.x_prev; mm.n_mix = x.n_mix; mm.pad2 = 0;
+                for (int p = 0; p < 4; ++p)
+                    mm.mix[p] = p < x.n_mix ? PostMix{x.idx[p], (const uint32_t*)x.cb[p], x.out[p]} : PostMix{nullptr, nullptr, nullptr};
+                a.wg_end[i] = wgs;
+            } else {
+                a.wg_end[i] = 0x7FFFFFFF;
+            }
+            a.m[i] = mm;
         }
         a.M = 1; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
         hipError_t e = launch_splitk(pick_split(tiles), wgs, a, s);

@@ -239,11 +239,11 @@ def test_dispatch_post_rejects():
                                          kw.get("kbits", 6), 0)
 
     def call(mat=good, x=FAKE, m=None, op=B.POST_RELU2, gate=None, y=FAKE, n=1, xdt=B.F16, ydt=B.F16, no_x=False,
-             no_posts=False):
+             no_posts=False, pm=None):
         mats = (B.rwkvq_matrix * 1)(mat)
         xs = None if no_x else (c_void_p * 1)(x)
         mixes = None if m is None else (B.rwkvq_mix_input * 1)(m)
-        posts = None if no_posts else (B.rwkvq_post_op * 1)(B.rwkvq_post_op(op, 0, gate))
+        posts = None if no_posts else (B.rwkvq_post_op * 1)(B._post_op((op, gate) if pm is None else (op, gate, pm[0], pm[1])))
         ys = (c_void_p * 1)(y)
         return L.rwkvq_linear_dispatch_post(mats, xs, mixes, posts, ys, n, xdt, ydt, None)
 
@@ -255,3 +255,9 @@ def test_dispatch_post_rejects():
     assert call(n=0) == B.ERR_SHAPE
     assert call(op=B.POST_SIGMOID_GATE, gate=FAKE + 2) == B.ERR_ALIGN and call(x=FAKE + 8) == B.ERR_ALIGN
     assert call(m=mix(idx=FAKE + 1)) == B.ERR_ALIGN
+    one = [(FAKE, FAKE, 6, FAKE)]
+    assert call(pm=(None, one)) == B.ERR_NULL and call(pm=(FAKE, [(None, FAKE, 6, FAKE)])) == B.ERR_NULL
+    assert call(pm=(FAKE, [(FAKE, FAKE, 6, None)])) == B.ERR_NULL
+    assert call(pm=(FAKE, [(FAKE, FAKE, 7, FAKE)])) == B.ERR_UNSUPPORTED
+    assert call(pm=(FAKE, one), ydt=B.F32) == B.ERR_UNSUPPORTED and call(pm=(FAKE, one), m=mix()) == B.ERR_UNSUPPORTED
+    assert call(pm=(FAKE + 2, one)) == B.ERR_ALIGN and call(pm=(FAKE, [(FAKE, FAKE, 6, FAKE + 4)])) == B.ERR_ALIGN

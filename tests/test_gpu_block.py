@@ -454,3 +454,40 @@ def test_block_chunk_through_quantized_projections():
         want_out = BO.channel_mixing_gate(W(y1["cr"]), narrow(y_cv))
         assert rel(W(out1), want_out) <= 1e-2
         o_prev = y1["o"]
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("N,K,P,op", [(4096, 512, 4, "gate"), (512, 3584, 2, "none"), (256, 256, 1, "relu2"), (8192, 256, 3, "gate")])
+def test_post_mix_equals_projection_then_mix_pass(dt, N, K, P, op):
+    """The output of a batch-1 projection also stored as the token-shift mixes of the next stage
+    (rwkvq_post_op.n_mix) against the same call without them followed by rwkvq_token_shift_mix on the
+    stored output: the same bits in the output and in every mix, for all three operators in front."""
+    torch = G.torch_()
+    rng = np.random.default_rng(9800 + N + K)
+    mat = synth.gen_vq(rng, N, K, 6) if (N // 256) % 2 else synth.gen_sq(rng, N, K)
+    dm = B.upload(mat, native=True)
+    x = dev(synth.gen_activations(rng, 1, K, dt))
+    gate = dev(synth.gen_activations(rng, 1, N, dt)[0])
+    zprev = dev(synth.gen_activations(rng, 1, N, dt)[0])
+    idx = [dev(rng.integers(0, 64, size=N // 2, dtype=np.uint8)) for _ in range(P)]
+    cbs = [dev(synth.gen_codebook(rng, 64).reshape(64, 2)) for _ in range(P)]
+    opc = {"none": B.POST_NONE, "relu2": B.POST_RELU2, "gate": B.POST_SIGMOID_GATE}[op]
+    g = gate if op == "gate" else None
+    buf = lambda: torch.zeros((1, N), dtype=torch.int16, device="cuda")
+    z_ref, mix_ref = buf(), [buf() for _ in range(P)]
+    B.rwkvq_linear_dispatch_post(B.PostDispatchTable([dm.desc()], [x], None, [(opc, g)], [z_ref]), B.DTYPES[dt], B.DTYPES[dt])
+    B.rwkvq_token_shift_mix(z_ref, zprev, B.DTYPES[dt], 1, N, B.MixTable(idx, cbs, mix_ref), 6)
+    z, mix = buf(), [buf() for _ in range(P)]
+    print(f"post-mix {dt} N={N} K={K} P={P} op={op}", flush=True)
+    B.rwkvq_linear_dispatch_post(B.PostDispatchTable([dm.desc()], [x], None,
+                                 [(opc, g, zprev, [(idx[p], cbs[p], 6, mix[p]) for p in range(P)])], [z]), B.DTYPES[dt], B.DTYPES[dt])
+    torch.cuda.synchronize()
+    assert torch.equal(z, z_ref)
+    for p in range(P):
+        assert torch.equal(mix[p], mix_ref[p]), p
+    # and the mix itself against the oracle on the stored output
+    zf, zp = orc.widen(z.cpu().numpy().view(np.uint16).reshape(-1), dt), orc.widen(zprev.cpu().numpy().view(np.uint16), dt)
+    for p in range(P):
+        mu_hat = orc.widen(cbs[p].cpu().numpy().view(np.uint16), "f16").reshape(64, 2)[idx[p].cpu().numpy()].reshape(-1)
+        want = MO.narrow(MO.token_shift_mix(zf[None, :], zp, mu_hat), dt)
+        assert np.array_equal(mix[p].cpu().numpy().view(np.uint16), want), p
