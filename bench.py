@@ -257,6 +257,42 @@ def sequential_step(dec, n_layers):
             else:
                 B.rwkvq_linear_dispatch_post(a, B.F16, B.F16)
 
+    # the same block once more with every token-shift mix taken where its input vector is produced
+    # (rwkvq_post_op.n_mix): W_o stores o and the two mixes of channel mixing, W'_v stores the block's
+    # output and the four mixes of the next block; the projections then read plain vectors.  One mix
+    # pass in front of the first block.  5 launches per layer + 1.
+    blockpm = []
+    mixbuf = lambda n: [torch.zeros((1, d), dtype=torch.int16, device="cuda") for _ in range(n)]
+    in4 = [mixbuf(4) for _ in range(n_layers + 1)]
+    m4_0 = stages[0][1]
+    blockpm.append(("mix", (h, B.MixTable(m4_0.keep[0], m4_0.keep[1], in4[0]))))
+    for layer in range(n_layers):
+        D = dec["descs"][8 * layer: 8 * layer + 8]
+        Y = dec["ys"][8 * layer: 8 * layer + 8]
+        b7 = block[7 * layer: 7 * layer + 7]
+        m2 = stages[6 * layer + 3][1]
+        m4n = stages[6 * ((layer + 1) % n_layers)][1]         # the next block's four mix weights
+        gated, sq, outb = b7[1][1][6], b7[4][1][1], b7[6][1][2]
+        in2 = mixbuf(2)
+        blockpm.append(("lin", B.DispatchTable(D[0:4], in4[layer], Y[0:4])))
+        blockpm.append(b7[1])
+        blockpm.append(("post", B.PostDispatchTable([D[4]], [gated], None,
+                        [(B.POST_NONE, None, hprev, [(m2.keep[0][p], m2.keep[1][p], 6, in2[p]) for p in range(2)])], [Y[4]])))
+        blockpm.append(("post", B.PostDispatchTable([D[5], D[7]], in2, None, [(B.POST_RELU2, None), (B.POST_NONE, None)], [sq, Y[7]])))
+        blockpm.append(("post", B.PostDispatchTable([D[6]], [sq], None,
+                        [(B.POST_SIGMOID_GATE, Y[7], hprev, [(m4n.keep[0][p], m4n.keep[1][p], 6, in4[layer + 1][p]) for p in range(4)])], [outb])))
+
+    def step_blockpm():
+        for kind, a in blockpm:
+            if kind == "mix":
+                B.rwkvq_token_shift_mix(a[0], hprev, B.F16, 1, d, a[1], 6)
+            elif kind == "lin":
+                B.rwkvq_linear_dispatch(a, 1, B.F16, B.F16)
+            elif kind == "wkv":
+                B.rwkvq_wkv(a[0], a[1], a[2], B.F16, 1, d, a[3], a[4], a[5], a[6])
+            else:
+                B.rwkvq_linear_dispatch_post(a, B.F16, B.F16)
+
     def timed(fn):
         fn()
         torch.cuda.synchronize()
@@ -270,18 +306,33 @@ def sequential_step(dec, n_layers):
     ms_fused = timed(step_fused)
     ms_block7 = timed(step_block)
     ms_block = timed(step_block5)
+    ms_blockpm = timed(step_blockpm)
+
+    def one_step_from_empty_state(fn):
+        for layer in range(n_layers):
+            st = block[7 * layer + 1][1][5]
+            st[:2].zero_(); st[2].fill_(-1e38)
+        fn()
+        torch.cuda.synchronize()
+        return block[-1][1][2].clone()
+    same_bits = bool(torch.equal(one_step_from_empty_state(step_block5), one_step_from_empty_state(step_blockpm)))
     last = block[-1][1][2].view(torch.float16).float()
     final_ok = bool(torch.isfinite(last).all()) and float(last.abs().max()) > 0.0
     eager_ms = time_steps(step, 200, 50)[0] / 200
     return {"ms_per_step": ms_fused, "tokens_per_s": 1e3 / ms_fused, "value": dec["wbytes"] / (ms_fused * 1e-3) / 1e9,
             "unit": "GB/s", "launches_per_step": len(fused),
             "unfused": {"ms_per_step": ms, "launches_per_step": len(stages), "eager_ms_per_step": eager_ms},
-            "block": {"ms_per_step": ms_block, "tokens_per_s": 1e3 / ms_block, "launches_per_step": len(block5),
+            "block": {"ms_per_step": ms_blockpm, "tokens_per_s": 1e3 / ms_blockpm, "launches_per_step": len(blockpm),
                       "block_output_rms_min_max": [min(flow), max(flow)], "final_output_finite": final_ok,
+                      "mixes_in_the_consumers": {"ms_per_step": ms_block, "launches_per_step": len(block5),
+                                                 "same_output_bits": same_bits},
                       "separate_operators": {"ms_per_step": ms_block7, "launches_per_step": len(block)},
                       "note": "with the element-wise operators of the block: wkv recurrence and its gate as one "
-                              "launch, squared ReLU and output gate applied by the GEMVs that produce their operands "
-                              "(5 launches per layer); separate_operators = each operator a launch of its own (7)"},
+                              "launch, squared ReLU and output gate applied by the GEMVs that produce their operands, "
+                              "every token-shift mix taken by the GEMV that produces its input vector (5 launches per "
+                              "layer + one mix pass in front); mixes_in_the_consumers = the mixes fused into the "
+                              "activation loads of the GEMVs that read them instead (5 per layer); separate_operators "
+                              "= that, with each operator a launch of its own (7)"},
             "note": "same 256 matrices, data-flow order, 4 launches per layer (token-shift mixes fused into the "
                     "GEMVs) in one HIP graph; unfused = 6 launches per layer with separate mix passes; "
                     "block = the fused step plus the element-wise operators between the stages"}

@@ -20,7 +20,9 @@
 //   * decode_splitk_kernel<S>: batch 1 for launches too small to fill the device (the stages of a
 //     block): one workgroup of S wavefronts per row tile, the column tiles dealt round-robin, the
 //     partial sums added in LDS in a fixed order.  With MixedDecodeArgs the token-shift mix of
-//     Eq. "time mixing r/k/v" is applied while the activations are loaded.
+//     Eq. "time mixing r/k/v" is applied while the activations are loaded; with PostMixArgs the
+//     outputs also leave as the mixes of the stage that follows (store_post_mix).  The squared ReLU
+//     and the gates of App. A.1 can be applied where an output is stored (store_post).
 //   * Batch 2..32 (MT = 4, 16, 32) on the matrix cores (v_mfma_f32_16x16x32_f16, activations = A
 //     operand, weights = B operand): the activation tile of a column tile is fetched once per
 //     workgroup into LDS (two buffers, one barrier per tile); SQ codes enter as 8 + q (one shift
@@ -138,16 +140,29 @@ __device__ __forceinline__ float store_post(const DecodeMat& mt, size_t i, int y
 // mixing r/k/v", "channel mixing r/k"): the mix is element-wise, so it can be taken where the vector is
 // produced, once, instead of by every workgroup of the stage that consumes it.  Arithmetic as the mix
 // pass and the fused mix: the stored (rounded) y, binary32, one rounding per operation, rounded to the type.
-__device__ __forceinline__ void store_post_mix(const PostMixMat& mt, size_t i, int ydt, float v) {
+// The previous token's value and the indices are fetched by post_mix_prefetch at the start of the kernel
+// (their latency hides behind the GEMV); the codebook entries, which depend on the indices, here, in one
+// batch of loads.
+struct PostMixPre { float xp; uint32_t ix[4]; };
+__device__ __forceinline__ void post_mix_prefetch(PostMixPre& pre, const PostMixMat& mt, size_t i, int ydt) {
+    pre.xp = load_as_f32(mt.xprev, i, ydt);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) pre.ix[p] = p < mt.n_mix ? mt.mix[p].idx[i >> 1] : 0u;   // static indices: mt stays in registers
+}
+__device__ __forceinline__ void store_post_mix(const PostMixMat& mt, size_t i, int ydt, float v, const PostMixPre& pre) {
     v = store_post(mt, i, ydt, v);
     if (mt.n_mix > 0) {
         const float xt = ydt == DT_F16 ? f16_bits_to_f32(f32_to_f16_bits(v)) : bf16_bits_to_f32(f32_to_bf16_bits(v));
-        const float xp = load_as_f32(mt.xprev, i, ydt);
-        for (int p = 0; p < mt.n_mix; ++p) {
-            const uint32_t e = mt.mix[p].cb[mt.mix[p].idx[i >> 1]];
-            const float m = f16_bits_to_f32((uint16_t)((i & 1) ? e >> 16 : e & 0xFFFFu));
-            const float o = __fadd_rn(__fmul_rn(m, xt), __fmul_rn(__fsub_rn(1.0f, m), xp));
-            store_from_f32(mt.mix[p].out, i, ydt, o);
+        uint32_t e[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) e[p] = p < mt.n_mix ? mt.mix[p].cb[pre.ix[p]] : 0u;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (p < mt.n_mix) {
+                const float m = f16_bits_to_f32((uint16_t)((i & 1) ? e[p] >> 16 : e[p] & 0xFFFFu));
+                const float o = __fadd_rn(__fmul_rn(m, xt), __fmul_rn(__fsub_rn(1.0f, m), pre.xp));
+                store_from_f32(mt.mix[p].out, i, ydt, o);
+            }
         }
     }
 }
@@ -934,6 +949,10 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
         wave_lds_sync();
         wp.xprev = mt.xprev; wp.mix_idx = mt.mix_idx; wp.mix_cb = cb_mix[wave];
     }
+    PostMixPre pre{};
+    if constexpr (Args::kPostMix) {
+        if (wave == 0 && lane < 16 && mt.n_mix > 0) post_mix_prefetch(pre, mt, (size_t)16 * wp.R[0] + lane, a.ydt);
+    }
     float part[kRT] = {0.f};
     if (wp.nt > 0) {
         if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true, MIXED>(mt, wp, part);
@@ -949,7 +968,7 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
         float t = red[0][lane];
 #pragma unroll
         for (int s = 1; s < S; ++s) t += red[s][lane];
-        if constexpr (Args::kPostMix) store_post_mix(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+        if constexpr (Args::kPostMix) store_post_mix(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t, pre);
         else store_post(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
     }
 }
