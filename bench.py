@@ -282,6 +282,32 @@ def sequential_step(dec, n_layers):
         blockpm.append(("post", B.PostDispatchTable([D[6]], [sq], None,
                         [(B.POST_SIGMOID_GATE, Y[7], hprev, [(m4n.keep[0][p], m4n.keep[1][p], 6, in4[layer + 1][p]) for p in range(4)])], [outb])))
 
+    # the bare GEMV chain (no element-wise operators) with the mixes at the producer: 4 launches per layer + 1
+    barepm = [blockpm[0]]
+    in4b = [mixbuf(4) for _ in range(n_layers + 1)]
+    barepm[0] = ("mix", (h, B.MixTable(m4_0.keep[0], m4_0.keep[1], in4b[0])))
+    for layer in range(n_layers):
+        D = dec["descs"][8 * layer: 8 * layer + 8]
+        Y = dec["ys"][8 * layer: 8 * layer + 8]
+        m2 = stages[6 * layer + 3][1]
+        m4n = stages[6 * ((layer + 1) % n_layers)][1]
+        in2 = mixbuf(2)
+        barepm.append(("lin", B.DispatchTable(D[0:4], in4b[layer], Y[0:4])))
+        barepm.append(("post", B.PostDispatchTable([D[4]], [Y[2]], None,
+                       [(B.POST_NONE, None, hprev, [(m2.keep[0][p], m2.keep[1][p], 6, in2[p]) for p in range(2)])], [Y[4]])))
+        barepm.append(("lin", B.DispatchTable([D[5], D[7]], in2, [Y[5], Y[7]])))
+        barepm.append(("post", B.PostDispatchTable([D[6]], [Y[5]], None,
+                       [(B.POST_NONE, None, hprev, [(m4n.keep[0][p], m4n.keep[1][p], 6, in4b[layer + 1][p]) for p in range(4)])], [Y[6]])))
+
+    def step_barepm():
+        for kind, a in barepm:
+            if kind == "mix":
+                B.rwkvq_token_shift_mix(a[0], hprev, B.F16, 1, d, a[1], 6)
+            elif kind == "lin":
+                B.rwkvq_linear_dispatch(a, 1, B.F16, B.F16)
+            else:
+                B.rwkvq_linear_dispatch_post(a, B.F16, B.F16)
+
     def step_blockpm():
         for kind, a in blockpm:
             if kind == "mix":
@@ -304,6 +330,7 @@ def sequential_step(dec, n_layers):
 
     ms = timed(step)
     ms_fused = timed(step_fused)
+    ms_barepm = timed(step_barepm)
     ms_block7 = timed(step_block)
     ms_block = timed(step_block5)
     ms_blockpm = timed(step_blockpm)
@@ -319,8 +346,9 @@ def sequential_step(dec, n_layers):
     last = block[-1][1][2].view(torch.float16).float()
     final_ok = bool(torch.isfinite(last).all()) and float(last.abs().max()) > 0.0
     eager_ms = time_steps(step, 200, 50)[0] / 200
-    return {"ms_per_step": ms_fused, "tokens_per_s": 1e3 / ms_fused, "value": dec["wbytes"] / (ms_fused * 1e-3) / 1e9,
-            "unit": "GB/s", "launches_per_step": len(fused),
+    return {"ms_per_step": ms_barepm, "tokens_per_s": 1e3 / ms_barepm, "value": dec["wbytes"] / (ms_barepm * 1e-3) / 1e9,
+            "unit": "GB/s", "launches_per_step": len(barepm),
+            "mixes_in_the_consumers": {"ms_per_step": ms_fused, "launches_per_step": len(fused)},
             "unfused": {"ms_per_step": ms, "launches_per_step": len(stages), "eager_ms_per_step": eager_ms},
             "block": {"ms_per_step": ms_blockpm, "tokens_per_s": 1e3 / ms_blockpm, "launches_per_step": len(blockpm),
                       "block_output_rms_min_max": [min(flow), max(flow)], "final_output_finite": final_ok,
@@ -333,9 +361,11 @@ def sequential_step(dec, n_layers):
                               "layer + one mix pass in front); mixes_in_the_consumers = the mixes fused into the "
                               "activation loads of the GEMVs that read them instead (5 per layer); separate_operators "
                               "= that, with each operator a launch of its own (7)"},
-            "note": "same 256 matrices, data-flow order, 4 launches per layer (token-shift mixes fused into the "
-                    "GEMVs) in one HIP graph; unfused = 6 launches per layer with separate mix passes; "
-                    "block = the fused step plus the element-wise operators between the stages"}
+            "note": "same 256 matrices, data-flow order, in one HIP graph: 4 launches per layer, every token-shift mix "
+                    "taken by the GEMV that produces its input vector (+ one mix pass in front); "
+                    "mixes_in_the_consumers = the mixes in the activation loads of the GEMVs that read them (4 per "
+                    "layer); unfused = 6 launches per layer with separate mix passes; block = with the element-wise "
+                    "operators of the block between the stages"}
 
 
 def batched_decode(dec):
