@@ -293,6 +293,20 @@ int rwkvq_linear_dispatch_mixed(const rwkvq_matrix* mats, const rwkvq_mix_input*
 int rwkvq_wkv(const void* r, const void* k, const void* v, int x_dtype, int M, int d, const float* w,
               const float* u, float* state, void* out, void* stream);
 int rwkvq_relu2(const void* x, int x_dtype, long long n, void* out, void* stream);
+
+/* rwkvq_rkv_wkv: one token of time mixing in one launch: the three projections r, k, v (rkv[0..2], native
+ *   layout, equal N = d, K <= 20480, any mix of SQ / VQ) of xs[0..2] ([K_i] of x_dtype each), stored in
+ *   ys[0..2] ([d] of y_dtype, fp16 or bf16), and the step of rwkvq_wkv on them: `state` (3 x d floats)
+ *   advanced in place, out[c] = sigma(r[c]) * wkv[c] ([d] of y_dtype).  The recurrence is per channel and
+ *   channel c needs output row c of the three matrices: the workgroup that computes a row tile of all
+ *   three steps its 16 channels.  The columns of a row are split over four wavefronts: the same bits as
+ *   rwkvq_linear_dispatch on the three matrices (one call, M = 1) followed by rwkvq_wkv with M = 1
+ *   when that call splits them the same way (d >= 2736), otherwise equal up to the order of the
+ *   binary32 sums.  rkv, xs, ys: HOST arrays of three entries, read before
+ *   return.  Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_UNSUPPORTED (dtypes, canonical layout, K too long),
+ *   RWKVQ_ERR_SHAPE (different N, or a descriptor's), RWKVQ_ERR_ALIGN, RWKVQ_ERR_DEVICE. */
+int rwkvq_rkv_wkv(const rwkvq_matrix* rkv, const void* const* xs, void* const* ys, const float* w, const float* u,
+                  float* state, void* out, int x_dtype, int y_dtype, void* stream);
 int rwkvq_sigmoid_gate(const void* r, const void* y, int x_dtype, long long n, void* out, void* stream);
 
 /* rwkvq_linear_dispatch_post: batch-1 projections with the element-wise operator that follows them

@@ -22,7 +22,7 @@ EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
            "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
-           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan"]
+           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan", "rwkvq_rkv_wkv"]
 
 
 class rwkvq_mix_input(Structure):
@@ -118,6 +118,9 @@ def lib() -> ctypes.CDLL:
                                                  c_void_p]
         L.rwkvq_linear_dispatch_plan.restype = c_int
         L.rwkvq_linear_dispatch_plan.argtypes = [c_void_p, c_int, c_int, c_void_p]
+        L.rwkvq_rkv_wkv.restype = c_int
+        L.rwkvq_rkv_wkv.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int,
+                                    c_void_p]
         L.rwkvq_wkv.restype = c_int
         L.rwkvq_wkv.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
                                 c_void_p, c_void_p]
@@ -490,3 +493,20 @@ def rwkvq_linear_dispatch_plan(descs: Sequence, M: int, check=True):
         _check(st)
         return list(paths)
     return st
+
+
+class RkvWkvTable:
+    """Host arrays for rwkvq_rkv_wkv: the descriptors of r, k, v, their inputs and outputs."""
+
+    def __init__(self, descs: Sequence, xs: Sequence, ys: Sequence):
+        assert len(descs) == 3 and len(xs) == 3 and len(ys) == 3
+        self.mats = (rwkvq_matrix * 3)(*descs)
+        self.xs = _ptr_array(xs)
+        self.ys = _ptr_array(ys)
+        self.keep = (xs, ys)
+
+
+def rwkvq_rkv_wkv(table: RkvWkvTable, w, u, state, out, x_dtype, y_dtype, stream=None, check=True):
+    st = lib().rwkvq_rkv_wkv(table.mats, table.xs, table.ys, _ptr(w), _ptr(u), _ptr(state), _ptr(out), x_dtype, y_dtype,
+                             _stream(stream))
+    return _check(st) if check else st

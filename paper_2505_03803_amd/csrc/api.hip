@@ -438,6 +438,25 @@ int rwkvq_linear_dispatch_post(const rwkvq_matrix* mats, const void* const* xs, 
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 
+int rwkvq_rkv_wkv(const rwkvq_matrix* rkv, const void* const* xs, void* const* ys, const float* w, const float* u,
+                  float* state, void* out, int x_dtype, int y_dtype, void* stream) {
+    if (!rkv || !xs || !ys || !w || !u || !state || !out) return RWKVQ_ERR_NULL;
+    int st;
+    if ((st = check_dtype_x(x_dtype)) != RWKVQ_OK) return st;
+    if (y_dtype != RWKVQ_F16 && y_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    MatDev md[3];
+    for (int i = 0; i < 3; ++i) {
+        if (!xs[i] || !ys[i]) return RWKVQ_ERR_NULL;
+        if (!aligned16(xs[i]) || !aligned16(ys[i])) return RWKVQ_ERR_ALIGN;
+        if ((st = to_dev(rkv[i], xs[i], ys[i], &md[i])) != RWKVQ_OK) return st;
+        if (md[i].layout != RWKVQ_NATIVE || md[i].K > kDecodeMaxK) return RWKVQ_ERR_UNSUPPORTED;
+        if (md[i].N != md[0].N) return RWKVQ_ERR_SHAPE;
+    }
+    if (!aligned16(out) || ((uintptr_t)w & 3u) || ((uintptr_t)u & 3u) || ((uintptr_t)state & 3u)) return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_decode_rkv_wkv(md, WkvDev{w, u, state, out}, x_dtype, y_dtype, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
+
 int rwkvq_wkv(const void* r, const void* k, const void* v, int x_dtype, int M, int d, const float* w, const float* u,
               float* state, void* out, void* stream) {
     if (!r || !k || !v || !w || !u || !state || !out) return RWKVQ_ERR_NULL;

@@ -48,19 +48,10 @@ __global__ void __launch_bounds__(64) wkv_kernel(const uint16_t* __restrict__ r,
 #pragma unroll
         for (int j = 0; j < kTok; ++j) {
             if (t0 + j < M) {
-                // output of token t: past sums (a, b) exp(p) plus the current token with the bonus u
-                const float ww = uc + kk[j];
-                const float q = fmaxf(p, ww);
-                const float e1 = expf(p - q), e2 = expf(ww - q);
-                const float wkv = (e1 * a + e2 * vv[j]) / (e1 * b + e2);
-                out[(size_t)(t0 + j) * d + c] = st16<BF16>(gate_f32(rr[j], wkv));
-                // advance the sums: decay by exp(-w), add the current token without the bonus
-                const float pw = p - wc;
-                const float q2 = fmaxf(pw, kk[j]);
-                const float f1 = expf(pw - q2), f2 = expf(kk[j] - q2);
-                a = f1 * a + f2 * vv[j];
-                b = f1 * b + f2;
-                p = q2;
+                // output of token t: past sums (a, b) exp(p) plus the current token with the bonus u;
+                // then the sums advanced: decayed by exp(-w), the current token added without the bonus
+                out[(size_t)(t0 + j) * d + c] = st16<BF16>(gate_f32(rr[j], wkv_out(a, b, p, uc, kk[j], vv[j])));
+                wkv_advance(a, b, p, wc, kk[j], vv[j]);
             }
         }
     }
@@ -75,22 +66,6 @@ __global__ void __launch_bounds__(64) wkv_kernel(const uint16_t* __restrict__ r,
 // arithmetic, 64 times the parallelism.  The merges re-associate the sums: the result agrees with the
 // token-by-token kernel to rounding, not bit for bit.
 constexpr int kChunks = 64, kWgChannels = 16;
-
-// one token: output from (a, b, p) and the current (k, v), then the sums advanced
-__device__ __forceinline__ float wkv_out(float a, float b, float p, float uc, float kk, float vv) {
-    const float ww = uc + kk;
-    const float q = fmaxf(p, ww);
-    const float e1 = expf(p - q), e2 = expf(ww - q);
-    return (e1 * a + e2 * vv) / (e1 * b + e2);
-}
-__device__ __forceinline__ void wkv_advance(float& a, float& b, float& p, float wc, float kk, float vv) {
-    const float pw = p - wc;
-    const float q2 = fmaxf(pw, kk);
-    const float f1 = expf(pw - q2), f2 = expf(kk - q2);
-    a = f1 * a + f2 * vv;
-    b = f1 * b + f2;
-    p = q2;
-}
 
 template <bool BF16>
 __global__ void __launch_bounds__(kChunks * kWgChannels) wkv_chunked_kernel(

@@ -70,6 +70,26 @@ __device__ __forceinline__ float gate_f32(float r, float y) {
     return p;
 }
 
+// One token of Eq. "time mixing wkv" carried as a state (a, b, p) per channel: the sums over earlier
+// tokens equal a exp(p) and b exp(p), p the largest exponent so far, so every exp() argument is <= 0.
+// wkv_out: the output for the current (k, v) with the bonus u; wkv_advance: the sums decayed by
+// exp(-w) and the current token added without the bonus.  Shared by every kernel that steps the
+// recurrence, so that they store the same bits.
+__device__ __forceinline__ float wkv_out(float a, float b, float p, float uc, float kk, float vv) {
+    const float ww = uc + kk;
+    const float q = fmaxf(p, ww);
+    const float e1 = expf(p - q), e2 = expf(ww - q);
+    return (e1 * a + e2 * vv) / (e1 * b + e2);
+}
+__device__ __forceinline__ void wkv_advance(float& a, float& b, float& p, float wc, float kk, float vv) {
+    const float pw = p - wc;
+    const float q2 = fmaxf(pw, kk);
+    const float f1 = expf(pw - q2), f2 = expf(kk - q2);
+    a = f1 * a + f2 * vv;
+    b = f1 * b + f2;
+    p = q2;
+}
+
 // The SQ inverse of Sec. 2.2 Eq. "SQ": subtract, round, multiply, round.  The intrinsics keep
 // the compiler from fusing the two steps.
 __device__ __forceinline__ float sq_deq(uint32_t q, float s, float z) {
@@ -145,6 +165,10 @@ struct PostDev { int op; const void* gate; };
 struct PostMixDev { const void* x_prev; int n_mix; const uint8_t* idx[4]; const uint16_t* cb[4]; void* out[4]; };
 hipError_t launch_decode_postmix(const MatDev* mats, const PostDev* posts, const PostMixDev* pm, int n_mats,
                                  int x_dtype, int y_dtype, hipStream_t s);
+// Batch 1: the three projections r, k, v of time mixing (equal N) and, in the same launch, the wkv step
+// with its gate for the 16 channels of every row tile (state updated in place, `out` = sigma(r) wkv).
+struct WkvDev { const float* w; const float* u; float* state; void* out; };
+hipError_t launch_decode_rkv_wkv(const MatDev* rkv, const WkvDev& wkv, int x_dtype, int y_dtype, hipStream_t s);
 // posts: nullptr, or one PostDev per matrix (M must be 1 then)
 hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_mats, int x_dtype, int y_dtype,
                                hipStream_t s, const PostDev* posts = nullptr);

@@ -973,6 +973,78 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     }
 }
 
+// Time mixing's r, k, v and the wkv step in one launch.  The recurrence is per channel, and channel c
+// needs r[c], k[c], v[c]: output row c of three matrices.  A workgroup of 12 wavefronts takes row tile R
+// of all three (four wavefronts per matrix, the column tiles dealt as in the split-K kernel with S = 4,
+// the same order of summation), and the 16 lanes that hold the tile's sums step the recurrence for
+// channels 16 R .. 16 R + 15 and store sigma(r) wkv, the vector W_o multiplies: no launch and no pass
+// over memory between the projections and the recurrence, and every channel's state is touched by
+// exactly one lane.  Arithmetic and bits as rwkvq_linear_dispatch on the three matrices followed by
+// rwkvq_wkv (the projections are rounded to the output type before they enter the recurrence, as
+// they would be read back).
+struct WkvFuseArgs {
+    DecodeMat m[3];
+    const float* w; const float* u; float* state; void* out;
+    int d, xdt, ydt, pad;
+};
+__global__ void __launch_bounds__(768) decode_rkv_wkv_kernel(WkvFuseArgs a) {
+    constexpr int DEPTH = RWKVQ_DECODE_DEPTH, S = 4;
+    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[3 * S][256];
+    __shared__ float red[3 * S][16];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int mi = wave >> 2, s = wave & 3;
+    const DecodeMat mt = mi == 0 ? a.m[0] : mi == 1 ? a.m[1] : a.m[2];
+    const int KT = mt.K >> 8;
+    WavePos wp;
+    wp.R[0] = wp.R[1] = wp.R[2] = wp.R[3] = blockIdx.x;
+    wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
+    wp.t0 = s; wp.ts = S; wp.nt = s < KT ? (KT - s + S - 1) / S : 0;
+    wp.xprev = nullptr; wp.mix_idx = nullptr; wp.mix_cb = nullptr;
+    // the recurrence's operands for this tile's channels: fetched now, used after the GEMV
+    const size_t c = (size_t)16 * blockIdx.x + (lane & 15);
+    float sa = 0.f, sb = 0.f, sp = 0.f, wc = 0.f, uc = 0.f;
+    if (wave == 0 && lane < 16) {
+        sa = a.state[c]; sb = a.state[(size_t)a.d + c]; sp = a.state[2 * (size_t)a.d + c];
+        wc = a.w[c]; uc = a.u[c];
+    }
+    float part[kRT] = {0.f};
+    if (wp.nt > 0) {
+        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true, false>(mt, wp, part);
+        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, true, false>(mt, wp, cb_all[wave], part);
+        else run_vq8_m1<DEPTH, true, false>(mt, wp, cb_all[wave], part);
+    }
+    float v = part[0];                             // sum the four column groups of each row
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    if (lane < 16) red[wave][lane] = v;
+    __syncthreads();
+    if (wave == 0 && lane < 16) {
+        float y[3];
+#pragma unroll
+        for (int m = 0; m < 3; ++m) {
+            float t = red[S * m][lane];
+#pragma unroll
+            for (int j = 1; j < S; ++j) t += red[S * m + j][lane];
+            store_from_f32(m == 0 ? a.m[0].y : m == 1 ? a.m[1].y : a.m[2].y, c, a.ydt, t);
+            y[m] = a.ydt == DT_F16 ? f16_bits_to_f32(f32_to_f16_bits(t)) : bf16_bits_to_f32(f32_to_bf16_bits(t));
+        }
+        store_from_f32(a.out, c, a.ydt, gate_f32(y[0], wkv_out(sa, sb, sp, uc, y[1], y[2])));
+        wkv_advance(sa, sb, sp, wc, y[1], y[2]);
+        a.state[c] = sa; a.state[(size_t)a.d + c] = sb; a.state[2 * (size_t)a.d + c] = sp;
+    }
+}
+
+hipError_t launch_decode_rkv_wkv(const MatDev* rkv, const WkvDev& wkv, int x_dtype, int y_dtype, hipStream_t s) {
+    WkvFuseArgs a;
+    for (int i = 0; i < 3; ++i)
+        a.m[i] = DecodeMat{rkv[i].codes, rkv[i].aux, rkv[i].x, rkv[i].y, rkv[i].N, rkv[i].K, rkv[i].fmt, POST_NONE, nullptr};
+    a.w = wkv.w; a.u = wkv.u; a.state = wkv.state; a.out = wkv.out;
+    a.d = rkv[0].N; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
+    hipLaunchKernelGGL(decode_rkv_wkv_kernel, dim3(rkv[0].N / 16), dim3(768), 0, s, a);
+    return hipGetLastError();
+}
+
 // Smallest S of 4, 8, 16 that brings `tiles` row tiles to kSplitTarget wavefronts.
 static int pick_split(int tiles) { return tiles * 4 >= kSplitTarget ? 4 : tiles * 8 >= kSplitTarget ? 8 : 16; }
 

@@ -261,3 +261,22 @@ def test_dispatch_post_rejects():
     assert call(pm=(FAKE, [(FAKE, FAKE, 7, FAKE)])) == B.ERR_UNSUPPORTED
     assert call(pm=(FAKE, one), ydt=B.F32) == B.ERR_UNSUPPORTED and call(pm=(FAKE, one), m=mix()) == B.ERR_UNSUPPORTED
     assert call(pm=(FAKE + 2, one)) == B.ERR_ALIGN and call(pm=(FAKE, [(FAKE, FAKE, 6, FAKE + 4)])) == B.ERR_ALIGN
+
+
+def test_rkv_wkv_rejects():
+    from ctypes import c_void_p
+    L = B.lib()
+    good = B.rwkvq_matrix(B.SQ, B.NATIVE, 256, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, None, None)
+    other_n = B.rwkvq_matrix(B.SQ, B.NATIVE, 512, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, None, None)
+    canon = B.rwkvq_matrix(B.SQ, B.CANONICAL, 256, 512, 3, 128, 0, 0, 0, 0, FAKE, FAKE, FAKE, None)
+
+    def call(m=(good, good, good), xs=(FAKE, FAKE, FAKE), ys=(FAKE, FAKE, FAKE), w=FAKE, u=FAKE, state=FAKE, out=FAKE,
+             xdt=B.F16, ydt=B.F16):
+        return L.rwkvq_rkv_wkv((B.rwkvq_matrix * 3)(*m), (c_void_p * 3)(*xs), (c_void_p * 3)(*ys), w, u, state, out, xdt, ydt, None)
+
+    assert call(w=None) == B.ERR_NULL and call(state=None) == B.ERR_NULL and call(out=None) == B.ERR_NULL
+    assert call(xs=(FAKE, None, FAKE)) == B.ERR_NULL and call(ys=(None, FAKE, FAKE)) == B.ERR_NULL
+    assert call(ydt=B.F32) == B.ERR_UNSUPPORTED and call(xdt=B.F32) == B.ERR_UNSUPPORTED
+    assert call(m=(good, canon, good)) == B.ERR_UNSUPPORTED
+    assert call(m=(good, good, other_n)) == B.ERR_SHAPE
+    assert call(out=FAKE + 2) == B.ERR_ALIGN and call(state=FAKE + 2) == B.ERR_ALIGN and call(xs=(FAKE + 4, FAKE, FAKE)) == B.ERR_ALIGN

@@ -491,3 +491,47 @@ def test_post_mix_equals_projection_then_mix_pass(dt, N, K, P, op):
         mu_hat = orc.widen(cbs[p].cpu().numpy().view(np.uint16), "f16").reshape(64, 2)[idx[p].cpu().numpy()].reshape(-1)
         want = MO.narrow(MO.token_shift_mix(zf[None, :], zp, mu_hat), dt)
         assert np.array_equal(mix[p].cpu().numpy().view(np.uint16), want), p
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("d,K,kinds", [(512, 512, ("sq", "vq6", "vq8")), (4096, 4096, ("vq6", "sq", "sq")), (256, 1792, ("vq8", "vq8", "sq"))])
+def test_rkv_wkv_equals_dispatch_then_wkv(dt, d, K, kinds):
+    """The three projections and the wkv step in one launch against rwkvq_linear_dispatch on the three
+    matrices followed by rwkvq_wkv, token after token from the same starting state: the same bits in r, k,
+    v, in the gated output and in the carried state whenever the two take their sums in the same order."""
+    torch = G.torch_()
+    rng = np.random.default_rng(9900 + d + K)
+    mats = [synth.gen_sq(rng, d, K) if kd == "sq" else synth.gen_vq(rng, d, K, 6 if kd == "vq6" else 8) for kd in kinds]
+    dms = [B.upload(m, native=True) for m in mats]
+    descs = [m.desc() for m in dms]
+    _, _, _, w, u = synth.gen_block_inputs(rng, 1, d, dt)
+    wd, ud = dev(w), dev(u)
+    buf = lambda: torch.zeros((1, d), dtype=torch.int16, device="cuda")
+    ya, yb = [buf() for _ in range(3)], [buf() for _ in range(3)]
+    ga, gb = buf(), buf()
+    sa, sb = fresh_state(d), fresh_state(d)
+    DT = B.DTYPES[dt]
+    for t in range(4):
+        xs = [dev(synth.gen_activations(rng, 1, K, dt)) for _ in range(3)]
+        print(f"rkv+wkv {dt} d={d} K={K} {kinds} token {t}", flush=True)
+        B.rwkvq_linear_dispatch(B.DispatchTable(descs, xs, ya), 1, DT, DT)
+        B.rwkvq_wkv(ya[0], ya[1], ya[2], DT, 1, d, wd, ud, sa, ga)
+        B.rwkvq_rkv_wkv(B.RkvWkvTable(descs, xs, yb), wd, ud, sb, gb, DT, DT)
+        torch.cuda.synchronize()
+        # the fused launch always splits a row's columns over four wavefronts; the dispatch of the three
+        # matrices does so from 512 row tiles on (or trivially, with at most four column tiles): then the
+        # binary32 sums are taken in the same order and every bit agrees; otherwise to rounding
+        same_order = 3 * (d // 16) * 4 >= 2048 or K // 256 <= 4
+        if same_order:
+            for i in range(3):
+                assert torch.equal(ya[i], yb[i]), ("rkv"[i], t)
+            assert torch.equal(ga, gb), t
+            assert torch.equal(sa, sb), t
+        else:
+            ulp = 2.0 ** -10 if dt == "f16" else 2.0 ** -7
+            for i in range(3):
+                a_, b_ = host(ya[i], dt), host(yb[i], dt)
+                assert np.all(np.abs(a_ - b_) <= ulp * np.maximum(np.abs(a_), 2.0 ** -14)), ("rkv"[i], t)
+            a_, b_ = host(ga, dt), host(gb, dt)
+            assert np.all(np.abs(a_ - b_) <= 4 * ulp * np.maximum(np.abs(a_), 1e-3)), t
+    assert not torch.equal(sb, fresh_state(d))
