@@ -158,3 +158,69 @@ def test_block_token_step_in_graph():
         assert torch.equal(got_out, out) and torch.equal(got_state, state) and torch.equal(got_o, y["o"])
         assert not torch.equal(state, before)
         o_prev.copy_(y["o"])
+
+
+def test_fused_block_token_step_in_graph():
+    """The same, with r, k, v and the wkv step in one launch and the mixes of channel mixing taken by the
+    W_o launch: replayed for successive tokens against the eager calls from the same state."""
+    torch = G.torch_()
+    rng = np.random.default_rng(7)
+    d, ffn = 512, 1024
+    names = ["r", "k", "v", "o", "ck", "cr", "cv"]
+    mats = dict(zip(names, [synth.gen_vq(rng, d, d, 6), synth.gen_sq(rng, d, d), synth.gen_vq(rng, d, d, 8),
+                            synth.gen_sq(rng, d, d), synth.gen_sq(rng, ffn, d), synth.gen_vq(rng, d, d, 6),
+                            synth.gen_vq(rng, d, ffn, 6)]))
+    dms = {n: B.upload(m, native=True) for n, m in mats.items()}
+    t16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    mix = {n: (torch.from_numpy(rng.integers(0, 64, size=d // 2, dtype=np.uint8)).cuda(), t16(synth.gen_codebook(rng, 64)))
+           for n in ("ck", "cr")}
+    _, _, _, w, u = synth.gen_block_inputs(rng, 1, d, "f16")
+    wd, ud = torch.from_numpy(w).cuda(), torch.from_numpy(u).cuda()
+    buf = lambda n: torch.zeros((1, n), dtype=torch.int16, device="cuda")
+    x, o_prev = buf(d), buf(d)
+    y = {n: buf(mats[n].N) for n in names}
+    gated, sq, out, in_ck, in_cr = buf(d), buf(ffn), buf(d), buf(d), buf(d)
+    st0 = np.zeros((3, d), dtype=np.float32); st0[2] = -1e38
+    state = torch.from_numpy(st0).cuda()
+    t1 = B.RkvWkvTable([dms[n].desc() for n in ("r", "k", "v")], [x, x, x], [y[n] for n in ("r", "k", "v")])
+    t2 = B.PostDispatchTable([dms["o"].desc()], [gated], None,
+                             [(B.POST_NONE, None, o_prev, [(mix["ck"][0], mix["ck"][1], 6, in_ck), (mix["cr"][0], mix["cr"][1], 6, in_cr)])],
+                             [y["o"]])
+    t3 = B.PostDispatchTable([dms[n].desc() for n in ("ck", "cr")], [in_ck, in_cr], None,
+                             [(B.POST_RELU2, None), (B.POST_NONE, None)], [sq, y["cr"]])
+    t4 = B.PostDispatchTable([dms["cv"].desc()], [sq], None, [(B.POST_SIGMOID_GATE, y["cr"])], [out])
+
+    def run():
+        B.rwkvq_rkv_wkv(t1, wd, ud, state, gated, B.F16, B.F16)
+        B.rwkvq_linear_dispatch_post(t2, B.F16, B.F16)
+        B.rwkvq_linear_dispatch_post(t3, B.F16, B.F16)
+        B.rwkvq_linear_dispatch_post(t4, B.F16, B.F16)
+
+    toks = synth.gen_activations(rng, 6, d, "f16")
+    _bits(x, toks[0][None, :])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                              # first call outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    state.copy_(torch.from_numpy(st0).cuda())
+    o_prev.zero_()
+    for t in range(1, 6):
+        print(f"fused block step graph replay, token {t}", flush=True)
+        _bits(x, toks[t][None, :])
+        before = state.clone()
+        out.zero_(); gated.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_out, got_state, got_o = out.clone(), state.clone(), y["o"].clone()
+        state.copy_(before)
+        out.fill_(-1); gated.fill_(-1)
+        run()
+        torch.cuda.synchronize()
+        assert torch.equal(got_out, out) and torch.equal(got_state, state) and torch.equal(got_o, y["o"])
+        assert not torch.equal(state, before)
+        o_prev.copy_(y["o"])
