@@ -23,6 +23,8 @@
 //     Eq. "time mixing r/k/v" is applied while the activations are loaded; with PostMixArgs the
 //     outputs also leave as the mixes of the stage that follows (store_post_mix).  The squared ReLU
 //     and the gates of App. A.1 can be applied where an output is stored (store_post).
+//   * decode_rkv_wkv_kernel: the three projections of time mixing and the wkv step of Eq. "time
+//     mixing wkv" in one launch (a workgroup takes a row tile of r, k and v and steps its 16 channels).
 //   * Batch 2..32 (MT = 4, 16, 32) on the matrix cores (v_mfma_f32_16x16x32_f16, activations = A
 //     operand, weights = B operand): the activation tile of a column tile is fetched once per
 //     workgroup into LDS (two buffers, one barrier per tile); SQ codes enter as 8 + q (one shift
