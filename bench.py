@@ -116,7 +116,7 @@ def sequential_step(dec, n_layers):
     import torch
     from paper_2505_03803_amd import binding as B
     from paper_2505_03803_amd import synth
-    d = 4096
+    d = int(dec["descs"][0].K)                                  # hidden size: K of the receptance projection
     rng = np.random.default_rng(4000)
     t16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda()
     h = t16(synth.gen_activations(rng, 1, d, "f16"))            # the hidden state entering a layer
@@ -434,7 +434,7 @@ def prefill_block_step(pf, n_layers, M):
     import torch
     from paper_2505_03803_amd import binding as B
     from paper_2505_03803_amd import synth
-    d = 4096
+    d = int(pf["descs"][0].K)
     ffn = pf["ys"][5].shape[1]
     rng = np.random.default_rng(4100)
     t16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda()
