@@ -185,6 +185,18 @@ int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats,
                 double tau_c, double tau_f, void* workspace, double* proxies, int32_t* phi,
                 void* stream);
 
+/* rwkvq_proxy for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as rwkvq_proxy without `workspace`: the bitmaps live in a device array inside the library
+ * (8 KiB per matrix, RWKVQ_PROXY_STATIC_MAX_MATS matrices = 2 MiB, held on every GPU the library
+ * runs on until the process ends), whose address is looked up on the first call on each device.  The
+ * call allocates nothing, on the host or on the device.  n_mats > RWKVQ_PROXY_STATIC_MAX_MATS returns
+ * RWKVQ_ERR_SHAPE.  Every call on a GPU uses that GPU's one array (cleared by a kernel at the start of
+ * each call): calls on one GPU must be ordered, by one stream or by events; calls that overlap race. */
+#define RWKVQ_PROXY_STATIC_MAX_MATS 256
+int rwkvq_proxy_static(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
+                       double tau_c, double tau_f, double* proxies, int32_t* phi, void* stream);
+
 /* ---- encoders (Sec. 2.2, Eq. "SQ" and Eq. "VQ"): dense weights -> canonical-layout codes -----------
  *
  * w: DEVICE pointer, row-major [N][K], fp16 / bf16 bit patterns or binary32 (w_dtype), finite.

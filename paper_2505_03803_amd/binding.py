@@ -22,7 +22,7 @@ EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
            "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
-           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan", "rwkvq_rkv_wkv"]
+           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan", "rwkvq_rkv_wkv", "rwkvq_proxy_static"]
 
 
 class rwkvq_mix_input(Structure):
@@ -97,6 +97,9 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_proxy.restype = c_int
         L.rwkvq_proxy.argtypes = [POINTER(c_void_p), POINTER(c_int), POINTER(c_int), c_int, c_int, c_int,
                                   c_double, c_double, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.rwkvq_proxy_static.restype = c_int
+        L.rwkvq_proxy_static.argtypes = [POINTER(c_void_p), POINTER(c_int), POINTER(c_int), c_int, c_int, c_int,
+                                         c_double, c_double, c_void_p, c_void_p, c_void_p]
         L.rwkvq_sq_encode.restype = c_int
         L.rwkvq_sq_encode.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
                                       c_void_p]
@@ -221,6 +224,12 @@ def rwkvq_proxy(table: ProxyTable, w_dtype, terms, tau_c, tau_f, workspace, prox
                 check=True):
     st = lib().rwkvq_proxy(table.ws, table.Ns, table.Ks, table.n, w_dtype, terms, tau_c, tau_f,
                            _ptr(workspace), _ptr(proxies), _ptr(phi), _stream(stream))
+    return _check(st) if check else st
+
+
+def rwkvq_proxy_static(table: ProxyTable, w_dtype, terms, tau_c, tau_f, proxies, phi, stream=None, check=True):
+    st = lib().rwkvq_proxy_static(table.ws, table.Ns, table.Ks, table.n, w_dtype, terms, tau_c, tau_f,
+                                  _ptr(proxies), _ptr(phi), _stream(stream))
     return _check(st) if check else st
 
 

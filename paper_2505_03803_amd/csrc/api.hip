@@ -265,21 +265,12 @@ size_t rwkvq_proxy_workspace_bytes(int n_mats) {          /* one bit per 16-bit 
 
 int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
                 double tau_c, double tau_f, void* workspace, double* proxies, int32_t* phi, void* stream) {
-    if (!ws || !Ns || !Ks || !workspace || !proxies || !phi) return RWKVQ_ERR_NULL;
-    if (n_mats < 1) return RWKVQ_ERR_SHAPE;
-    if (w_dtype != RWKVQ_F16 && w_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
-    if (terms < 2 || terms > 8) return RWKVQ_ERR_UNSUPPORTED;
-    if (!aligned16(workspace) || !aligned16(proxies) || ((uintptr_t)phi & 3u)) return RWKVQ_ERR_ALIGN;
-    std::vector<unsigned long long> counts((size_t)n_mats);
-    for (int i = 0; i < n_mats; ++i) {
-        if (!ws[i]) return RWKVQ_ERR_NULL;
-        if (!aligned16(ws[i])) return RWKVQ_ERR_ALIGN;
-        if (Ns[i] < 1 || Ks[i] < 1) return RWKVQ_ERR_SHAPE;
-        counts[(size_t)i] = (unsigned long long)Ns[i] * (unsigned long long)Ks[i];
-        if (counts[(size_t)i] < 2ull || counts[(size_t)i] > 0xFFFFFFFFull) return RWKVQ_ERR_SHAPE;
-    }
-    hipError_t e = launch_proxy(ws, counts.data(), n_mats, w_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, terms, tau_c,
-                                tau_f, (uint32_t*)workspace, proxies, phi, (hipStream_t)stream);
+    if (!workspace) return RWKVQ_ERR_NULL;
+    const int st = check_proxy_args(ws, Ns, Ks, n_mats, w_dtype, terms, proxies, phi);
+    if (st != RWKVQ_OK) return st;
+    if (!aligned16(workspace)) return RWKVQ_ERR_ALIGN;
+    hipError_t e = launch_proxy(ws, Ns, Ks, n_mats, w_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, terms, tau_c, tau_f,
+                                (uint32_t*)workspace, proxies, phi, (hipStream_t)stream);
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 

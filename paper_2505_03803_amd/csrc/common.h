@@ -177,9 +177,12 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
 hipError_t launch_prefill(const MatDev* mats, int n_mats, int M, int x_dtype, int y_dtype,
                           hipStream_t s);
 
-hipError_t launch_proxy(const void* const* ws, const unsigned long long* counts, int n_mats, int dtype,
+hipError_t launch_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int dtype,
                         int terms, double tau_c, double tau_f, uint32_t* bitmaps, double* out, int32_t* phi,
                         hipStream_t s);
+// Host-side checks of a proxy call (everything but the workspace); RWKVQ_OK or the status to return.
+int check_proxy_args(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
+                     const double* proxies, const int32_t* phi);
 
 hipError_t launch_sq_encode(const void* w, int wdt, int N, int K, uint32_t* codes, uint16_t* scales,
                             uint16_t* zeros, hipStream_t s);

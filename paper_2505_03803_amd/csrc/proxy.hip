@@ -16,6 +16,9 @@
 // quantity of order one where n^k delta^k would leave the range of the arithmetic.  All sums are
 // binary64 in a fixed order, so results are reproducible bit for bit.
 #include "common.h"
+#include "../../include/rwkvq.h"
+
+#include <mutex>
 
 namespace rwkvq {
 
@@ -204,20 +207,21 @@ __global__ void __launch_bounds__(kFinalThreads, 1) proxy_final_kernel(ProxyArgs
     }
 }
 
-hipError_t launch_proxy(const void* const* ws, const unsigned long long* counts, int n_mats, int dtype, int terms,
+hipError_t launch_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int dtype, int terms,
                         double tau_c, double tau_f, uint32_t* bitmaps, double* out, int32_t* phi, hipStream_t s) {
     for (int base = 0; base < n_mats; base += kProxyMaxMats) {
         ProxyArgs a;
         const int cnt = n_mats - base < kProxyMaxMats ? n_mats - base : kProxyMaxMats;
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
-            const unsigned long long nvec = counts[base + i] / 8;
+            const unsigned long long count = (unsigned long long)Ns[base + i] * (unsigned long long)Ks[base + i];
+            const unsigned long long nvec = count / 8;
             unsigned long long g = (nvec + 16ull * kSetThreads - 1) / (16ull * kSetThreads);   // >= 128 weights per thread
             g = g < 1 ? 1 : g > (unsigned long long)kSetMaxWgs ? kSetMaxWgs : g;
             wgs += (int)g;
             a.wg_end[i] = wgs;
             a.w[i] = (const uint16_t*)ws[base + i];
-            a.count[i] = counts[base + i];
+            a.count[i] = count;
         }
         for (int i = cnt; i < kProxyMaxMats; ++i) { a.wg_end[i] = 0x7FFFFFFF; a.w[i] = nullptr; a.count[i] = 0; }
         a.bitmaps = bitmaps + (size_t)base * kBitmapWords;
@@ -238,4 +242,62 @@ hipError_t launch_proxy(const void* const* ws, const unsigned long long* counts,
     return hipSuccess;
 }
 
+int check_proxy_args(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
+                     const double* proxies, const int32_t* phi) {
+    if (!ws || !Ns || !Ks || !proxies || !phi) return RWKVQ_ERR_NULL;
+    if (n_mats < 1) return RWKVQ_ERR_SHAPE;
+    if (w_dtype != RWKVQ_F16 && w_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    if (terms < 2 || terms > kMaxTerms) return RWKVQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)proxies & 15u) || ((uintptr_t)phi & 3u)) return RWKVQ_ERR_ALIGN;
+    for (int i = 0; i < n_mats; ++i) {
+        if (!ws[i]) return RWKVQ_ERR_NULL;
+        if ((uintptr_t)ws[i] & 15u) return RWKVQ_ERR_ALIGN;
+        if (Ns[i] < 1 || Ks[i] < 1) return RWKVQ_ERR_SHAPE;
+        const unsigned long long count = (unsigned long long)Ns[i] * (unsigned long long)Ks[i];
+        if (count < 2ull || count > 0xFFFFFFFFull) return RWKVQ_ERR_SHAPE;
+    }
+    return RWKVQ_OK;
+}
+
+// ---- the same call for callers that cannot allocate -------------------------------------------
+// The bitmaps live in a file-scope device array instead of a caller's workspace.  The array's name
+// is a host-side stand-in in host code: its device address is looked up once per device
+// (hipGetSymbolAddress with that device current) and only that address is handed to the kernels.
+constexpr int kStaticMaxMats = RWKVQ_PROXY_STATIC_MAX_MATS;
+static __device__ __align__(256) uint32_t scratch[(size_t)kStaticMaxMats * kBitmapWords];   // 2 MiB per device
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static uint32_t* scratch_addr[kMaxDevices];       // device address of `scratch` on device i, once known
+
+static hipError_t scratch_of_current_device(uint32_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_addr[dev] = (uint32_t*)p;
+    }
+    *out = scratch_addr[dev];
+    return hipSuccess;
+}
+
 }  // namespace rwkvq
+
+extern "C" int rwkvq_proxy_static(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype,
+                                  int terms, double tau_c, double tau_f, double* proxies, int32_t* phi, void* stream) {
+    using namespace rwkvq;
+    const int st = check_proxy_args(ws, Ns, Ks, n_mats, w_dtype, terms, proxies, phi);
+    if (st != RWKVQ_OK) return st;
+    if (n_mats > kStaticMaxMats) return RWKVQ_ERR_SHAPE;
+    uint32_t* bitmaps = nullptr;
+    if (scratch_of_current_device(&bitmaps) != hipSuccess) return RWKVQ_ERR_DEVICE;
+    hipError_t e = launch_proxy(ws, Ns, Ks, n_mats, w_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, terms, tau_c, tau_f, bitmaps,
+                                proxies, phi, (hipStream_t)stream);
+    return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
+}
