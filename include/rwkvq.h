@@ -91,6 +91,27 @@ typedef struct rwkvq_matrix {
 int rwkvq_version(void);
 const char* rwkvq_status_string(int status);
 
+/* Process-wide settings that replace a choice the library otherwise makes from the sizes of a call
+ * (for tests, which run both sides of each choice, and for tuning on another machine).  Thread-safe;
+ * a call made after rwkvq_set_option returns sees the new value.
+ *   RWKVQ_OPT_SMALL_BATCH_PATH    how native-layout matrices run at 16 < M <= 128 (see rwkvq_sq_gemm):
+ *                                 RWKVQ_SMALL_BATCH_AUTO (default: the estimate below), _STREAM, _MATRIX_CORES
+ *   RWKVQ_OPT_PREFILL_TILE_ROWS   rows of x per matrix-core workgroup: 0 (default: chosen per launch), 128, 256
+ *   the constants of the small-batch estimate, measured on the RWKV-6-7B shapes on one MI355X
+ *   (0 restores the default):
+ *   RWKVQ_OPT_STREAM_WIDE_GBPS    packed-weight GB/s of a streaming pass over 17..32 batch rows (2800)
+ *   RWKVQ_OPT_STREAM_NARROW_GBPS  ... over <= 16 batch rows (4100)
+ *   RWKVQ_OPT_STREAM_WIDE_MIN_US  least duration of such a pass in microseconds (24)
+ *   RWKVQ_OPT_STREAM_NARROW_MIN_US  (12)
+ *   RWKVQ_OPT_MFMA_KSTEP_NS       one 64-column step of a 128-row matrix-core workgroup in nanoseconds (1500)
+ * Errors: RWKVQ_ERR_UNSUPPORTED (unknown option, value out of range), RWKVQ_ERR_NULL. */
+enum { RWKVQ_OPT_SMALL_BATCH_PATH = 0, RWKVQ_OPT_PREFILL_TILE_ROWS = 1, RWKVQ_OPT_STREAM_WIDE_GBPS = 2,
+       RWKVQ_OPT_STREAM_NARROW_GBPS = 3, RWKVQ_OPT_STREAM_WIDE_MIN_US = 4, RWKVQ_OPT_STREAM_NARROW_MIN_US = 5,
+       RWKVQ_OPT_MFMA_KSTEP_NS = 6 };
+enum { RWKVQ_SMALL_BATCH_AUTO = 0, RWKVQ_SMALL_BATCH_STREAM = 1, RWKVQ_SMALL_BATCH_MATRIX_CORES = 2 };
+int rwkvq_set_option(int option, int value);
+int rwkvq_get_option(int option, int* value /* host */);
+
 /* One-time reordering canonical -> native (see the layout section above).  Output buffers have
  * the same sizes as the inputs: codes_native K*bits/8*N bytes, sz_native 4*N*K/group bytes;
  * indices_native (K/vdim)*kbits/8*N bytes.  Outputs must not overlap inputs. */
@@ -111,8 +132,12 @@ int rwkvq_vq_dequant(const void* indices, const void* codebooks, int layout, int
                      void* stream);
 
 /* y[M][N] = x[M][K] * Deq(W)^T for one matrix (the W. products of App. A.1).
- * x is row-major fp16 or bf16; y is row-major fp16, bf16 or fp32; products are accumulated in
- * binary32 and y is rounded to nearest even.  The path is chosen from M and the layout:
+ * x is row-major fp16 or bf16 (any finite values: the streaming kernels multiply fp16 operands and
+ * bring bf16 activations into fp16's range group by group with exact power-of-two scales - a
+ * group being the columns that share an accumulator, at most 256 consecutive ones of a row of x - so
+ * an activation enters its sum exactly unless it is more than 2^29 times smaller than the largest
+ * of its group, which is below the resolution of the binary32 sum); y is row-major fp16, bf16 or
+ * fp32; products are accumulated in binary32 and y is rounded to nearest even.  The path is chosen from M and the layout:
  *   canonical layout: a plain reference kernel (any M);
  *   native layout, M <= 16: streaming dequant-GEMV kernels bound by HBM bandwidth;
  *   native layout, M  > 16: tiles dequantized into LDS and multiplied on the matrix cores in

@@ -22,7 +22,8 @@ EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq
            "rwkvq_sq_dequant", "rwkvq_vq_dequant", "rwkvq_sq_gemm", "rwkvq_vq_gemm",
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
            "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
-           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan", "rwkvq_rkv_wkv", "rwkvq_proxy_static"]
+           "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan", "rwkvq_rkv_wkv", "rwkvq_proxy_static",
+           "rwkvq_set_option", "rwkvq_get_option"]
 
 
 class rwkvq_mix_input(Structure):
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_version.argtypes = []
         L.rwkvq_status_string.restype = c_char_p
         L.rwkvq_status_string.argtypes = [c_int]
+        L.rwkvq_set_option.restype = c_int
+        L.rwkvq_set_option.argtypes = [c_int, c_int]
+        L.rwkvq_get_option.restype = c_int
+        L.rwkvq_get_option.argtypes = [c_int, POINTER(c_int)]
         L.rwkvq_sq_prepack.restype = c_int
         L.rwkvq_sq_prepack.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p,
                                        c_void_p, c_void_p]
@@ -133,6 +138,22 @@ def lib() -> ctypes.CDLL:
         L.rwkvq_sigmoid_gate.argtypes = [c_void_p, c_void_p, c_int, c_longlong, c_void_p, c_void_p]
         _lib = L
     return _lib
+
+
+(OPT_SMALL_BATCH_PATH, OPT_PREFILL_TILE_ROWS, OPT_STREAM_WIDE_GBPS, OPT_STREAM_NARROW_GBPS, OPT_STREAM_WIDE_MIN_US,
+ OPT_STREAM_NARROW_MIN_US, OPT_MFMA_KSTEP_NS) = range(7)
+SMALL_BATCH_AUTO, SMALL_BATCH_STREAM, SMALL_BATCH_MATRIX_CORES = 0, 1, 2
+
+
+def rwkvq_set_option(option: int, value: int, check=True):
+    st = lib().rwkvq_set_option(option, value)
+    return _check(st) if check else st
+
+
+def rwkvq_get_option(option: int) -> int:
+    v = c_int(0)
+    _check(lib().rwkvq_get_option(option, ctypes.byref(v)))
+    return int(v.value)
 
 
 def status_string(status: int) -> str:

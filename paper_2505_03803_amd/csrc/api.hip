@@ -5,7 +5,7 @@
 
 #include <cmath>
 #include <algorithm>
-#include <cstdlib>
+#include <atomic>
 #include <vector>
 
 using namespace rwkvq;
@@ -74,20 +74,19 @@ rwkvq_matrix vq_desc(const void* indices, const void* codebooks, int layout, int
     return m;
 }
 
-// Estimated cost, in microseconds, of the two ways to run native-layout matrices at 16 < M <= 128.
-// Constants measured on the 7B shapes: a streaming pass over 17..32 batch rows moves 2.8 TB/s of
-// packed weights and costs at least 24 us, one over <= 16 rows 4.1 TB/s and at least 12 us; a k-step
-// of a 128-row matrix-core workgroup takes 1.5 us, one workgroup per compute unit.
-// RWKVQ_SMALL_BATCH_PATH=stream|mfma in the environment overrides the estimate (tests run both).
+// Estimated cost, in microseconds, of the two ways to run native-layout matrices at 16 < M <= 128:
+// a streaming pass over 17..32 batch rows moves `wide` GB/s of packed weights and costs at least
+// `wide_min` us, one over <= 16 rows `narrow` GB/s and at least `narrow_min` us; a k-step of a 128-row
+// matrix-core workgroup takes `kstep` ns, one workgroup per compute unit.  The defaults (rwkvq.h) were
+// measured on the 7B shapes on one MI355X; rwkvq_set_option replaces them, or forces one path.
 constexpr int kStreamPassesMaxM = 128;
 constexpr int kStreamPassRows = 32;    // batch rows per pass of the streaming kernels (their largest instance)
 bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
     for (const MatDev& d : mats)
         if (d.K > kDecodeMaxK) return false;
-    if (const char* e = std::getenv("RWKVQ_SMALL_BATCH_PATH")) {
-        if (e[0] == 's') return true;
-        if (e[0] == 'm') return false;
-    }
+    const int forced = option(RWKVQ_OPT_SMALL_BATCH_PATH);
+    if (forced == RWKVQ_SMALL_BATCH_STREAM) return true;
+    if (forced == RWKVQ_SMALL_BATCH_MATRIX_CORES) return false;
     double bytes = 0.0, work = 0.0, longest = 0.0;
     for (const MatDev& d : mats) {
         const double nk = (double)d.N * d.K;
@@ -95,10 +94,11 @@ bool stream_passes_cheaper(const std::vector<MatDev>& mats, int M) {
         work += (double)(d.N / 256) * (d.K / 64);
         longest = std::max(longest, (double)(d.K / 64));
     }
-    const double wide = std::max(bytes / 2.8e6, 24.0), narrow = std::max(bytes / 4.1e6, 12.0);
+    const double wide = std::max(bytes / (1e3 * option(RWKVQ_OPT_STREAM_WIDE_GBPS)), (double)option(RWKVQ_OPT_STREAM_WIDE_MIN_US));
+    const double narrow = std::max(bytes / (1e3 * option(RWKVQ_OPT_STREAM_NARROW_GBPS)), (double)option(RWKVQ_OPT_STREAM_NARROW_MIN_US));
     const int full = M / kStreamPassRows, rest = M % kStreamPassRows;
     const double t_stream = full * wide + (rest == 0 ? 0.0 : rest <= kDecodeMaxM ? narrow : wide);
-    const double t_mfma = 1.5 * std::max(work / 256.0, longest);
+    const double t_mfma = 1e-3 * option(RWKVQ_OPT_MFMA_KSTEP_NS) * std::max(work / 256.0, longest);
     return t_stream < t_mfma;
 }
 
@@ -123,9 +123,37 @@ void plan_paths(const std::vector<MatDev>& devs, int M, std::vector<int>* path) 
 
 }  // namespace
 
+namespace rwkvq {
+static const int kOptionDefault[kOptionCount] = {RWKVQ_SMALL_BATCH_AUTO, 0, 2800, 4100, 24, 12, 1500};
+static std::atomic<int> g_option[kOptionCount] = {{RWKVQ_SMALL_BATCH_AUTO}, {0}, {2800}, {4100}, {24}, {12}, {1500}};
+int option(int which) { return g_option[which].load(std::memory_order_relaxed); }
+}  // namespace rwkvq
+
 extern "C" {
 
-int rwkvq_version(void) { return 100; }
+int rwkvq_version(void) { return 101; }
+
+int rwkvq_set_option(int opt, int value) {
+    if (opt < 0 || opt >= kOptionCount) return RWKVQ_ERR_UNSUPPORTED;
+    if (opt == RWKVQ_OPT_SMALL_BATCH_PATH) {
+        if (value != RWKVQ_SMALL_BATCH_AUTO && value != RWKVQ_SMALL_BATCH_STREAM && value != RWKVQ_SMALL_BATCH_MATRIX_CORES)
+            return RWKVQ_ERR_UNSUPPORTED;
+    } else if (opt == RWKVQ_OPT_PREFILL_TILE_ROWS) {
+        if (value != 0 && value != 128 && value != 256) return RWKVQ_ERR_UNSUPPORTED;
+    } else {
+        if (value < 0 || value > 1000000) return RWKVQ_ERR_UNSUPPORTED;
+        if (value == 0) value = kOptionDefault[opt];
+    }
+    g_option[opt].store(value, std::memory_order_relaxed);
+    return RWKVQ_OK;
+}
+
+int rwkvq_get_option(int opt, int* value) {
+    if (!value) return RWKVQ_ERR_NULL;
+    if (opt < 0 || opt >= kOptionCount) return RWKVQ_ERR_UNSUPPORTED;
+    *value = option(opt);
+    return RWKVQ_OK;
+}
 
 const char* rwkvq_status_string(int status) {
     switch (status) {

@@ -32,7 +32,8 @@
 //     operand, y += s (acc - (8 + z) X); VQ pairs are LDS gathers.  A wavefront takes two row
 //     tiles of W, and with MT = 32 two groups of 16 batch rows: every unpacked weight operand
 //     feeds one MFMA per group.
-//   * bf16 activations are converted to fp16 on load (exact for |x| in [2^-14, 65504]).
+//   * bf16 activations are converted to fp16 on load, group by group under an exact power-of-two
+//     scale (see "bf16 activations" below), so their whole range is accepted.
 #include "common.h"
 #include <algorithm>
 
@@ -221,21 +222,71 @@ __device__ __forceinline__ void x_load_wg(XShared& r, const uint16_t* x, int M, 
     r.b = *(const uint4_t*)(p + 8);
 }
 
-__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
-    half_t h0 = (half_t)__builtin_bit_cast(float, v << 16);
-    half_t h1 = (half_t)__builtin_bit_cast(float, v & 0xFFFF0000u);
-    return (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
+// ---- bf16 activations -----------------------------------------------------------------------
+// These kernels multiply fp16 operands (codebook entries are fp16, SQ codes are fp16 subnormals in
+// place), so bf16 activations are converted, and fp16 holds a bf16 value exactly only for
+// magnitudes in [2^-17, 65536).  Activations that share an accumulator (batch 1: the 64 columns a
+// row of sixteen lanes multiplies in a tile; batch > 1: the 256 columns of one batch row in a tile)
+// are therefore first multiplied by the power of two that brings the largest magnitude among them to
+// [2^15, 2^16), and their partial sum is multiplied by the inverse power before it joins the running
+// output.  Both steps are exact, so every activation within 2^-32 of its group's largest enters the
+// sum exactly, whatever the magnitudes are; a smaller one is cut off below 2^-39 of that largest (the
+// conversion rounds toward zero, which only matters there), far below the resolution of the
+// binary32 sum it joins.
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// Larger of the two halves of max(|a|, |b|) taken per bf16 half: the magnitude bits of the largest of four values.
+__device__ __forceinline__ uint32_t bf16x2_absmax(uint32_t a, uint32_t b) {
+    const ushort2_t m = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a & 0x7FFF7FFFu),
+                                                  __builtin_bit_cast(ushort2_t, b & 0x7FFF7FFFu));
+    const uint32_t w = __builtin_bit_cast(uint32_t, m);
+    return max(w >> 16, w & 0xFFFFu);
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_max(uint32_t v) {   // lanes the control leaves out contribute zero
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+    return max(v, o);
+}
+// All sixteen lanes of a row get the row's maximum.
+__device__ __forceinline__ uint32_t dpp_row_max(uint32_t v) {
+    v = dpp_max<0xB1>(v);       // quad_perm [1, 0, 3, 2]
+    v = dpp_max<0x4E>(v);       // quad_perm [2, 3, 0, 1]
+    v = dpp_max<0x141>(v);      // row_half_mirror
+    return dpp_max<0x140>(v);   // row_mirror
+}
+// Exponent n of the scale 2^n for a group whose largest bf16 magnitude has the bits `amax`: the
+// largest lands in [2^15, 2^16).  An all-zero (or tiny) group takes the largest n whose inverse
+// 2^-n is still a normal binary32 number.
+__device__ __forceinline__ int bf16_scale_exponent(uint32_t amax) {
+    const int e = (int)(amax >> 7);                 // biased exponent, 0..254 for finite values
+    return 142 - (e > 16 ? e : 16);
+}
+// Two bf16 -> two fp16, each multiplied by 2^n first.  Exact where fp16 can hold the product.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v, int n) {
+    const float lo = ldexpf(__builtin_bit_cast(float, v << 16), n);
+    const float hi = ldexpf(__builtin_bit_cast(float, v & 0xFFFF0000u), n);
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
+// bf16: the sixteen threads that hold one batch row's 256 columns are one DPP row; they agree on the
+// row's scale for this tile, convert, and thread 0 of the row leaves the inverse scale in xsc[row].
 template <int MT>
-__device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, int tid, bool bf16, int g = 0) {
-    if (16 * g + (tid >> 4) < MT) {
-        uint4_t a = r.a, b = r.b;
-        if (bf16) {
-            a.x = bf16x2_to_f16x2(a.x); a.y = bf16x2_to_f16x2(a.y); a.z = bf16x2_to_f16x2(a.z); a.w = bf16x2_to_f16x2(a.w);
-            b.x = bf16x2_to_f16x2(b.x); b.y = bf16x2_to_f16x2(b.y); b.z = bf16x2_to_f16x2(b.z); b.w = bf16x2_to_f16x2(b.w);
-        }
-        half_t* d = xs + (16 * g + (tid >> 4)) * kXStride + 16 * (tid & 15);
+__device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, float* xsc, int tid, bool bf16, int g = 0) {
+    const int row = 16 * g + (tid >> 4);
+    uint4_t a = r.a, b = r.b;
+    if (bf16) {
+        const ushort2_t m01 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a.x & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, a.y & 0x7FFF7FFFu));
+        const ushort2_t m23 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a.z & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, a.w & 0x7FFF7FFFu));
+        const ushort2_t m45 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, b.x & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, b.y & 0x7FFF7FFFu));
+        const ushort2_t m67 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, b.z & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, b.w & 0x7FFF7FFFu));
+        const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_elementwise_max(m01, m23), __builtin_elementwise_max(m45, m67)));
+        const int n = bf16_scale_exponent(dpp_row_max(max(w >> 16, w & 0xFFFFu)));
+        a.x = bf16x2_to_f16x2(a.x, n); a.y = bf16x2_to_f16x2(a.y, n); a.z = bf16x2_to_f16x2(a.z, n); a.w = bf16x2_to_f16x2(a.w, n);
+        b.x = bf16x2_to_f16x2(b.x, n); b.y = bf16x2_to_f16x2(b.y, n); b.z = bf16x2_to_f16x2(b.z, n); b.w = bf16x2_to_f16x2(b.w, n);
+        if ((tid & 15) == 0) xsc[row] = ldexpf(1.0f, -n);      // rows beyond MT repeat row M - 1: written, never used
+    }
+    if (row < MT) {
+        half_t* d = xs + row * kXStride + 16 * (tid & 15);
         *(uint4_t*)d = a;
         *(uint4_t*)(d + 8) = b;
     }
@@ -350,8 +401,8 @@ struct WavePos {
 // SQ: the codes enter as 8 + q (one shift and one and-or per pair).  The group sums of the
 // activations come from the matrix cores too: one more MFMA per k-step with an all-ones B operand
 // leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
-template <int MT, int DEPTH>
-__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs,
+template <int MT, int DEPTH, bool XB>
+__device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc,
                                        float4_t (&out)[groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = G == 1 ? 2 : 1;   // one group: the fragments of both column halves up front
     using Regs = SqRegs<G>;
@@ -385,9 +436,13 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     };
     auto compute = [&](const Regs& r, int T) {
         half_t* buf = xs + (T & 1) * (MT * kXStride);
+        float* scb = xsc + (T & 1) * (16 * G);
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, wp.tid, wp.xbf16, g);
+        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
         __syncthreads();
+        float4_t sc[G];                              // bf16: inverse scale of this tile for the lane's batch rows
+#pragma unroll
+        for (int g = 0; g < G; ++g) sc[g] = XB ? *(const float4_t*)(scb + 16 * g + 4 * (lane >> 4)) : float4_t{1, 1, 1, 1};
 #pragma unroll
         for (int ub = 0; ub < 2; ub += UB) {
             half8_t xa[UB][G][4];
@@ -424,7 +479,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
                         acc = RWKVQ_MFMA(xa[uu][g][2], op2, acc);
                         acc = RWKVQ_MFMA(xa[uu][g][3], op3, acc);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(s, fmaf(-z8, X[g][i], acc[i]), out[g][rt][i]);
+                        for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(XB ? s * sc[g][i] : s, fmaf(-z8, X[g][i], acc[i]), out[g][rt][i]);
                     }
                 }
             }
@@ -435,8 +490,8 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
 
 // 6-bit VQ: the codebook of a tile (64 entries, one per lane) goes through a wavefront-private LDS
 // slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
-template <int MT, int DEPTH>
-__device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+template <int MT, int DEPTH, bool XB>
+__device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
                                         float4_t (&out)[groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = G == 1 ? 2 : 1;
     using Regs = Vq6Regs<G>;
@@ -464,11 +519,21 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
     };
     auto compute = [&](const Regs& r, int T) {
         half_t* buf = xs + (T & 1) * (MT * kXStride);
+        float* scb = xsc + (T & 1) * (16 * G);
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, wp.tid, wp.xbf16, g);
+        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
         cb_lds[(T & 1) * 256 + lane] = r.cb;         // two slots, 1 KB apart (the gather address ORs the index in)
         __syncthreads();
         const uint32_t base = base0 + (T & 1) * 1024;
+        // bf16: the tile's products are summed on their own and join the output through the rows' inverse scales
+        float4_t part[G][kBRT];
+        float4_t (&acc)[G][kBRT] = *(XB ? &part : &out);
+        if (XB) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int rt = 0; rt < kBRT; ++rt) part[g][rt] = float4_t{0, 0, 0, 0};
+        }
 #pragma unroll
         for (int ub = 0; ub < 2; ub += UB) {
             half8_t xa[UB][G][4];
@@ -491,12 +556,22 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
                                   op3 = __builtin_bit_cast(half8_t, vq6_gather4<3>(w0, w1, w2, m, base));
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][0], op0, out[g][rt]);
-                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][1], op1, out[g][rt]);
-                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][2], op2, out[g][rt]);
-                        out[g][rt] = RWKVQ_MFMA(xa[uu][g][3], op3, out[g][rt]);
+                        acc[g][rt] = RWKVQ_MFMA(xa[uu][g][0], op0, acc[g][rt]);
+                        acc[g][rt] = RWKVQ_MFMA(xa[uu][g][1], op1, acc[g][rt]);
+                        acc[g][rt] = RWKVQ_MFMA(xa[uu][g][2], op2, acc[g][rt]);
+                        acc[g][rt] = RWKVQ_MFMA(xa[uu][g][3], op3, acc[g][rt]);
                     }
                 }
+            }
+        }
+        if (XB) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float4_t sc = *(const float4_t*)(scb + 16 * g + 4 * (lane >> 4));
+#pragma unroll
+                for (int rt = 0; rt < kBRT; ++rt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(part[g][rt][i], sc[i], out[g][rt][i]);
             }
         }
     };
@@ -505,8 +580,8 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
 
 // 8-bit VQ: the codebook of a tile (256 entries) goes through a wavefront-private LDS region; the
 // workgroup barrier that publishes the activations also orders that store before the gathers.
-template <int MT, int DEPTH>
-__device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, uint32_t* cb_lds,
+template <int MT, int DEPTH, bool XB>
+__device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
                                         float4_t (&out)[groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT);
     using Regs = Vq8Regs<G>;
@@ -531,11 +606,20 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
     };
     auto compute = [&](const Regs& r, int T) {
         half_t* buf = xs + (T & 1) * (MT * kXStride);
+        float* scb = xsc + (T & 1) * (16 * G);
         uint32_t* cbuf = cb_lds + (T & 1) * 256;     // two codebook slots, like the activations
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, wp.tid, wp.xbf16, g);
+        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
         *(uint4_t*)(cbuf + 4 * lane) = r.cb;
         __syncthreads();
+        float4_t part[G][kBRT];                      // bf16: as in run_vq6
+        float4_t (&acc)[G][kBRT] = *(XB ? &part : &out);
+        if (XB) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int rt = 0; rt < kBRT; ++rt) part[g][rt] = float4_t{0, 0, 0, 0};
+        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             half8_t xa[G][4];
@@ -550,11 +634,21 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
                               op3 = vq8_operand(w.w, cbuf);
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    out[g][rt] = RWKVQ_MFMA(xa[g][0], op0, out[g][rt]);
-                    out[g][rt] = RWKVQ_MFMA(xa[g][1], op1, out[g][rt]);
-                    out[g][rt] = RWKVQ_MFMA(xa[g][2], op2, out[g][rt]);
-                    out[g][rt] = RWKVQ_MFMA(xa[g][3], op3, out[g][rt]);
+                    acc[g][rt] = RWKVQ_MFMA(xa[g][0], op0, acc[g][rt]);
+                    acc[g][rt] = RWKVQ_MFMA(xa[g][1], op1, acc[g][rt]);
+                    acc[g][rt] = RWKVQ_MFMA(xa[g][2], op2, acc[g][rt]);
+                    acc[g][rt] = RWKVQ_MFMA(xa[g][3], op3, acc[g][rt]);
                 }
+            }
+        }
+        if (XB) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float4_t sc = *(const float4_t*)(scb + 16 * g + 4 * (lane >> 4));
+#pragma unroll
+                for (int rt = 0; rt < kBRT; ++rt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(part[g][rt][i], sc[i], out[g][rt][i]);
             }
         }
     };
@@ -647,7 +741,7 @@ __device__ __forceinline__ void mix_apply(const Regs& r, const WavePos& wp, uint
 
 struct Vq6M1Regs { uint4_t a[kRT]; uint2_t b[kRT]; uint32_t cb; XPairs x, xq; uint32_t mi; };
 
-template <int DEPTH, bool SPLIT = false, bool MIXED = false>
+template <int DEPTH, bool SPLIT, bool MIXED, bool XB>
 __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     const int KT = mt.K >> 8, lane = wp.lane;
     const uint32_t* codes[2] = {mt.codes + (size_t)wp.R[0] * KT * 384, mt.codes + (size_t)wp.R[1] * KT * 384};
@@ -674,7 +768,11 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
         wave_lds_sync();
         uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
         if (MIXED) mix_apply(r, wp, x0, x1);
-        if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
+        int nx = 0;                                       // bf16: x0, x1 enter as 2^nx times the activations
+        if (XB) {
+            nx = bf16_scale_exponent(dpp_row_max(bf16x2_absmax(x0, x1)));
+            x0 = bf16x2_to_f16x2(x0, nx); x1 = bf16x2_to_f16x2(x1, nx);
+        }
         // a DPP read needs two wait states after a vector-ALU write of the register
         asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));
         // All sixteen gathers of a unit are issued before its dot products, and the second
@@ -693,14 +791,29 @@ __device__ __forceinline__ void run_vq6_m1(const DecodeMat& mt, const WavePos& w
         __builtin_amdgcn_sched_barrier(0);
         // two accumulation chains (one per unit), interleaved, so that a dot product never waits
         // for the one issued just before it
-        acc1 = dot8_row_bcast<0>(acc1, x1, g[1][0]);
-        out[0] = dot8_row_bcast<0>(out[0], x0, g[0][0]);
-        acc1 = dot8_row_bcast<1>(acc1, x1, g[1][1]);
-        out[0] = dot8_row_bcast<1>(out[0], x0, g[0][1]);
-        acc1 = dot8_row_bcast<2>(acc1, x1, g[1][2]);
-        out[0] = dot8_row_bcast<2>(out[0], x0, g[0][2]);
-        acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
-        out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
+        if (XB) {
+            // the tile's products on their own, then into the output through the inverse scale
+            float p0 = 0.f, p1 = 0.f;
+            p1 = dot8_row_bcast<0>(p1, x1, g[1][0]);
+            p0 = dot8_row_bcast<0>(p0, x0, g[0][0]);
+            p1 = dot8_row_bcast<1>(p1, x1, g[1][1]);
+            p0 = dot8_row_bcast<1>(p0, x0, g[0][1]);
+            p1 = dot8_row_bcast<2>(p1, x1, g[1][2]);
+            p0 = dot8_row_bcast<2>(p0, x0, g[0][2]);
+            p1 = dot8_row_bcast<3>(p1, x1, g[1][3]);
+            p0 = dot8_row_bcast<3>(p0, x0, g[0][3]);
+            RWKVQ_DOT_RESULT_FENCE("+v"(p0), "+v"(p1));
+            out[0] += ldexpf(p0 + p1, -nx);
+        } else {
+            acc1 = dot8_row_bcast<0>(acc1, x1, g[1][0]);
+            out[0] = dot8_row_bcast<0>(out[0], x0, g[0][0]);
+            acc1 = dot8_row_bcast<1>(acc1, x1, g[1][1]);
+            out[0] = dot8_row_bcast<1>(out[0], x0, g[0][1]);
+            acc1 = dot8_row_bcast<2>(acc1, x1, g[1][2]);
+            out[0] = dot8_row_bcast<2>(out[0], x0, g[0][2]);
+            acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
+            out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
+        }
     };
     tile_pipeline<DEPTH, Vq6M1Regs>(SPLIT ? wp.nt : KT, load, compute);
     RWKVQ_DOT_RESULT_FENCE("+v"(out[0]), "+v"(acc1));
@@ -741,7 +854,7 @@ __device__ __forceinline__ void sq_dot_pairs(float (&acc)[3], uint32_t xp, uint3
     (sq_dot_pair<P>(acc, xp, w0, w1, w2, s0, s1, s2), ...);
 }
 
-template <int DEPTH, bool SPLIT = false, bool MIXED = false>
+template <int DEPTH, bool SPLIT, bool MIXED, bool XB>
 __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp, float (&out)[kRT]) {
     static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
@@ -759,7 +872,11 @@ __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp
     auto compute = [&](const SqM1Regs& r, int) {
         uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
         if (MIXED) mix_apply(r, wp, x0, x1);
-        if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
+        int nx = 0;                                       // bf16: x0, x1 enter as 2^nx times the activations
+        if (XB) {
+            nx = bf16_scale_exponent(dpp_row_max(bf16x2_absmax(x0, x1)));
+            x0 = bf16x2_to_f16x2(x0, nx); x1 = bf16x2_to_f16x2(x1, nx);
+        }
         asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));     // vector-ALU write -> DPP read
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -782,7 +899,7 @@ __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp
             const uint32_t szw = u == 0 ? r.sz[0].x : r.sz[0].y;
             const float s = f16_bits_to_f32((uint16_t)(szw & 0xFFFFu));
             const float z = f16_bits_to_f32((uint16_t)(szw >> 16));
-            out[0] = fmaf(s, fmaf(-z, Xp, S), out[0]);
+            out[0] = fmaf(XB ? ldexpf(s, -nx) : s, fmaf(-z, Xp, S), out[0]);
         }
     };
     tile_pipeline<DEPTH, SqM1Regs>(SPLIT ? wp.nt : KT, load, compute);
@@ -791,7 +908,7 @@ __device__ __forceinline__ void run_sq_m1(const DecodeMat& mt, const WavePos& wp
 
 struct Vq8M1Regs { uint4_t a[kRT]; uint4_t b[kRT]; uint4_t cb; XPairs x, xq; uint32_t mi; };
 
-template <int DEPTH, bool SPLIT = false, bool MIXED = false>
+template <int DEPTH, bool SPLIT, bool MIXED, bool XB>
 __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&out)[kRT]) {
     static_assert(kRT == 1, "one row tile per wavefront");
     const int KT = mt.K >> 8, lane = wp.lane;
@@ -813,7 +930,11 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
         wave_lds_sync();
         uint32_t x0 = r.x.p[0], x1 = r.x.p[1];
         if (MIXED) mix_apply(r, wp, x0, x1);
-        if (wp.xbf16) { x0 = bf16x2_to_f16x2(x0); x1 = bf16x2_to_f16x2(x1); }
+        int nx = 0;                                       // bf16: x0, x1 enter as 2^nx times the activations
+        if (XB) {
+            nx = bf16_scale_exponent(dpp_row_max(bf16x2_absmax(x0, x1)));
+            x0 = bf16x2_to_f16x2(x0, nx); x1 = bf16x2_to_f16x2(x1, nx);
+        }
         asm volatile("s_nop 1" : "+v"(x0), "+v"(x1));     // vector-ALU write -> DPP read
         uint4_t g[2][4];
 #pragma unroll
@@ -825,30 +946,73 @@ __device__ __forceinline__ void run_vq8_m1(const DecodeMat& mt, const WavePos& w
             g[u][3] = __builtin_bit_cast(uint4_t, vq8_operand(w.w, cb_lds));
         }
         __builtin_amdgcn_sched_barrier(0);
-        acc1 = dot8_row_bcast<0>(acc1, x1, g[1][0]);
-        out[0] = dot8_row_bcast<0>(out[0], x0, g[0][0]);
-        acc1 = dot8_row_bcast<1>(acc1, x1, g[1][1]);
-        out[0] = dot8_row_bcast<1>(out[0], x0, g[0][1]);
-        acc1 = dot8_row_bcast<2>(acc1, x1, g[1][2]);
-        out[0] = dot8_row_bcast<2>(out[0], x0, g[0][2]);
-        acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
-        out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
+        if (XB) {
+            // the tile's products on their own, then into the output through the inverse scale
+            float p0 = 0.f, p1 = 0.f;
+            p1 = dot8_row_bcast<0>(p1, x1, g[1][0]);
+            p0 = dot8_row_bcast<0>(p0, x0, g[0][0]);
+            p1 = dot8_row_bcast<1>(p1, x1, g[1][1]);
+            p0 = dot8_row_bcast<1>(p0, x0, g[0][1]);
+            p1 = dot8_row_bcast<2>(p1, x1, g[1][2]);
+            p0 = dot8_row_bcast<2>(p0, x0, g[0][2]);
+            p1 = dot8_row_bcast<3>(p1, x1, g[1][3]);
+            p0 = dot8_row_bcast<3>(p0, x0, g[0][3]);
+            RWKVQ_DOT_RESULT_FENCE("+v"(p0), "+v"(p1));
+            out[0] += ldexpf(p0 + p1, -nx);
+        } else {
+            acc1 = dot8_row_bcast<0>(acc1, x1, g[1][0]);
+            out[0] = dot8_row_bcast<0>(out[0], x0, g[0][0]);
+            acc1 = dot8_row_bcast<1>(acc1, x1, g[1][1]);
+            out[0] = dot8_row_bcast<1>(out[0], x0, g[0][1]);
+            acc1 = dot8_row_bcast<2>(acc1, x1, g[1][2]);
+            out[0] = dot8_row_bcast<2>(out[0], x0, g[0][2]);
+            acc1 = dot8_row_bcast<3>(acc1, x1, g[1][3]);
+            out[0] = dot8_row_bcast<3>(out[0], x0, g[0][3]);
+        }
     };
     tile_pipeline<DEPTH, Vq8M1Regs>(SPLIT ? wp.nt : KT, load, compute);
     RWKVQ_DOT_RESULT_FENCE("+v"(out[0]), "+v"(acc1));
     out[0] += acc1;
 }
 
-// MT = number of activation rows carried (1, 4 or 16 >= M).  D layout of the MFMA: lane holds
-// rows 4*(lane/16) + i, column lane%16.  With MT = 1 the SQ matrices still use the MFMA path
-// (its unpack is the cheapest per weight) while the VQ matrices use the vector-ALU path above,
-// whose LDS gathers are cheaper than ds_bpermute.
+// The batch-1 tile loop of a matrix's format; XB = the activations are bf16.
+template <int DEPTH, bool SPLIT, bool MIXED>
+__device__ __forceinline__ void run_m1(const DecodeMat& mt, const WavePos& wp, uint32_t* cb_lds, float (&part)[kRT]) {
+    if (wp.xbf16) {
+        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, SPLIT, MIXED, true>(mt, wp, part);
+        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, SPLIT, MIXED, true>(mt, wp, cb_lds, part);
+        else run_vq8_m1<DEPTH, SPLIT, MIXED, true>(mt, wp, cb_lds, part);
+    } else {
+        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, SPLIT, MIXED, false>(mt, wp, part);
+        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, SPLIT, MIXED, false>(mt, wp, cb_lds, part);
+        else run_vq8_m1<DEPTH, SPLIT, MIXED, false>(mt, wp, cb_lds, part);
+    }
+}
+// The same for batch 2..32.
+template <int MT, int DEPTH>
+__device__ __forceinline__ void run_batched(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
+                                            float4_t (&out)[groups_of(MT)][kBRT]) {
+    if (wp.xbf16) {
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, true>(mt, wp, xs, xsc, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, true>(mt, wp, xs, xsc, cb_lds, out);
+        else run_vq8<MT, DEPTH, true>(mt, wp, xs, xsc, cb_lds, out);
+    } else {
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, false>(mt, wp, xs, xsc, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, false>(mt, wp, xs, xsc, cb_lds, out);
+        else run_vq8<MT, DEPTH, false>(mt, wp, xs, xsc, cb_lds, out);
+    }
+}
+
+// MT = number of activation rows carried (1, 4, 16 or 32 >= M).  MT = 1 runs every format on the
+// vector ALU (run_*_m1); the others on the matrix cores, whose D layout is: lane holds batch rows
+// 4*(lane/16) + i of output column lane%16.
 template <int MT>
 __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : MT == 16 ? 2 : 1) decode_kernel(DecodeArgs a) {
     constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : 2;
     // batch > 1: two activation tiles shared by the workgroup; codebook slots per wavefront
     __shared__ __attribute__((aligned(16))) half_t xs[MT == 1 ? 8 : 2 * MT * kXStride];
     __shared__ __attribute__((aligned(1024))) uint32_t cb_all[4][MT == 1 ? 256 : 512];
+    __shared__ __attribute__((aligned(16))) float xsc[MT == 1 ? 4 : 2 * 16 * groups_of(MT)];   // bf16: inverse scales per tile and batch row
 
     // Which matrix does this workgroup belong to?  Lane i compares against the end of matrix i
     // (one load per wavefront from the argument block); the count of matrices that end at or
@@ -878,9 +1042,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
         float part[kRT];
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) part[rt] = 0.f;
-        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH>(mt, wp, part);
-        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH>(mt, wp, cb_all[wave], part);
-        else run_vq8_m1<DEPTH>(mt, wp, cb_all[wave], part);
+        run_m1<DEPTH, false, false>(mt, wp, cb_all[wave], part);
 #pragma unroll
         for (int rt = 0; rt < kRT; ++rt) {
             float v = part[rt];                    // sum the four column groups of each row
@@ -900,9 +1062,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
         for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) out[g][rt] = float4_t{0, 0, 0, 0};
-        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH>(mt, wp, xs, out);
-        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
-        else run_vq8<MT, DEPTH>(mt, wp, xs, cb_all[wave], out);
+        run_batched<MT, DEPTH>(mt, wp, xs, xsc, cb_all[wave], out);
         if (!live) return;
         // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 (of its group) of output column n
 #pragma unroll
@@ -957,9 +1117,7 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     }
     float part[kRT] = {0.f};
     if (wp.nt > 0) {
-        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true, MIXED>(mt, wp, part);
-        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, true, MIXED>(mt, wp, cb_all[wave], part);
-        else run_vq8_m1<DEPTH, true, MIXED>(mt, wp, cb_all[wave], part);
+        run_m1<DEPTH, true, MIXED>(mt, wp, cb_all[wave], part);
     }
     float v = part[0];                             // sum the four column groups of each row
     v += __shfl_xor(v, 16, 64);
@@ -1012,9 +1170,7 @@ __global__ void __launch_bounds__(768) decode_rkv_wkv_kernel(WkvFuseArgs a) {
     }
     float part[kRT] = {0.f};
     if (wp.nt > 0) {
-        if (mt.fmt == FMT_SQ3) run_sq_m1<DEPTH, true, false>(mt, wp, part);
-        else if (mt.fmt == FMT_VQ6) run_vq6_m1<DEPTH, true, false>(mt, wp, cb_all[wave], part);
-        else run_vq8_m1<DEPTH, true, false>(mt, wp, cb_all[wave], part);
+        run_m1<DEPTH, true, false>(mt, wp, cb_all[wave], part);
     }
     float v = part[0];                             // sum the four column groups of each row
     v += __shfl_xor(v, 16, 64);

@@ -25,9 +25,10 @@
 // Workgroup -> tile order: the m-tile index runs fastest, so workgroups that are dispatched
 // round-robin over the 8 XCDs keep one slice of x (256 rows) per XCD L2 when there are 8 m-tiles.
 #include "common.h"
+#include "../../include/rwkvq.h"
 
 #include <algorithm>
-#include <cstdlib>
+#include <atomic>
 #include <vector>
 
 namespace rwkvq {
@@ -613,14 +614,20 @@ __global__ void __launch_bounds__(256, 1) prefill_kernel(PfArgs a) {
 #undef CB8
 }
 
+// The kernels need more dynamic LDS than the default limit: raised once per kernel and device.  Two
+// threads that get here together both raise it, which is harmless.
 template <bool BF16, int FMT, int MF>
 static hipError_t launch_fmt_mf(const PfArgs& a, int wgs, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)prefill_kernel<BF16, FMT, MF>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, pf_lds_bytes(FMT));
+    static std::atomic<unsigned long long> raised{0ull};        // bit d: done on device d
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(raised.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute((const void*)prefill_kernel<BF16, FMT, MF>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, pf_lds_bytes(FMT));
         if (e != hipSuccess) return e;
-        attr_set = true;
+        raised.fetch_or(bit, std::memory_order_release);
     }
     hipLaunchKernelGGL((prefill_kernel<BF16, FMT, MF>), dim3(wgs), dim3(256), pf_lds_bytes(FMT), s, a);
     return hipGetLastError();
@@ -636,12 +643,10 @@ static hipError_t launch_fmt(const PfArgs& a, int wgs, int mf, hipStream_t s) {
 // 7B stack: the W tile is unpacked once per workgroup either way), i.e. costs 0.705 of it.  The
 // cheaper of the two wins: 128 rows for launches that would leave compute units without a tile
 // (one 4096 x 4096 matrix at M = 2048 is 128 tiles) and for short M.
-// RWKVQ_PREFILL_BM=128|256 in the environment overrides the choice (tests run both kernels).
+// rwkvq_set_option(RWKVQ_OPT_PREFILL_TILE_ROWS, 128 | 256) overrides the choice (tests run both kernels).
 static int pick_bm(int M, long long n_tiles) {
-    if (const char* e = std::getenv("RWKVQ_PREFILL_BM")) {
-        if (e[0] == '1') return 128;
-        if (e[0] == '2') return 256;
-    }
+    const int forced = option(RWKVQ_OPT_PREFILL_TILE_ROWS);
+    if (forced == 128 || forced == 256) return forced;
     const long long wg256 = n_tiles * ((M + 255) / 256), wg128 = n_tiles * ((M + 127) / 128);
     const double t256 = (double)((wg256 + 255) / 256), t128 = 0.705 * (double)((wg128 + 255) / 256);
     return t128 < t256 ? 128 : 256;

@@ -15,3 +15,18 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def options():
+    """Set process-wide library options for one test (rwkvq_set_option); restored afterwards."""
+    from paper_2505_03803_amd import binding as B
+    before = {}
+
+    def set_(option, value):
+        before.setdefault(option, B.rwkvq_get_option(option))
+        B.rwkvq_set_option(option, value)
+
+    yield set_
+    for option, value in before.items():
+        B.rwkvq_set_option(option, value)

@@ -23,8 +23,8 @@ def layer_7b():
 
 
 @pytest.fixture(autouse=True)
-def no_override(monkeypatch):
-    monkeypatch.delenv("RWKVQ_SMALL_BATCH_PATH", raising=False)
+def no_override(options):
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_AUTO)
 
 
 def test_batch_up_to_16_streams():
@@ -72,12 +72,34 @@ def test_rows_longer_than_the_streaming_kernels_hold():
     assert B.rwkvq_linear_dispatch_plan([sq(48, 20480 + 256)], 64) == [B.PATH_REFERENCE]
 
 
-def test_environment_override(monkeypatch):
-    monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", "mfma")
+def test_forced_path(options):
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_MATRIX_CORES)
     assert B.rwkvq_linear_dispatch_plan([sq(4096, 4096)], 32) == [B.PATH_MATRIX_CORES]
-    monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", "stream")
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_STREAM)
     assert B.rwkvq_linear_dispatch_plan([sq(256, 512)], 128) == [B.PATH_STREAM_PASSES]
     assert B.rwkvq_linear_dispatch_plan([sq(256, 512)], 129) == [B.PATH_MATRIX_CORES]      # beyond 128: no choice
+
+
+def test_estimate_constants_are_settable(options):
+    """The estimate's constants are one machine's; another machine's replace them through rwkvq_set_option."""
+    one = [sq(4096, 4096)]
+    assert B.rwkvq_linear_dispatch_plan(one, 64) == [B.PATH_STREAM_PASSES]
+    options(B.OPT_STREAM_WIDE_MIN_US, 200)                       # a machine whose streaming passes start slowly
+    assert B.rwkvq_linear_dispatch_plan(one, 64) == [B.PATH_MATRIX_CORES]
+    options(B.OPT_STREAM_WIDE_MIN_US, 0)                         # 0 = the default again
+    assert B.rwkvq_get_option(B.OPT_STREAM_WIDE_MIN_US) == 24
+    assert B.rwkvq_linear_dispatch_plan(one, 64) == [B.PATH_STREAM_PASSES]
+    options(B.OPT_MFMA_KSTEP_NS, 100)                            # much faster matrix-core steps
+    assert B.rwkvq_linear_dispatch_plan(one, 64) == [B.PATH_MATRIX_CORES]
+
+
+def test_option_rejects():
+    assert B.rwkvq_set_option(99, 1, check=False) == B.ERR_UNSUPPORTED
+    assert B.rwkvq_set_option(-1, 1, check=False) == B.ERR_UNSUPPORTED
+    assert B.rwkvq_set_option(B.OPT_SMALL_BATCH_PATH, 3, check=False) == B.ERR_UNSUPPORTED
+    assert B.rwkvq_set_option(B.OPT_PREFILL_TILE_ROWS, 64, check=False) == B.ERR_UNSUPPORTED
+    assert B.rwkvq_set_option(B.OPT_STREAM_WIDE_GBPS, -5, check=False) == B.ERR_UNSUPPORTED
+    assert B.lib().rwkvq_get_option(0, None) == B.ERR_NULL
 
 
 def test_plan_rejects():

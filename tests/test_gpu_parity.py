@@ -24,6 +24,8 @@ def acts(M, K, dtype, seed):
     return synth.gen_activations(np.random.default_rng(seed + 99), M, K, dtype)
 
 
+FORCE = {None: B.SMALL_BATCH_AUTO, "stream": B.SMALL_BATCH_STREAM, "mfma": B.SMALL_BATCH_MATRIX_CORES}
+
 SMALL = [("sq", 48, 768), ("sq", 256, 256), ("vq6", 256, 768), ("vq6", 512, 256), ("vq8", 256, 768),
          ("vq8", 512, 512)]
 
@@ -96,9 +98,9 @@ def test_decode_batch1_launch_shapes(fmt, N, K):
 @pytest.mark.parametrize("fmt,N,K", [("sq", 256, 768), ("vq6", 256, 768), ("vq8", 512, 512)])
 @pytest.mark.parametrize("M", [17, 256, 300])
 @pytest.mark.parametrize("xdt", ["bf16", "f16"])
-def test_prefill_small(fmt, N, K, M, xdt, monkeypatch):
+def test_prefill_small(fmt, N, K, M, xdt, options):
     print(f"prefill {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
-    monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", "mfma")     # M = 17 on the matrix cores, whatever the estimate says
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_MATRIX_CORES)     # M = 17 on the matrix cores, whatever the estimate says
     mat = make(fmt, N, K, 4)
     x = acts(M, K, xdt, M)
     y = G.gpu_gemm(B.upload(mat, native=True), x, xdt)
@@ -275,10 +277,9 @@ def test_config5_prefill_layer_sampled_rows():
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
 @pytest.mark.parametrize("xdt", ["bf16", "f16"])
 @pytest.mark.parametrize("N,K,M", [(256, 512, 64), (512, 768, 200), (256, 1024, 256), (512, 512, 300), (768, 256, 129)])
-def test_prefill_both_tile_heights(fmt, xdt, N, K, M, monkeypatch):
+def test_prefill_both_tile_heights(fmt, xdt, N, K, M, options):
     """The matrix-core kernel exists with 256 and with 128 rows of x per workgroup (the launcher picks
-    by how many tiles a launch has); both are forced in turn through the library's environment
-    override.  Same order of summation over k: the same bits, and each against the oracle."""
+    by how many tiles a launch has); both are forced in turn through rwkvq_set_option.  Same order of summation over k: the same bits, and each against the oracle."""
     torch = G.torch_()
     mat = make(fmt, N, K, 7)
     x = acts(M, K, xdt, M + 1)
@@ -286,7 +287,7 @@ def test_prefill_both_tile_heights(fmt, xdt, N, K, M, monkeypatch):
     ys = {}
     for bm in ("128", "256"):
         print(f"prefill tile height {bm}: {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
-        monkeypatch.setenv("RWKVQ_PREFILL_BM", bm)
+        options(B.OPT_PREFILL_TILE_ROWS, int(bm))
         ys[bm] = G.gpu_gemm(dm, x, xdt)
     assert np.array_equal(ys["128"], ys["256"])
     # against the oracle fed the rounding of the weights the kernel declares (the gate against exact
@@ -298,7 +299,7 @@ def test_prefill_both_tile_heights(fmt, xdt, N, K, M, monkeypatch):
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
 @pytest.mark.parametrize("xdt", ["bf16", "f16"])
 @pytest.mark.parametrize("N,K,M", [(512, 2048, 17), (256, 4096, 40), (768, 1024, 128), (256, 512, 100)])
-def test_small_batch_both_paths(fmt, xdt, N, K, M, monkeypatch):
+def test_small_batch_both_paths(fmt, xdt, N, K, M, options):
     """16 < M <= 128 runs either on the matrix cores (M padded to 128 rows) or as ceil(M / 32) passes
     of the streaming kernels over row blocks of x (the 17..32-row instance, then one for the rest),
     whichever the dispatcher estimates cheaper.  Both
@@ -310,18 +311,93 @@ def test_small_batch_both_paths(fmt, xdt, N, K, M, monkeypatch):
     ys = {}
     for path, fed in (("stream", None), ("mfma", xdt)):
         print(f"small batch via {path}: {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
-        monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", path)
+        options(B.OPT_SMALL_BATCH_PATH, FORCE[path])
         ys[path] = G.gpu_gemm(dm, x, xdt)
         asfed = orc.linear(mat, orc.widen(x, xdt), "f64", weight_round=fed)
         assert G.err_g2(ys[path], asfed) <= 2e-5, path
-    monkeypatch.delenv("RWKVQ_SMALL_BATCH_PATH")
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_AUTO)
     free = G.gpu_gemm(dm, x, xdt)
     assert np.array_equal(free, ys["stream"]) or np.array_equal(free, ys["mfma"])
     # fp16 output as well (the row blocks of y are addressed in its element size)
-    monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", "stream")
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_STREAM)
     y16 = G.gpu_gemm(dm, x, xdt, B.F16)
     back = orc.widen(y16, "f16").astype(np.float64)
     assert np.abs(back - ys["stream"]).max() <= 2.0 ** -10 * np.abs(ys["stream"]).max()
+
+
+def wide_range_rows(M, K, seed):
+    """bf16 activation rows whose magnitudes leave what fp16 holds (|x| up to 65504, exact down to 2^-17):
+    row m follows pattern m % 6 - the whole row at 7e4, the whole row at 1e-8, N(0, 1) with 1 % of the
+    entries at +-7e4, N(0, 1) with 1 % of the entries at 1e-8 scale, the first half of the columns at 7e4
+    and the second at 1e-8, and squared-ReLU values max(300 g, 0)^2 (the input of W'_v in Eq. "channel
+    mixing o": many exact zeros, values up to 1e6)."""
+    rng = np.random.default_rng(seed)
+    g = rng.standard_normal((M, K))
+    for m in range(M):
+        p = m % 6
+        if p == 0:
+            g[m] *= 7e4
+        elif p == 1:
+            g[m] *= 1e-8
+        elif p == 2:
+            pick = rng.random(K) < 0.01
+            g[m, pick] = np.sign(g[m, pick]) * 7e4
+        elif p == 3:
+            pick = rng.random(K) < 0.01
+            g[m, pick] *= 1e-8
+        elif p == 4:
+            g[m, : K // 2] *= 7e4
+            g[m, K // 2:] *= 1e-8
+        else:
+            g[m] = np.maximum(300.0 * g[m], 0.0) ** 2
+    return synth.f32_to_bf16_bits(g.astype(np.float32))
+
+
+def rowwise_g2(y, ref):
+    return max(G.err_g2(y[m:m + 1], ref[m:m + 1]) for m in range(y.shape[0]))
+
+
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+@pytest.mark.parametrize("M", [1, 6, 16, 32, 48])
+def test_bf16_activations_of_any_magnitude(fmt, M, options):
+    """Every finite bf16 activation is in contract.  The streaming kernels multiply fp16 operands: they
+    must bring the activations into fp16's range with exact scales, so that a row of tiny values, a
+    row of huge ones and rows that mix both all come out as the oracle computes them - row by row,
+    since the rows of a batch are independent requests.  M = 48 runs both ways the dispatcher has
+    for it (two streaming passes; the matrix cores, which multiply bf16 directly)."""
+    N, K = 512, 1024
+    mat = make(fmt, N, K, 21)
+    dm = B.upload(mat, native=True)
+    if M == 1:
+        xs = [wide_range_rows(6, K, 50)[p:p + 1] for p in range(6)]        # each pattern as a call of its own
+    else:
+        xs = [wide_range_rows(M, K, 50 + M)]
+    for path in (("stream", "mfma") if M > 16 else ("stream",)):
+        options(B.OPT_SMALL_BATCH_PATH, FORCE[path])
+        for x in xs:
+            print(f"bf16 range {fmt} M={M} via {path}", flush=True)
+            y = G.gpu_gemm(dm, x, "bf16")
+            assert np.all(np.isfinite(y))
+            ref = orc.linear(mat, orc.widen(x, "bf16"), "f64", weight_round="bf16" if path == "mfma" else None)
+            assert rowwise_g2(y, ref) <= 2e-5, (path, rowwise_g2(y, ref))
+
+
+@pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
+def test_bf16_activations_of_any_magnitude_grouped_batch1(fmt):
+    """The same through the batch-1 kernel that gives a wavefront a whole row tile (launches of 2048 row
+    tiles and more; the test above runs the split-K kernel)."""
+    N, K = 32768, 512
+    mat = make(fmt, N, K, 22)
+    dm = B.upload(mat, native=True)
+    for p in range(6):
+        print(f"bf16 range grouped {fmt} pattern {p}", flush=True)
+        x = wide_range_rows(6, K, 60)[p:p + 1]
+        y = G.gpu_gemm(dm, x, "bf16")
+        ref = orc.linear(mat, orc.widen(x, "bf16"), "f64")
+        # 1e-4, not 2e-5: with a few entries 7e4 times the rest (pattern 2) an SQ group's sum q.x and its
+        # z * sum(x) are each 2^-24-accurate relative to 7e4 * 7 while their difference, the group's
+        # contribution, is several times smaller; the scale of the activations plays no part in that
+        assert G.err_g2(y, ref) <= 1e-4, p
 
 
 @pytest.mark.parametrize("M", [17, 50, 128])
@@ -347,7 +423,7 @@ def test_small_batch_rows_not_multiple_of_256(M):
             G.check_outputs(got, m, x, "bf16", fed="bf16")
 
 
-def test_dispatch_randomized_batches_and_paths(monkeypatch):
+def test_dispatch_randomized_batches_and_paths(options):
     """Seeded sweep over batch sizes 1..300, call compositions and the small-batch override: every
     output against the oracle with the weights as the reported path feeds them (rwkvq_linear_dispatch_plan:
     exact for the streaming kernels and the reference kernel, rounded to the type of x on the matrix
@@ -367,10 +443,7 @@ def test_dispatch_randomized_batches_and_paths(monkeypatch):
                 N = 256
             mats.append(make(fmt, N, K, 100 + 7 * case + j))
         override = (None, "stream", "mfma")[int(rng.integers(0, 3))]
-        if override:
-            monkeypatch.setenv("RWKVQ_SMALL_BATCH_PATH", override)
-        else:
-            monkeypatch.delenv("RWKVQ_SMALL_BATCH_PATH", raising=False)
+        options(B.OPT_SMALL_BATCH_PATH, FORCE[override])
         dms = [B.upload(m, native=True) for m in mats]
         descs = [d.desc() for d in dms]
         xs = [acts(M, m.K, xdt, 1000 + case * 10 + j) for j, m in enumerate(mats)]
