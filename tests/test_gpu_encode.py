@@ -45,6 +45,22 @@ def test_sq_encode_bit_exact(dtype, N, K):
     assert np.array_equal(dm.codes.cpu().numpy().view(np.uint32), codes)
 
 
+def test_sq_encode_range_below_the_resolution_of_an_fp16_scale():
+    """Groups whose range is positive but rounds to an fp16 scale of zero take s = 1, z = -min; the group
+    just above takes the smallest fp16 subnormal as its scale.  Hand-built binary32 groups (the same as
+    the oracle's CPU pin, whose expected values are written out there), bit for bit."""
+    from paper_2505_03803_amd import binding as B
+    from test_oracle_encode import subresolution_groups
+    W, want_s, want_z, want_q = subresolution_groups()
+    dm = B.sq_encode(dev(W, "f32"), B.F32)
+    codes, s16, z16 = E.sq_encode_packed(W)
+    assert np.array_equal(s16[:, 0], want_s.view(np.uint16)) and np.array_equal(z16[:, 0], want_z.view(np.uint16))
+    assert np.array_equal(dm.scales.cpu().numpy().view(np.uint16), s16)
+    assert np.array_equal(dm.zeros.cpu().numpy().view(np.uint16), z16)
+    assert np.array_equal(dm.codes.cpu().numpy().view(np.uint32), codes)
+    assert np.array_equal(codes, E.pack_fields(want_q, 3))
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("kbits,N,K", [(6, 256, 256), (6, 512, 768), (8, 256, 512)])
 def test_vq_assign_bit_exact(dtype, kbits, N, K):

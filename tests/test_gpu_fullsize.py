@@ -88,20 +88,20 @@ def test_config4_full_stack_prefill_launches():
         xb = xs[i][idx].cpu().numpy().view(np.uint16)
         x = orc.widen(xb, "bf16")
         y = ys[i][idx].cpu().numpy().astype(np.float64)
+        ymax = float(ys[i].abs().max())
         for r0, sub in slices:
             ref = orc.linear(sub, x, "f64", weight_round="bf16")
             err = np.abs(y[:, r0:r0 + 16] - ref).max() / max(np.abs(ref).max(), 1e-30)
             worst = max(worst, err)
             assert err <= 2e-5, (name, r0, err)
-            # against the exact binary32 weights the difference is the bf16 rounding of the weights;
-            # the 2e-3 bar is relative to the largest output of the whole matrix, which a 4 x 16
-            # sample underestimates, so the sample is held to twice the bar
+            # against the exact binary32 weights the difference is the bf16 rounding of the weights: the
+            # 2e-3 bar, relative to the largest output of the whole matrix (taken on the device)
             exact = orc.linear(sub, x, "f64")
-            g1 = np.abs(y[:, r0:r0 + 16] - exact).max() / np.abs(exact).max()
+            g1 = np.abs(y[:, r0:r0 + 16] - exact).max() / ymax
             worst_g1 = max(worst_g1, g1)
-            assert g1 <= 4e-3, (name, r0, g1)
+            assert g1 <= G.TOL, (name, r0, g1)
     print(f"config 4 full stack, {len(checks)} matrices x 3 row tiles x 4 tokens: worst as-fed error {worst:.2e}, "
-          f"worst error against exact weights (sample-normalised) {worst_g1:.2e}", flush=True)
+          f"worst error against exact weights over max|y| of the matrix {worst_g1:.2e}", flush=True)
 
 
 @pytest.mark.parametrize("M", [1, 16])
@@ -152,14 +152,47 @@ def test_config5_full_stack_prefill():
     print("config 5 M=4096: 384 matrices and activations resident", flush=True)
     B.rwkvq_linear_dispatch(B.DispatchTable([d.desc() for d in dms], xs, ys), M, B.BF16, B.F32)
     torch.cuda.synchronize()
-    worst = 0.0
+    worst, worst_g1 = 0.0, 0.0
     idx = torch.from_numpy(mrows).cuda()
     for i, name, slices in checks:
         x = orc.widen(xs[i][idx].cpu().numpy().view(np.uint16), "bf16")
         y = ys[i][idx].cpu().numpy().astype(np.float64)
+        ymax = float(ys[i].abs().max())
         for r0, sub in slices:
             ref = orc.linear(sub, x, "f64", weight_round="bf16")
             err = np.abs(y[:, r0:r0 + 16] - ref).max() / max(np.abs(ref).max(), 1e-30)
             worst = max(worst, err)
             assert err <= 2e-5, (name, r0, err)
-    print(f"config 5 prefill full stack, {len(checks)} matrices x 3 row tiles x 3 tokens: worst as-fed error {worst:.2e}", flush=True)
+            exact = orc.linear(sub, x, "f64")            # exact binary32 weights: the 2e-3 bar over max|y| of the matrix
+            g1 = np.abs(y[:, r0:r0 + 16] - exact).max() / ymax
+            worst_g1 = max(worst_g1, g1)
+            assert g1 <= G.TOL, (name, r0, g1)
+    print(f"config 5 prefill full stack, {len(checks)} matrices x 3 row tiles x 3 tokens: worst as-fed error {worst:.2e}, "
+          f"worst error against exact weights over max|y| of the matrix {worst_g1:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("config,w_dtype", [(3, "f32"), (4, "bf16"), (5, "f32")])
+def test_dequant_bit_exact_every_matrix(config, w_dtype):
+    """Deq(W) of every matrix of a full stack, streamed one matrix at a time through the native layout
+    (prepack, then the library's definition kernel) and compared with the oracle bit for bit: all 256
+    matrices of configuration 3 in binary32, all 256 of configuration 4 rounded to bf16 (what the
+    matrix cores are fed), all 384 of configuration 5 (SQ, 6- and 8-bit VQ) in binary32."""
+    import sys
+    torch = G.torch_()
+    n, weights = 0, 0
+    for mat, _ in synth.stack(config, 1, with_activations=False):
+        dm = B.upload(mat, native=True)
+        want = orc.dequant(mat)
+        if w_dtype == "f32":
+            got = G.gpu_dequant(dm)
+            same = np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        else:
+            got = G.gpu_dequant(dm, B.BF16)
+            same = np.array_equal(orc.widen(got, "bf16").view(np.uint32), orc.round_weights(want, "bf16").view(np.uint32))
+        assert same, (config, n, mat.name, mat.kind, mat.N, mat.K)
+        n += 1
+        weights += mat.N * mat.K
+        del dm, got, want
+        if n % 32 == 0:
+            print(f"config {config}: {n} matrices bit-exact ({weights / 1e9:.2f} G weights)", file=sys.__stderr__, flush=True)
+    assert n == (384 if config == 5 else 256)

@@ -86,6 +86,41 @@ def test_sq_constant_group_and_scale_definition():
     assert s16.view(np.float16)[0, 0] == 0.5 and z16.view(np.float16)[0, 0] == 2.0
 
 
+def subresolution_groups():
+    """Groups whose range is positive but too small for an fp16 scale: (max - min)/7 rounds to the
+    fp16 zero exactly when it is at most 2^-25 (the tie 2^-25 itself goes to the even neighbour 0).
+    Hand values, every number a power of two or a small multiple:
+      row 0: 2^-8 and 2^-8 + 2^-30 alternating        -> s = 1, z = -2^-8, all codes 0
+      row 1: 0 and 7 * 2^-25 alternating (the tie)      -> s = 1, z = 0, all codes 0
+      row 2: 0 and 7 * 2^-25 * (1 + 2^-20): just above  -> s = 2^-24 (smallest fp16 subnormal), z = 0,
+             codes 0 and rne(3.5 (1 + 2^-20)) = 4
+      row 3: -3 * 2^-30 and 0                            -> s = 1, z = 3 * 2^-30 -> fp16 0, all codes 0"""
+    W = np.zeros((4, 128), np.float32)
+    W[0] = 2.0 ** -8; W[0, 1::2] = 2.0 ** -8 + 2.0 ** -30
+    W[1, 1::2] = 7 * 2.0 ** -25
+    W[2, 1::2] = np.float32(7 * 2.0 ** -25) * np.float32(1 + 2.0 ** -20)
+    W[3, 0::2] = -3 * 2.0 ** -30
+    want_s = np.array([1.0, 1.0, 2.0 ** -24, 1.0], np.float16)
+    want_z = np.array([-(2.0 ** -8), -0.0, -0.0, 0.0], np.float16)      # z = -min / s: a minimum of +0 gives -0
+    want_q = np.zeros((4, 128), np.uint8); want_q[2, 1::2] = 4
+    return W, want_s, want_z, want_q
+
+
+def test_sq_range_below_the_resolution_of_an_fp16_scale():
+    W, want_s, want_z, want_q = subresolution_groups()
+    assert W[0, 1] != W[0, 0] and W[2, 1] > W[1, 1]          # the inputs really differ in binary32
+    q, s16, z16 = E.sq_encode(W)
+    assert np.array_equal(s16[:, 0], want_s.view(np.uint16))
+    assert np.array_equal(z16[:, 0], want_z.view(np.uint16))
+    assert np.array_equal(q, want_q)
+    # what the decoder returns: the group's minimum for rows 0, 1, 3 (error at most the range), and
+    # for row 2 the grid {0, 4 * 2^-24}: the error stays within half a step of the stored scale
+    mat = synth.QMatrix("t", "sq", 4, 128, 0, E.pack_fields(q, 3), s16, z16, None)
+    What = orc.dequant(mat).astype(np.float64)
+    assert np.all(What[0] == 2.0 ** -8) and np.all(What[1] == 0.0) and np.all(What[3] == 0.0)
+    assert np.all(np.abs(What - W) <= np.array([2.0 ** -30, 7 * 2.0 ** -25, 2.0 ** -25, 3 * 2.0 ** -30])[:, None] * (1 + 1e-6))
+
+
 def brute_force_assign(v, cb):
     best, bestd = 0, None
     for e in range(cb.shape[0]):
