@@ -4,16 +4,22 @@
 A step is one pass of the whole RWKV-6-7B-shaped layer stack (32 layers x 8 matrices, each SQ or VQ
 by a seeded coin flip) through rwkvq_linear_dispatch:
 
-  * decode leg (the headline `value`): batch 1, fp16 activations, one independent activation
-    vector per matrix; metric = packed weight bytes read per second (GB/s) and the fraction of
-    the 8 TB/s HBM peak;
-  * prefill leg (reported under "prefill"): the same matrix recipe at M = 2048 tokens, bf16
-    activations, bf16 MFMA with binary32 accumulate; metric = 2*M*N*K FLOP per second and the
-    fraction of the 2.5 PFLOP/s dense bf16 peak.
+  * headline (`value`): batch 1, fp16 activations, one independent activation vector per matrix,
+    exactly --steps timed steps after --warmup untimed ones; metric = packed weight bytes read per second
+    (GB/s) and the fraction of the 8 TB/s HBM peak.  `steady_state` holds the same step timed over a long
+    region of its own (run first: the device leaves the clock transient that follows idle there);
+  * `decode_batched`: the same matrices at batch 4, 16, 32, 64; `sequential_step`: in data-flow order;
+  * `config1`, `config2`: the single-matrix configurations, cache-hot, HBM-cold (rotated copies) and grouped;
+  * `prefill`: the same matrix recipe at M = 2048 tokens, bf16 activations, bf16 MFMA with binary32
+    accumulate; metric = 2*M*N*K FLOP per second and the fraction of the 2.5 PFLOP/s dense bf16 peak;
+  * `config5`: the 14B-class stack (48 layers, d = 5120, SQ / 6-bit VQ / 8-bit VQ, bf16 activations) at
+    batch 1 and 16 and as a prefill of M = 4096 tokens;
+  * `proxy`, `encode`, `mu`: the quantization-time kernels.
 
-All inputs are resident in HBM before the timed region.  Timing uses HIP events on the stream
-the kernels are launched on.  The CPU oracle is timed on the host cores on the same decode
-workload as a reported baseline.  Prints ONE JSON line.
+All inputs are resident in HBM before a timed region.  Timing uses HIP events on the stream the kernels
+are launched on (torch's current stream), one event per step.  The CPU oracle is timed on the host cores
+on the decode workload (`cpu_baseline`) and on a sample of the prefill workload as reported baselines.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -32,12 +38,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 DECODE_KERNEL = "rwkvq::decode_kernel<1>"
+DECODE16_KERNEL = "rwkvq::decode_kernel<16>"
 PREFILL_KERNEL = "rwkvq::prefill_kernel<true, FMT, 8>"   # bf16; one instantiation per weight format
 PROXY_KERNEL = "rwkvq::proxy_set_kernel"
 DECODE_MATS_PER_LAUNCH = 256
-# HBM traffic of one decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch),
-# scaled by what the same counters read for a plain 1 GiB copy; see profiles/decode_hbm_traffic_config3.txt.
-DECODE_TRAFFIC_BYTES_PER_LAUNCH = 2806.7e6
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each scaled by what the
+# same counter reads for a plain 1 GiB copy (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000 on this image).  Counter runs
+# are separate runs of this file (commands in the named summaries under profiles/); the figures are theirs, for the
+# default workload only, and are not re-measured by the run that prints them.
+TRAFFIC = {
+    "decode_config3": (2806.7e6, "profiles/decode_hbm_traffic_config3.txt"),
+    "prefill_config4": (8.87e9, "profiles/prefill_and_mix_hbm_traffic.txt"),
+    "proxy_8_layers": (3495.6e6, "profiles/proxy_kernel_trace_and_traffic_7b_layers.txt"),
+    "mix_per_call": (75.7e6, "profiles/prefill_and_mix_hbm_traffic.txt"),
+}
+
+
+def traffic(key, applies=True):
+    """(bytes per launch | None, source) for a roofline record."""
+    return (TRAFFIC[key][0] if applies else None), TRAFFIC[key][1]
 
 
 def log(*a):
@@ -499,23 +518,165 @@ def prefill_block_step(pf, n_layers, M):
                     "time-parallel wkv with its gate, squared ReLU, output gate; value counts the GEMM FLOP only"}
 
 
+class TimedRegion:
+    """W untimed steps, then exactly K steps bracketed by synchronize + HIP events on the current stream
+    (one event per step).  The steps are enqueued by the constructor; `result()` waits for them and reads
+    the events.  Enqueueing a second region before reading the first keeps the device busy between them:
+    reading some thousand events takes the host tens of milliseconds, and after an idle gap of that length
+    the device runs its next ~100 decode steps through a clock transient."""
+
+    def __init__(self, run, steps: int, warmup: int):
+        import torch
+        for _ in range(warmup):
+            run()
+        torch.cuda.synchronize()
+        self.steps = steps
+        self.ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        self.t0 = time.perf_counter()
+        self.ev[0].record()
+        for i in range(steps):
+            run()
+            self.ev[i + 1].record()
+        self.res = None
+
+    def result(self):
+        """(total ms over the K steps, per-step ms list, host wall ms)"""
+        import torch
+        if self.res is None:
+            self.ev[-1].synchronize()
+            wall_ms = (time.perf_counter() - self.t0) * 1e3
+            torch.cuda.synchronize()
+            ev = self.ev
+            self.res = (ev[0].elapsed_time(ev[-1]), [ev[i].elapsed_time(ev[i + 1]) for i in range(self.steps)], wall_ms)
+        return self.res
+
+
 def time_steps(run, steps: int, warmup: int):
-    """W untimed steps, then exactly K steps bracketed by synchronize + HIP events on the current
-    stream.  Returns (total ms over K steps, per-step ms list)."""
+    return TimedRegion(run, steps, warmup).result()
+
+
+def slices_of(per, n=10):
+    return [round(float(np.mean(c)), 4) for c in np.array_split(np.asarray(per), n)] if len(per) >= n else None
+
+
+def hbm_roofline(kernel, bytes_per_step, ms, launches=1, traffic_key=None, traffic_applies=True, note=None):
+    """Roofline record of an HBM-bound leg: achieved = algorithmic bytes of one launch / average launch
+    duration (HIP events on the launch stream around each step of the timed region, / launches per step)."""
+    r = {"kernel": kernel, "bound": "hbm", "achieved": bytes_per_step / launches / (ms / launches * 1e-3) / 1e9,
+         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_per_step / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+         "traffic": None, "algorithmic_bytes_per_launch": bytes_per_step / launches, "avg_launch_ms": ms / launches}
+    if traffic_key:
+        r["traffic"], r["traffic_source"] = traffic(traffic_key, traffic_applies)
+    if note:
+        r["note"] = note
+    return r
+
+
+def decode_leg(stack, M, steps, warmup, kernel, traffic_key=None, traffic_applies=True, y_dtype=None, enqueue_only=False):
+    """Time `steps` grouped dispatches of a resident stack at batch M after `warmup` untimed ones.  With
+    enqueue_only the steps are enqueued and a function that returns the record is handed back."""
+    from paper_2505_03803_amd import binding as B
+    yd = B.F16 if y_dtype is None else y_dtype
+    run = lambda: B.rwkvq_linear_dispatch(stack["table"], M, stack["x_dtype"], yd)
+    region = TimedRegion(run, steps, warmup)
+    launches = (stack["n_mats"] + DECODE_MATS_PER_LAUNCH - 1) // DECODE_MATS_PER_LAUNCH
+    wbytes = stack["wbytes"]
+
+    def record():
+        total_ms, per, wall_ms = region.result()
+        ms = total_ms / steps
+        gbs = wbytes / (ms * 1e-3) / 1e9
+        return {"value": gbs, "unit": "GB/s", "steps": steps, "warmup": warmup, "ms_per_step": ms,
+                "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS, "tokens_per_s": M * 1e3 / ms,
+                "ms_per_step_min": min(per), "ms_per_step_median": float(np.median(per)),
+                "ms_per_step_slices": slices_of(per), "wall_ms_per_step": wall_ms / steps,
+                "launches_per_step": launches,
+                "roofline": hbm_roofline(kernel, wbytes, ms, launches, traffic_key, traffic_applies)}
+    return record if enqueue_only else record()
+
+
+def with_batch(stack, M, y_dtype):
+    """The same resident matrices with fresh activations / outputs for batch M (drawn on the GPU)."""
     import torch
-    for _ in range(warmup):
-        run()
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-    t0 = time.perf_counter()
-    ev[0].record()
-    for i in range(steps):
-        run()
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
-    return ev[0].elapsed_time(ev[steps]), per, wall_ms
+    from paper_2505_03803_amd import binding as B
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7000 + M)
+    tdt = torch.bfloat16 if stack["x_dtype"] == B.BF16 else torch.float16
+    xs = [torch.randn((M, int(d.K)), device="cuda", generator=gen, dtype=torch.float32).to(tdt).view(torch.int16) for d in stack["descs"]]
+    ys = [torch.empty((M, int(d.N)), dtype=torch.float32 if y_dtype == B.F32 else torch.int16, device="cuda") for d in stack["descs"]]
+    out = dict(stack)
+    out.update(table=B.DispatchTable(stack["descs"], xs, ys), keep=(stack["keep"][0], xs, ys), ys=ys,
+               flops=sum(2 * M * int(d.N) * int(d.K) for d in stack["descs"]))
+    return out
+
+
+def single_matrix_legs(config, min_copies, steps, warmup):
+    """Configurations 1 and 2: ONE matrix, batch 1.  Its working set (0.4 / 6.4 MB) is far below the 256 MB
+    memory-side cache, so three figures: cache-hot (the same buffers every call), HBM-cold (rotating through
+    `min_copies` copies at distinct addresses, more than twice that cache in all, one call per copy) and
+    grouped (all copies in one rwkvq_linear_dispatch: a lone call of 0.05 / 0.8 us of traffic measures launch
+    latency, not the kernel).  Only the cold figures say anything about HBM."""
+    import torch
+    from paper_2505_03803_amd import binding as B
+    from paper_2505_03803_amd import synth
+    mat, x = (synth.config1 if config == 1 else synth.config2)(1)
+    dm0 = B.upload(mat, native=True)
+    clone = lambda t: None if t is None else t.clone()
+    dms = [dm0] + [B.DeviceMatrix(dm0.kind, dm0.layout, dm0.N, dm0.K, dm0.kbits, clone(dm0.codes), clone(dm0.scales), None,
+                                  clone(dm0.codebooks), dm0.packed_bytes) for _ in range(min_copies - 1)]
+    xd = [torch.from_numpy(x.view(np.int16)).cuda() for _ in range(min_copies)]
+    yd = [torch.empty((1, mat.N), dtype=torch.int16, device="cuda") for _ in range(min_copies)]
+    descs = [d.desc() for d in dms]
+    singles = [B.DispatchTable([descs[i]], [xd[i]], [yd[i]]) for i in range(min_copies)]
+    grouped = B.DispatchTable(descs, xd, yd)
+    wb = mat.packed_bytes
+    res = {"workload": ("configs[0]: one SQ matrix 1024 x 1024, 3-bit g128" if config == 1 else
+                        "configs[1]: one VQ matrix 4096 x 4096, d=2, 6-bit indices, 256 x 256 blocks") + ", batch 1, fp16 activations",
+           "weight_bytes": wb, "copies": min_copies, "rotated_set_bytes": wb * min_copies}
+    # cache-hot: the same matrix every call
+    tot, per, _ = time_steps(lambda: B.rwkvq_linear_dispatch(singles[0], 1, B.F16, B.F16), steps, warmup)
+    ms = tot / steps
+    res["cache_hot"] = {"ms_per_call": ms, "value": wb / (ms * 1e-3) / 1e9, "unit": "GB/s", "calls": steps,
+                        "note": "launch-latency bound; served by the caches, not a statement about HBM"}
+    # HBM-cold: one call per copy, rotating
+    it = [0]
+    def rot():
+        B.rwkvq_linear_dispatch(singles[it[0] % min_copies], 1, B.F16, B.F16)
+        it[0] += 1
+    n_calls = max(steps, min_copies)
+    tot, per, _ = time_steps(rot, n_calls, min(warmup, min_copies))
+    ms = tot / n_calls
+    res["hbm_cold_rotated"] = {"ms_per_call": ms, "value": wb / (ms * 1e-3) / 1e9, "unit": "GB/s", "calls": n_calls,
+                               "pct_hbm_peak": 100.0 * wb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                               "note": "one launch per call on cold data: bound by launch latency (%.1f us of traffic at peak)" % (wb / 8e12 * 1e6)}
+    # grouped: all copies in one dispatch
+    g_steps = max(20, steps // 20)
+    tot, per, _ = time_steps(lambda: B.rwkvq_linear_dispatch(grouped, 1, B.F16, B.F16), g_steps, 5)
+    ms = tot / g_steps
+    launches = (min_copies + DECODE_MATS_PER_LAUNCH - 1) // DECODE_MATS_PER_LAUNCH
+    res["grouped"] = {"ms_per_step": ms, "value": wb * min_copies / (ms * 1e-3) / 1e9, "unit": "GB/s", "steps": g_steps,
+                      "pct_hbm_peak": 100.0 * wb * min_copies / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "launches_per_step": launches,
+                      "roofline": hbm_roofline(DECODE_KERNEL, wb * min_copies, ms, launches)}
+    return res
+
+
+def cpu_baseline_prefill(n_rows=256, M=2048, n_layers_total=32):
+    """The oracle on a bounded sample of the prefill workload: the 8 matrices of the first layer of the
+    configuration-4 stack, the first n_rows of the M token rows (dequantize to binary32, naive binary32 sums)."""
+    from oracle import rwkvq_oracle as orc
+    from paper_2505_03803_amd import synth
+    secs, flop = 0.0, 0
+    for mat, x in synth.stack(4, n_rows, n_layers=1):
+        xf = orc.widen(x, "bf16")
+        t = time.perf_counter()
+        orc.linear(mat, xf, "f32")
+        secs += time.perf_counter() - t
+        flop += 2 * n_rows * mat.N * mat.K
+    return {"value": flop / secs / 1e12, "unit": "TFLOP/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"first layer (8 matrices) of the configuration-4 stack, first {n_rows} of {M} token rows: "
+                      f"{flop / 1e9:.1f} GFLOP in {secs:.2f} s of oracle time",
+            "extrapolated_s_per_step": secs * (M / n_rows) * n_layers_total,
+            "extrapolation": f"linear in rows and layers: x {M // n_rows} rows x {n_layers_total} layers (an extrapolation, not a measurement)"}
 
 
 def cpu_baseline(n_layers, min_seconds=10.0, max_passes=8):
@@ -541,13 +702,17 @@ def cpu_baseline(n_layers, min_seconds=10.0, max_passes=8):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # Defaults: long enough to time the steady state.  After idle the first ~100 decode steps run
-    # through a power-management transient (step time 0.47 -> 0.69 -> 0.49 ms on the 7B stack).
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--steps", type=int, default=200, help="timed steps of the headline decode leg")
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--layers", type=int, default=32, help="layers of the stack (32 = the full workload)")
     ap.add_argument("--prefill-steps", type=int, default=40)
     ap.add_argument("--prefill-warmup", type=int, default=10)
+    ap.add_argument("--steady-steps", type=int, default=2000, help="timed steps of the steady-state decode leg")
+    ap.add_argument("--steady-warmup", type=int, default=500)
+    ap.add_argument("--skip-steady", action="store_true")
+    ap.add_argument("--skip-single", action="store_true", help="skip the single-matrix legs (configurations 1 and 2)")
+    ap.add_argument("--skip-config5", action="store_true")
+    ap.add_argument("--config5-layers", type=int, default=48)
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-proxy", action="store_true", help="skip the proxy and encoder legs")
@@ -578,39 +743,42 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
-    # ---------------- decode leg: configuration 3
+    # ---------------- decode legs: configuration 3
+    # Order: the steady-state leg first (its own long warm-up takes the device through the power-management
+    # transient that follows idle: step time 0.47 -> 0.69 -> 0.49 ms over the first ~100 steps), then, directly
+    # after it, the headline with exactly the --warmup / --steps asked for.
     t = time.time()
     dec = build_stack(3, 1, args.layers, gpu_activations=False, y_dtype=B.F16)
     log(f"decode stack resident: {dec['n_mats']} matrices, {dec['wbytes'] / 1e9:.3f} GB packed, {time.time() - t:.1f} s")
-    run = lambda: B.rwkvq_linear_dispatch(dec["table"], 1, dec["x_dtype"], B.F16)
-    total_ms, per, wall_ms = time_steps(run, args.steps, args.warmup)
-    ms = total_ms / args.steps
-    gbs = dec["wbytes"] / (ms * 1e-3) / 1e9
-    launches = (dec["n_mats"] + DECODE_MATS_PER_LAUNCH - 1) // DECODE_MATS_PER_LAUNCH
+    full = args.layers == 32
+    steady = None
+    if not args.skip_steady:
+        steady = decode_leg(dec, 1, args.steady_steps, args.steady_warmup, DECODE_KERNEL, "decode_config3", full, enqueue_only=True)
+    head = decode_leg(dec, 1, args.steps, args.warmup, DECODE_KERNEL, "decode_config3", full)   # enqueued behind the steady leg
+    if steady:
+        steady = steady()
+        steady["note"] = ("the same step as the headline, timed over its own long region; enqueued first, the headline's warm-up and "
+                          "timed steps directly behind it on the same stream, so that they are not taken inside the clock "
+                          "transient that follows an idle device")
     out = {
         "metric": "dequant-GEMV weight GB/s (% of HBM peak) + prefill TFLOP/s, RWKV-6-7B shapes",
-        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "configs[2]: RWKV-6-7B-shaped decode stack, %d layers x 8 matrices, "
+        "config": {"workload": "configs[2]: RWKV-6-7B-shaped decode layer stack, %d layers x 8 matrices, "
                                "d=4096 ffn=14336, batch 1, SQ 3-bit g128 / VQ d=2 6-bit per matrix "
                                "(Bernoulli 0.5, seed 2), fp16 activations" % args.layers,
                    "weight_bytes_per_step": dec["wbytes"], "matrices": dec["n_mats"],
-                   "launches_per_step": launches},
-        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
-        "tokens_per_s": 1e3 / ms,
-        "ms_per_step_min": min(per), "ms_per_step_median": float(np.median(per)),
-        # mean of ten equal slices of the timed steps, in order: shows drift (with --warmup 0, the
-        # power-management transient after idle)
-        "ms_per_step_slices": [round(float(np.mean(c)), 4) for c in np.array_split(np.asarray(per), 10)] if args.steps >= 10 else None,
-        "wall_ms_per_step": wall_ms / args.steps,
-        "roofline": {"kernel": DECODE_KERNEL, "bound": "hbm",
-                     "achieved": dec["wbytes"] / launches / (ms / launches * 1e-3) / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": DECODE_TRAFFIC_BYTES_PER_LAUNCH,
-                     "algorithmic_bytes_per_launch": dec["wbytes"] / launches,
-                     "avg_launch_ms": ms / launches},
+                   "launches_per_step": head["launches_per_step"],
+                   "timed_after": "the steady_state leg" if steady else "stack upload (device idle before)"},
+        "pct_hbm_peak": head["pct_hbm_peak"], "tokens_per_s": head["tokens_per_s"],
+        "ms_per_step_min": head["ms_per_step_min"], "ms_per_step_median": head["ms_per_step_median"],
+        # mean of ten equal slices of the timed steps, in order: shows drift
+        "ms_per_step_slices": head["ms_per_step_slices"], "wall_ms_per_step": head["wall_ms_per_step"],
+        "roofline": head["roofline"],
     }
+    if steady:
+        out["steady_state"] = steady
     # ---------------- the same matrices at small batches (one grouped call per step)
     if not args.skip_batched:
         out["decode_batched"] = batched_decode(dec)
@@ -618,8 +786,14 @@ def main():
     if not args.skip_sequential:
         unit_gain(dec, 1)
         out["sequential_step"] = sequential_step(dec, args.layers)
-    del dec, run
+    del dec
     torch.cuda.empty_cache()
+
+    # ---------------- configurations 1 and 2: one matrix, cache-hot / HBM-cold rotated / grouped
+    if not args.skip_single:
+        out["config1"] = single_matrix_legs(1, 1600, 2000, 200)      # 1600 x 0.43 MB = 682 MB > 2 x 256 MB
+        out["config2"] = single_matrix_legs(2, 104, 1000, 100)       # 104 x 6.36 MB = 661 MB
+        torch.cuda.empty_cache()
 
     # ---------------- prefill leg: configuration 4
     if not args.skip_prefill:
@@ -631,22 +805,54 @@ def main():
         pms = ptotal / args.prefill_steps
         tflops = pf["flops"] / (pms * 1e-3) / 1e12
         out["prefill"] = {"value": tflops, "unit": "TFLOP/s", "ms_per_step": pms, "steps": args.prefill_steps,
-                          "warmup": args.prefill_warmup,
+                          "warmup": args.prefill_warmup, "ms_per_step_slices": slices_of(pper, 5),
                           "dtype": "bf16", "tokens_per_s": 2048 * 1e3 / pms,
                           "pct_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
                           "workload": "configs[3]: same stack recipe (seed 3), M=2048 tokens, bf16 "
                                       "activations, %d layers" % args.layers,
                           "flop_per_step": pf["flops"]}
+        tr, src = traffic("prefill_config4", full)
         out["roofline_prefill"] = {"kernel": PREFILL_KERNEL, "bound": "mfma", "achieved": tflops,
                                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
                                    # FETCH_SIZE x 2 + WRITE_SIZE per launch, mean of the four launches of a step
-                                   # (profiles/prefill_and_mix_hbm_traffic.txt)
-                                   "traffic": 8.87e9 if args.layers == 32 else None}
+                                   "traffic": tr, "traffic_source": src, "launches_per_step": 4,
+                                   "avg_launch_ms": pms / 4}
         if not args.skip_sequential:
             unit_gain(pf, 2048, bf16=True)
             out["prefill"]["block"] = prefill_block_step(pf, args.layers, 2048)
         del pf, runp
+        torch.cuda.empty_cache()
+        if not args.skip_cpu:
+            out["prefill"]["cpu_baseline"] = cpu_baseline_prefill()
+
+    # ---------------- configuration 5: the 14B-class stack (SQ / VQ-6 / VQ-8, bf16 activations)
+    if not args.skip_config5:
+        t = time.time()
+        c5 = build_stack(5, 1, args.config5_layers, gpu_activations=False, y_dtype=B.BF16)
+        log(f"configuration 5 resident: {c5['n_mats']} matrices, {c5['wbytes'] / 1e9:.3f} GB packed, {time.time() - t:.1f} s")
+        rec = {"workload": "configs[4]: 14B-class stack, %d layers x 8 matrices, d=5120 ffn=17920, SQ 3-bit g128 / VQ d=2 "
+                           "6-bit / VQ d=2 8-bit per matrix (seed 4), bf16 activations" % args.config5_layers,
+               "weight_bytes_per_step": c5["wbytes"], "matrices": c5["n_mats"]}
+        rec["decode_M1"] = decode_leg(c5, 1, 1000, 300, DECODE_KERNEL, y_dtype=B.BF16)
+        c16 = with_batch(c5, 16, B.BF16)
+        rec["decode_M16"] = decode_leg(c16, 16, 600, 200, DECODE16_KERNEL, y_dtype=B.BF16)
+        del c16
+        torch.cuda.empty_cache()
+        c4k = with_batch(c5, 4096, B.BF16)
+        runp = lambda: B.rwkvq_linear_dispatch(c4k["table"], 4096, c4k["x_dtype"], B.BF16)
+        ptotal, pper, _ = time_steps(runp, 8, 3)
+        pms = ptotal / 8
+        tflops = c4k["flops"] / (pms * 1e-3) / 1e12
+        launches = sum((n + 63) // 64 for n in np.bincount([0 if int(d.kind) == B.SQ else (1 if int(d.kbits) == 6 else 2) for d in c4k["descs"]], minlength=3) if n)
+        rec["prefill_M4096"] = {"value": tflops, "unit": "TFLOP/s", "ms_per_step": pms, "steps": 8, "warmup": 3, "dtype": "bf16",
+                                "tokens_per_s": 4096 * 1e3 / pms, "pct_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+                                "flop_per_step": c4k["flops"], "ms_per_step_slices": slices_of(pper, 4),
+                                "roofline": {"kernel": PREFILL_KERNEL, "bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                             "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                                             "launches_per_step": int(launches), "avg_launch_ms": pms / launches}}
+        out["config5"] = rec
+        del c5, c4k, runp
         torch.cuda.empty_cache()
 
     # ---------------- proxy leg: P_c, P_f, phi of the dense bf16 matrices of some layers
@@ -678,7 +884,8 @@ def main():
                                  "frac": xbytes / (xms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                  # FETCH_SIZE x 2 + WRITE_SIZE of the set kernel for the default 8 layers
                                  # (profiles/proxy_kernel_trace_and_traffic_7b_layers.txt)
-                                 "traffic": 3495.6e6 if args.proxy_layers == 8 else None,
+                                 "traffic": traffic("proxy_8_layers", args.proxy_layers == 8)[0],
+                                 "traffic_source": TRAFFIC["proxy_8_layers"][1],
                                  "algorithmic_bytes_per_launch": xbytes / launches,
                                  "avg_launch_ms": xms / launches,
                                  "note": "achieved = dense weight bytes / time of the whole call (clear + set + "
@@ -783,7 +990,7 @@ def main():
                                "achieved": mix_bytes / (mms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                "frac": mix_bytes / (mms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                # mean per call (profiles/prefill_and_mix_hbm_traffic.txt)
-                               "traffic": 75.7e6,
+                               "traffic": traffic("mix_per_call")[0], "traffic_source": TRAFFIC["mix_per_call"][1],
                                "algorithmic_bytes_per_launch": mix_bytes / (2 * L),
                                "avg_launch_ms": mms / (2 * L)}
         if not args.skip_cpu:
