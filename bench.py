@@ -903,6 +903,35 @@ def main():
                 k += 1
             out["proxy"]["cpu_baseline"] = {"value": nb / secs / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
                                             "sample": "first %d of the %d matrices (%d dense bytes in %.2f s)" % (k, n, nb, secs)}
+        # ---------------- the proxy for binary32 matrices: a real sort (four radix passes) per matrix
+        shapes32 = [(N, K) for _, N, K in synth.layer_shapes(4096, 14336)]
+        mats32 = [torch.randn(sh, device="cuda", generator=gen) * 0.02 for sh in shapes32]
+        table32 = B.ProxyTable(mats32, shapes32)
+        wsp32 = torch.empty((B.rwkvq_proxy_workspace_size(table32, B.F32) + 3) // 4, dtype=torch.int32, device="cuda")
+        run32 = lambda: B.rwkvq_proxy(table32, B.F32, 5, 1.5, 50.0, wsp32, pout, pphi)
+        t32, _, _ = time_steps(run32, 10, 3)
+        ms32 = t32 / 10
+        nw32 = sum(a * b for a, b in shapes32)
+        alg32 = nw32 * 36                      # per weight: 4 passes x (4 B read + 4 B written) + 4 B for the pass over the sorted keys
+        out["proxy_f32"] = {"value": nw32 / (ms32 * 1e-3) / 1e9, "unit": "G weights/s", "ms_per_call": ms32, "calls": 10, "dtype": "f64",
+                            "matrices": len(shapes32), "weights_per_call": nw32,
+                            "workload": "dense binary32 N(0, 0.02) weights of one RWKV-6-7B-shaped layer (8 matrices), K = 5 terms, "
+                                        "sorted by a four-pass radix sort, one matrix after another",
+                            "roofline": {"kernel": "rwkvq::sort_scatter_kernel", "bound": "hbm", "achieved": alg32 / (ms32 * 1e-3) / 1e9,
+                                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": alg32 / (ms32 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                         "traffic": None, "algorithmic_bytes_per_call": alg32,
+                                         "note": "algorithmic bytes = 36 per weight (4 passes x 8 B + 4 B); the histogram step re-reads "
+                                                 "the keys once per pass on top of that; achieved is over the whole call (18 launches per matrix)"}}
+        if not args.skip_cpu:
+            from oracle import proxy_oracle as PO
+            host32 = mats32[0].cpu().numpy()
+            t = time.perf_counter()
+            PO.proxies(host32.astype(np.float64))
+            secs = time.perf_counter() - t
+            out["proxy_f32"]["cpu_baseline"] = {"value": host32.size / secs / 1e9, "unit": "G weights/s", "cores": 1, "kind": "oracle",
+                                                "sample": "the first matrix (4096 x 4096) in %.2f s" % secs}
+        del mats32, table32, wsp32
+        torch.cuda.empty_cache()
         # ---------------- encoder leg: the same dense matrices -> SQ codes, and -> 6-bit VQ indices
         if not args.skip_encode:
             Nmax = max(a * b for a, b in shapes)

@@ -187,32 +187,38 @@ int rwkvq_linear_dispatch_plan(const rwkvq_matrix* mats, int n_mats, int M, int3
 /* ---- the SQ / VQ decision (Sec. 3.1, "Coarse-grained Proxy" and "Fine-grained Proxy") ----------
  *
  * For each of n_mats dense weight matrices ws[i] (DEVICE pointers in a HOST array; matrix i is
- * Ns[i] x Ks[i], row-major, fp16 or bf16 bit patterns, finite values; Ns and Ks are HOST arrays)
- * compute
+ * Ns[i] x Ks[i], row-major, fp16 or bf16 bit patterns or binary32 values, all of one type, finite;
+ * Ns and Ks are HOST arrays) compute
  *   P_c = H(uniform) - H(G')                       Eq. "coarse_proxy", natural logarithm
  *   P_f = sum_{k=2}^{terms} v_k |M_k|              Eq. "fine_proxy", K = terms in [2, 8]
  *   phi = 1 (RWKVQ_SQ) if P_c < tau_c and P_f < tau_f, else 0 (RWKVQ_VQ)    Eq. "multi_scale_proxy"
  * where G' are the normalised intervals between neighbours of the sorted, flattened weights
  * (Eqs. "interval", "interval_norm"), 0 ln 0 := 0 for the zero intervals between equal weights, and
  * a constant matrix gives P_c = P_f = 0.  All arithmetic after the pass over the weights is
- * binary64 in a fixed order.
+ * binary64 in a fixed order.  Sixteen-bit matrices are reduced to the set of bit patterns that
+ * occur (one pass over the matrix, many matrices per launch); binary32 matrices are sorted (four
+ * passes of a radix sort over order-preserving keys), one matrix after another.
  *
  * proxies: DEVICE pointer to 2 n_mats doubles (P_c, P_f per matrix); phi: DEVICE pointer to n_mats
- * int32.  workspace: DEVICE pointer to rwkvq_proxy_workspace_bytes(n_mats) bytes of scratch owned
- * by the caller (contents irrelevant on entry, undefined on exit).  workspace, proxies and every
- * ws[i] 16-byte aligned, phi 4-byte aligned.  The host arrays are read before return; the call is
- * asynchronous on `stream`; calls that share a workspace must be ordered by the stream.
+ * int32.  workspace: DEVICE pointer to rwkvq_proxy_workspace_size(Ns, Ks, n_mats, w_dtype) bytes of
+ * scratch owned by the caller (contents irrelevant on entry, undefined on exit): 8 KiB per matrix
+ * for 16-bit weights (= rwkvq_proxy_workspace_bytes(n_mats)); for binary32 about 8.3 bytes per weight
+ * of the largest matrix (two key buffers, digit counts and partial sums; 0 is returned for arguments
+ * rwkvq_proxy would reject).  workspace, proxies and every ws[i] 16-byte aligned, phi 4-byte aligned.
+ * The host arrays are read before return; the call is asynchronous on `stream`; calls that share a
+ * workspace must be ordered by the stream.
  * Errors: RWKVQ_ERR_NULL, RWKVQ_ERR_ALIGN, RWKVQ_ERR_SHAPE (n_mats < 1, N or K < 1, a matrix of
- * fewer than two weights or more than 2^32 - 1), RWKVQ_ERR_UNSUPPORTED (w_dtype other than
- * fp16 / bf16, terms outside [2, 8]), RWKVQ_ERR_DEVICE. */
+ * fewer than two weights or more than 2^32 - 1), RWKVQ_ERR_UNSUPPORTED (w_dtype, terms outside
+ * [2, 8]), RWKVQ_ERR_DEVICE. */
 size_t rwkvq_proxy_workspace_bytes(int n_mats);
+size_t rwkvq_proxy_workspace_size(const int* Ns, const int* Ks, int n_mats, int w_dtype);
 int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
                 double tau_c, double tau_f, void* workspace, double* proxies, int32_t* phi,
                 void* stream);
 
 /* rwkvq_proxy for callers that cannot allocate device memory or hand over a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
- * errors as rwkvq_proxy without `workspace`: the bitmaps live in a device array inside the library
+ * errors as rwkvq_proxy without `workspace`, for fp16 / bf16 matrices (binary32: RWKVQ_ERR_UNSUPPORTED): the bitmaps live in a device array inside the library
  * (8 KiB per matrix, RWKVQ_PROXY_STATIC_MAX_MATS matrices = 2 MiB, held on every GPU the library
  * runs on until the process ends), whose address is looked up on the first call on each device.  The
  * call allocates nothing, on the host or on the device.  n_mats > RWKVQ_PROXY_STATIC_MAX_MATS returns

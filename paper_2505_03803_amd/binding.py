@@ -23,7 +23,7 @@ EXPORTS = ["rwkvq_version", "rwkvq_status_string", "rwkvq_sq_prepack", "rwkvq_vq
            "rwkvq_linear_dispatch", "rwkvq_proxy_workspace_bytes", "rwkvq_proxy", "rwkvq_sq_encode",
            "rwkvq_vq_assign", "rwkvq_clip_mean", "rwkvq_mu_codebook", "rwkvq_token_shift_mix", "rwkvq_linear_dispatch_mixed",
            "rwkvq_wkv", "rwkvq_relu2", "rwkvq_sigmoid_gate", "rwkvq_linear_dispatch_post", "rwkvq_linear_dispatch_plan", "rwkvq_rkv_wkv", "rwkvq_proxy_static",
-           "rwkvq_set_option", "rwkvq_get_option"]
+           "rwkvq_set_option", "rwkvq_get_option", "rwkvq_proxy_workspace_size"]
 
 
 class rwkvq_mix_input(Structure):
@@ -99,6 +99,8 @@ def lib() -> ctypes.CDLL:
                                             c_int, c_int, c_int, c_int, c_void_p]
         L.rwkvq_proxy_workspace_bytes.restype = c_size_t
         L.rwkvq_proxy_workspace_bytes.argtypes = [c_int]
+        L.rwkvq_proxy_workspace_size.restype = c_size_t
+        L.rwkvq_proxy_workspace_size.argtypes = [POINTER(c_int), POINTER(c_int), c_int, c_int]
         L.rwkvq_proxy.restype = c_int
         L.rwkvq_proxy.argtypes = [POINTER(c_void_p), POINTER(c_int), POINTER(c_int), c_int, c_int, c_int,
                                   c_double, c_double, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -421,13 +423,18 @@ def gemm(dm: DeviceMatrix, x, M: int, x_dtype: int, y_dtype: int = F32, stream=N
     return y
 
 
+def rwkvq_proxy_workspace_size(table: "ProxyTable", w_dtype: int) -> int:
+    return int(lib().rwkvq_proxy_workspace_size(table.Ns, table.Ks, table.n, w_dtype))
+
+
 def proxy(ws, w_dtype: int, terms: int = 5, tau_c: float = 1.5, tau_f: float = 50.0, stream=None):
     """[(P_c, P_f, phi)] of dense weight matrices through one rwkvq_proxy call; ws is a list of 2-D
-    int16 tensors of fp16 / bf16 bit patterns on the GPU.  Synchronises to read the results back."""
+    tensors on the GPU (int16 bit patterns of fp16 / bf16 values, or float32).  Synchronises to read
+    the results back."""
     import torch
     dev = ws[0].device
     table = ProxyTable(ws, [tuple(w.shape) for w in ws])
-    workspace = torch.empty(rwkvq_proxy_workspace_bytes(table.n) // 4, dtype=torch.int32, device=dev)
+    workspace = torch.empty((rwkvq_proxy_workspace_size(table, w_dtype) + 3) // 4, dtype=torch.int32, device=dev)
     out = torch.empty(2 * table.n, dtype=torch.float64, device=dev)
     flag = torch.empty(table.n + 3, dtype=torch.int32, device=dev)
     rwkvq_proxy(table, w_dtype, terms, tau_c, tau_f, workspace, out, flag, stream)

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 # RWKVQ_LIBRARY overrides which built library the binding loads (e.g. an experimental build).
 LIB = os.environ.get("RWKVQ_LIBRARY") or os.path.join(HERE, "librwkvq.so")
-SOURCES = ["api.hip", "dequant.hip", "decode.hip", "prefill.hip", "proxy.hip", "encode.hip", "mu.hip", "block.hip"]
+SOURCES = ["api.hip", "dequant.hip", "decode.hip", "prefill.hip", "proxy.hip", "proxy_f32.hip", "encode.hip", "mu.hip", "block.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

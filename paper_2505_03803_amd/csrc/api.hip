@@ -291,14 +291,27 @@ size_t rwkvq_proxy_workspace_bytes(int n_mats) {          /* one bit per 16-bit 
     return n_mats > 0 ? (size_t)n_mats * (65536 / 8) : 0;
 }
 
+size_t rwkvq_proxy_workspace_size(const int* Ns, const int* Ks, int n_mats, int w_dtype) {
+    if (!Ns || !Ks || n_mats < 1) return 0;
+    if (w_dtype == RWKVQ_F16 || w_dtype == RWKVQ_BF16) return rwkvq_proxy_workspace_bytes(n_mats);
+    if (w_dtype != RWKVQ_F32) return 0;
+    for (int i = 0; i < n_mats; ++i)
+        if (Ns[i] < 1 || Ks[i] < 1 || (unsigned long long)Ns[i] * (unsigned long long)Ks[i] > 0xFFFFFFFFull) return 0;
+    return proxy_f32_workspace_bytes(Ns, Ks, n_mats);
+}
+
 int rwkvq_proxy(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
                 double tau_c, double tau_f, void* workspace, double* proxies, int32_t* phi, void* stream) {
     if (!workspace) return RWKVQ_ERR_NULL;
-    const int st = check_proxy_args(ws, Ns, Ks, n_mats, w_dtype, terms, proxies, phi);
+    const int st = check_proxy_args(ws, Ns, Ks, n_mats, w_dtype, terms, proxies, phi, true);
     if (st != RWKVQ_OK) return st;
     if (!aligned16(workspace)) return RWKVQ_ERR_ALIGN;
-    hipError_t e = launch_proxy(ws, Ns, Ks, n_mats, w_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, terms, tau_c, tau_f,
-                                (uint32_t*)workspace, proxies, phi, (hipStream_t)stream);
+    hipError_t e;
+    if (w_dtype == RWKVQ_F32)
+        e = launch_proxy_f32(ws, Ns, Ks, n_mats, terms, tau_c, tau_f, workspace, proxies, phi, (hipStream_t)stream);
+    else
+        e = launch_proxy(ws, Ns, Ks, n_mats, w_dtype == RWKVQ_F16 ? DT_F16 : DT_BF16, terms, tau_c, tau_f,
+                         (uint32_t*)workspace, proxies, phi, (hipStream_t)stream);
     return e == hipSuccess ? RWKVQ_OK : RWKVQ_ERR_DEVICE;
 }
 

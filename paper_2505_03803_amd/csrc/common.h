@@ -182,7 +182,11 @@ hipError_t launch_proxy(const void* const* ws, const int* Ns, const int* Ks, int
                         hipStream_t s);
 // Host-side checks of a proxy call (everything but the workspace); RWKVQ_OK or the status to return.
 int check_proxy_args(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
-                     const double* proxies, const int32_t* phi);
+                     const double* proxies, const int32_t* phi, bool allow_f32);
+// binary32 matrices: really sorted (proxy_f32.hip); the matrices of a call share the sort buffers
+size_t proxy_f32_workspace_bytes(const int* Ns, const int* Ks, int n_mats);
+hipError_t launch_proxy_f32(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int terms, double tau_c,
+                            double tau_f, void* workspace, double* out, int32_t* phi, hipStream_t s);
 
 hipError_t launch_sq_encode(const void* w, int wdt, int N, int K, uint32_t* codes, uint16_t* scales,
                             uint16_t* zeros, hipStream_t s);

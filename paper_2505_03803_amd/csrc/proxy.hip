@@ -243,10 +243,10 @@ hipError_t launch_proxy(const void* const* ws, const int* Ns, const int* Ks, int
 }
 
 int check_proxy_args(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype, int terms,
-                     const double* proxies, const int32_t* phi) {
+                     const double* proxies, const int32_t* phi, bool allow_f32) {
     if (!ws || !Ns || !Ks || !proxies || !phi) return RWKVQ_ERR_NULL;
     if (n_mats < 1) return RWKVQ_ERR_SHAPE;
-    if (w_dtype != RWKVQ_F16 && w_dtype != RWKVQ_BF16) return RWKVQ_ERR_UNSUPPORTED;
+    if (w_dtype != RWKVQ_F16 && w_dtype != RWKVQ_BF16 && !(allow_f32 && w_dtype == RWKVQ_F32)) return RWKVQ_ERR_UNSUPPORTED;
     if (terms < 2 || terms > kMaxTerms) return RWKVQ_ERR_UNSUPPORTED;
     if (((uintptr_t)proxies & 15u) || ((uintptr_t)phi & 3u)) return RWKVQ_ERR_ALIGN;
     for (int i = 0; i < n_mats; ++i) {
@@ -292,7 +292,7 @@ static hipError_t scratch_of_current_device(uint32_t** out) {
 extern "C" int rwkvq_proxy_static(const void* const* ws, const int* Ns, const int* Ks, int n_mats, int w_dtype,
                                   int terms, double tau_c, double tau_f, double* proxies, int32_t* phi, void* stream) {
     using namespace rwkvq;
-    const int st = check_proxy_args(ws, Ns, Ks, n_mats, w_dtype, terms, proxies, phi);
+    const int st = check_proxy_args(ws, Ns, Ks, n_mats, w_dtype, terms, proxies, phi, false);
     if (st != RWKVQ_OK) return st;
     if (n_mats > kStaticMaxMats) return RWKVQ_ERR_SHAPE;
     uint32_t* bitmaps = nullptr;

@@ -169,13 +169,15 @@ def stack(config: int, M: int, n_layers: Optional[int] = None,
 
 def gen_dense_weights(rng: np.random.Generator, N: int, K: int, dtype: str = "bf16", sigma: float = 0.02,
                       outlier_fraction: float = 0.0, outlier_scale: float = 20.0) -> np.ndarray:
-    """A dense weight matrix as the proxy of Sec. 3.1 sees it: [N][K] fp16 / bf16 bit patterns of
-    N(0, sigma) values, a fraction of them multiplied by outlier_scale (the stored precision of
+    """A dense weight matrix as the proxy of Sec. 3.1 sees it: [N][K] fp16 / bf16 bit patterns (or, for
+    dtype "f32", binary32 values: a master copy of the weights, with few equal values) of N(0, sigma) values, a fraction of them multiplied by outlier_scale (the stored precision of
     RWKV checkpoints is 16 bits; trained matrices are near-Gaussian with a few large entries)."""
     w = rng.standard_normal((N, K), dtype=np.float32) * np.float32(sigma)
     if outlier_fraction > 0.0:
         mask = rng.random((N, K)) < outlier_fraction
         w = np.where(mask, w * np.float32(outlier_scale), w).astype(np.float32)
+    if dtype == "f32":
+        return w
     return f32_to_f16_bits(w) if dtype == "f16" else f32_to_bf16_bits(w)
 
 

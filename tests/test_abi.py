@@ -111,6 +111,13 @@ def test_proxy_rejects():
     assert L.rwkvq_proxy_workspace_bytes(1) == 65536 // 8
     assert L.rwkvq_proxy_workspace_bytes(256) == 256 * 65536 // 8
     assert L.rwkvq_proxy_workspace_bytes(0) == 0
+    # the general query: 8 KiB per matrix for 16-bit weights; for binary32 two key buffers of the largest
+    # matrix, 256 counts per tile of 4096 keys, 256 totals and nine partial sums per 16384 intervals
+    sz = lambda Ns, Ks, dt: L.rwkvq_proxy_workspace_size((ctypes.c_int * len(Ns))(*Ns), (ctypes.c_int * len(Ks))(*Ks), len(Ns), dt)
+    assert sz([256, 64], [256, 64], B.BF16) == 2 * 8192 and sz([256], [256], B.F16) == 8192
+    assert sz([4096, 64], [4096, 64], B.F32) == 2 * 4 * 4096 * 4096 + 4096 * 256 * 4 + 1024 + 1024 * 9 * 8
+    assert sz([3], [5], B.F32) == 256 + 256 + 1024 + 1024 + 256            # every part rounded up to 256 bytes
+    assert sz([0], [5], B.F32) == 0 and sz([65536], [65536], B.F32) == 0 and sz([4], [4], 7) == 0
 
     def call(w=FAKE, N=256, K=256, n=1, dt=B.BF16, terms=5, ws=FAKE, out=FAKE, phi=FAKE, null_table=False):
         wp = (ctypes.c_void_p * 2)(w, FAKE)
@@ -124,7 +131,7 @@ def test_proxy_rejects():
     assert call(out=None) == B.ERR_NULL
     assert call(phi=None) == B.ERR_NULL
     assert call(n=0) == B.ERR_SHAPE
-    assert call(dt=B.F32) == B.ERR_UNSUPPORTED
+    assert call(dt=7) == B.ERR_UNSUPPORTED
     assert call(terms=1) == B.ERR_UNSUPPORTED
     assert call(terms=9) == B.ERR_UNSUPPORTED
     assert call(N=0) == B.ERR_SHAPE
