@@ -17,9 +17,57 @@
 namespace rwkvq {
 
 // ---------------------------------------------------------------------------------- clip_mean
-// One thread per position.  The order statistics are found by rank counting (rank of sample i =
-// number of samples that sort before it, ties by sample index): B^2 comparisons per position on
-// values that stay in cache; B is a calibration batch (128 in Sec. 4), so this is small.
+// The order statistics are found by rank counting (rank of sample i = number of samples that sort
+// before it, ties by sample index): B^2 comparisons per position.  B is a calibration batch (128 in
+// Sec. 4).
+//
+// clip_mean_tile_kernel<P>: a workgroup takes P consecutive positions and stages all B samples of them
+// in LDS (B x P floats); thread (position p, group g) ranks the samples g, g + G, ... of its position
+// against all B (LDS reads of one row of the tile per step: consecutive banks), the four order
+// statistics the percentiles need are left in LDS by whichever thread finds them, and one thread per
+// position then forms the clipped mean as a binary64 sum in sample order.  The same comparisons and the
+// same sum as the plain kernel below, which remains for batches too large for the tile.
+template <int P>
+__global__ void __launch_bounds__(256) clip_mean_tile_kernel(const void* __restrict__ x, int dt, int B, int n, int k_lo,
+                                                             double f_lo, int k_hi, double f_hi, float* __restrict__ out) {
+    extern __shared__ float tile[];                  // [B][P]
+    __shared__ float stat[4][P];
+    constexpr int G = 256 / P;
+    const int tid = threadIdx.x, p = tid % P, g = tid / P;
+    const int j0 = blockIdx.x * P, j = j0 + p;
+    const bool live = j < n;
+    for (int b = g; b < B; b += G) tile[b * P + p] = live ? load_as_f32(x, (size_t)b * n + j, dt) : 0.f;
+    __syncthreads();
+    const int k_lo1 = k_lo + 1 < B ? k_lo + 1 : B - 1, k_hi1 = k_hi + 1 < B ? k_hi + 1 : B - 1;
+    for (int i = g; i < B; i += G) {
+        const float vi = tile[i * P + p];
+        int rank = 0;
+        for (int b = 0; b < B; ++b) {
+            const float vb = tile[b * P + p];
+            rank += (vb < vi || (vb == vi && b < i)) ? 1 : 0;
+        }
+        if (rank == k_lo) stat[0][p] = vi;
+        if (rank == k_lo1) stat[1][p] = vi;
+        if (rank == k_hi) stat[2][p] = vi;
+        if (rank == k_hi1) stat[3][p] = vi;
+    }
+    __syncthreads();
+    if (g == 0 && live) {
+        const float v_lo = stat[0][p], v_lo1 = stat[1][p], v_hi = stat[2][p], v_hi1 = stat[3][p];
+        const double lo = __dadd_rn((double)v_lo, __dmul_rn(f_lo, __dsub_rn((double)v_lo1, (double)v_lo)));
+        const double hi = __dadd_rn((double)v_hi, __dmul_rn(f_hi, __dsub_rn((double)v_hi1, (double)v_hi)));
+        double acc = 0.0;
+        for (int b = 0; b < B; ++b) {                   // sample order: the sum is reproducible
+            double v = (double)tile[b * P + p];
+            v = v < lo ? lo : v;
+            v = v > hi ? hi : v;
+            acc = __dadd_rn(acc, v);
+        }
+        out[j] = (float)(acc / (double)B);
+    }
+}
+
+// One thread per position, samples re-read from memory: any batch size.
 __global__ void __launch_bounds__(256) clip_mean_kernel(const void* __restrict__ x, int dt, int B, int n, int k_lo,
                                                         double f_lo, int k_hi, double f_hi, float* __restrict__ out) {
     const int j = blockIdx.x * 256 + threadIdx.x;
@@ -53,7 +101,13 @@ __global__ void __launch_bounds__(256) clip_mean_kernel(const void* __restrict__
 
 hipError_t launch_clip_mean(const void* x, int dt, int B, int n, int k_lo, double f_lo, int k_hi, double f_hi,
                             float* out, hipStream_t s) {
-    hipLaunchKernelGGL(clip_mean_kernel, dim3((n + 255) / 256), dim3(256), 0, s, x, dt, B, n, k_lo, f_lo, k_hi, f_hi, out);
+    // the tile of B x P floats has to fit 64 KB of LDS: 64 positions per workgroup up to B = 256, 16 up to 1024
+    if (B <= 256)
+        hipLaunchKernelGGL(clip_mean_tile_kernel<64>, dim3((n + 63) / 64), dim3(256), (size_t)B * 64 * 4, s, x, dt, B, n, k_lo, f_lo, k_hi, f_hi, out);
+    else if (B <= 1024)
+        hipLaunchKernelGGL(clip_mean_tile_kernel<16>, dim3((n + 15) / 16), dim3(256), (size_t)B * 16 * 4, s, x, dt, B, n, k_lo, f_lo, k_hi, f_hi, out);
+    else
+        hipLaunchKernelGGL(clip_mean_kernel, dim3((n + 255) / 256), dim3(256), 0, s, x, dt, B, n, k_lo, f_lo, k_hi, f_hi, out);
     return hipGetLastError();
 }
 

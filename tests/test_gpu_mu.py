@@ -27,7 +27,7 @@ def widen(bits, dt):
     return bits.astype(np.float32) if dt == "f32" else orc.widen(bits, dt)
 
 
-@pytest.mark.parametrize("Bn,n", [(1, 7), (5, 300), (37, 64), (128, 4096), (129, 1000)])
+@pytest.mark.parametrize("Bn,n", [(1, 7), (5, 300), (37, 64), (128, 4096), (129, 1000), (256, 70), (300, 50), (1030, 20)])
 @pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
 def test_clip_mean(Bn, n, dt):
     torch = G.torch_()
