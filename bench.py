@@ -650,8 +650,8 @@ def single_matrix_legs(config, min_copies, steps, warmup):
                                "pct_hbm_peak": 100.0 * wb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                "note": "one launch per call on cold data: bound by launch latency (%.1f us of traffic at peak)" % (wb / 8e12 * 1e6)}
     # grouped: all copies in one dispatch
-    g_steps = max(20, steps // 20)
-    tot, per, _ = time_steps(lambda: B.rwkvq_linear_dispatch(grouped, 1, B.F16, B.F16), g_steps, 5)
+    g_steps = max(20, steps // 10)
+    tot, per, _ = time_steps(lambda: B.rwkvq_linear_dispatch(grouped, 1, B.F16, B.F16), g_steps, 300)   # ~50 ms of warm-up: past the clock transient
     ms = tot / g_steps
     launches = (min_copies + DECODE_MATS_PER_LAUNCH - 1) // DECODE_MATS_PER_LAUNCH
     res["grouped"] = {"ms_per_step": ms, "value": wb * min_copies / (ms * 1e-3) / 1e9, "unit": "GB/s", "steps": g_steps,
@@ -713,6 +713,7 @@ def main():
     ap.add_argument("--skip-single", action="store_true", help="skip the single-matrix legs (configurations 1 and 2)")
     ap.add_argument("--skip-config5", action="store_true")
     ap.add_argument("--config5-layers", type=int, default=48)
+    ap.add_argument("--config5-steps", type=int, default=1000, help="timed batch-1 steps of the configuration-5 leg (batch 16: 0.6 x)")
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-proxy", action="store_true", help="skip the proxy and encoder legs")
@@ -834,9 +835,9 @@ def main():
         rec = {"workload": "configs[4]: 14B-class stack, %d layers x 8 matrices, d=5120 ffn=17920, SQ 3-bit g128 / VQ d=2 "
                            "6-bit / VQ d=2 8-bit per matrix (seed 4), bf16 activations" % args.config5_layers,
                "weight_bytes_per_step": c5["wbytes"], "matrices": c5["n_mats"]}
-        rec["decode_M1"] = decode_leg(c5, 1, 1000, 300, DECODE_KERNEL, y_dtype=B.BF16)
+        rec["decode_M1"] = decode_leg(c5, 1, args.config5_steps, max(1, args.config5_steps * 3 // 10), DECODE_KERNEL, y_dtype=B.BF16)
         c16 = with_batch(c5, 16, B.BF16)
-        rec["decode_M16"] = decode_leg(c16, 16, 600, 200, DECODE16_KERNEL, y_dtype=B.BF16)
+        rec["decode_M16"] = decode_leg(c16, 16, max(1, args.config5_steps * 6 // 10), max(1, args.config5_steps * 2 // 10), DECODE16_KERNEL, y_dtype=B.BF16)
         del c16
         torch.cuda.empty_cache()
         c4k = with_batch(c5, 4096, B.BF16)

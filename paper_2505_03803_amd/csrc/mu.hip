@@ -133,50 +133,83 @@ __device__ __forceinline__ uint16_t f64_to_f16_bits(double d) {
     return f32_to_f16_bits(f);
 }
 
+// One workgroup per weight tensor.  The vectors go through LDS in chunks of 2048: every vector of a chunk is
+// assigned to its cheapest entry (index, weight and value staged in LDS), then the sums of an entry's
+// coordinate are continued by S = 1024 / (2 E) threads, each over a contiguous share of the chunk in index
+// order; after the last chunk the S partial sums are added in share order.  Binary64 sums in a fixed order:
+// a call gives the same codebook every time.
 template <int E>
 __global__ void __launch_bounds__(1024) mu_kmeans_kernel(MuArgs a) {
+    constexpr int S = 1024 / (2 * E);                 // threads per (entry, coordinate)
+    constexpr int kChunk = 2048, kPer = kChunk / S;   // vectors per chunk and per share
+    constexpr int kRow = kPer + 1;                    // padded: the S shares of a chunk start in different LDS banks
     __shared__ float cb[E][2];
-    __shared__ double num[E][2], den[E][2];
+    __shared__ uint32_t s_idx[S * kRow];
+    __shared__ float s_m[S * kRow][2], s_w[S * kRow][2];
+    __shared__ double num[2 * E][S], den[2 * E][S];
     const MuTensor t = a.t[blockIdx.x];
     const int V = t.n >> 1, tid = threadIdx.x;
     for (int e = tid; e < E; e += 1024) {
         cb[e][0] = f16_bits_to_f32(t.cb[2 * e]);
         cb[e][1] = f16_bits_to_f32(t.cb[2 * e + 1]);
     }
+    __syncthreads();
+    const int pair = tid / S, seg = tid % S;          // update phase: pair = 2 e + coordinate
     for (int it = 0; it <= a.iters; ++it) {
         const bool last = it == a.iters;
-        for (int e = tid; e < 2 * E; e += 1024) { (&num[0][0])[e] = 0.0; (&den[0][0])[e] = 0.0; }
-        __syncthreads();
-        for (int v = tid; v < V; v += 1024) {
-            const float m0 = load_as_f32(t.mu, 2 * (size_t)v, a.dt), m1 = load_as_f32(t.mu, 2 * (size_t)v + 1, a.dt);
-            const float x0 = t.xbar[2 * (size_t)v], x1 = t.xbar[2 * (size_t)v + 1];
-            const float w0 = __fmul_rn(x0, x0), w1 = __fmul_rn(x1, x1);
-            int best = 0;
-            float bestc = __builtin_inff();
-            for (int e = 0; e < E; ++e) {
-                const float t0 = __fsub_rn(m0, cb[e][0]), t1 = __fsub_rn(m1, cb[e][1]);
-                const float c = __fadd_rn(__fmul_rn(w0, __fmul_rn(t0, t0)), __fmul_rn(w1, __fmul_rn(t1, t1)));
-                if (c < bestc) { bestc = c; best = e; }
+        double sn = 0.0, sd = 0.0;
+        for (int c0 = 0; c0 < V; c0 += kChunk) {
+#pragma unroll
+            for (int h = 0; h < kChunk / 1024; ++h) {
+                const int vl = h * 1024 + tid, v = c0 + vl;
+                const int slot = (vl / kPer) * kRow + vl % kPer;
+                if (v < V) {
+                    const float m0 = load_as_f32(t.mu, 2 * (size_t)v, a.dt), m1 = load_as_f32(t.mu, 2 * (size_t)v + 1, a.dt);
+                    const float x0 = t.xbar[2 * (size_t)v], x1 = t.xbar[2 * (size_t)v + 1];
+                    const float w0 = __fmul_rn(x0, x0), w1 = __fmul_rn(x1, x1);
+                    int best = 0;
+                    float bestc = __builtin_inff();
+                    for (int e = 0; e < E; ++e) {
+                        const float t0 = __fsub_rn(m0, cb[e][0]), t1 = __fsub_rn(m1, cb[e][1]);
+                        const float c = __fadd_rn(__fmul_rn(w0, __fmul_rn(t0, t0)), __fmul_rn(w1, __fmul_rn(t1, t1)));
+                        if (c < bestc) { bestc = c; best = e; }
+                    }
+                    if (last) t.idx[v] = (uint8_t)best;
+                    s_idx[slot] = (uint32_t)best;
+                    s_m[slot][0] = m0; s_m[slot][1] = m1; s_w[slot][0] = w0; s_w[slot][1] = w1;
+                } else {
+                    s_idx[slot] = 0xFFFFFFFFu;       // past the end: matches no entry
+                }
             }
-            if (last) {
-                t.idx[v] = (uint8_t)best;
-            } else {
-                // products of two binary32 values are exact in binary64
-                atomicAdd(&num[best][0], (double)w0 * (double)m0);
-                atomicAdd(&num[best][1], (double)w1 * (double)m1);
-                atomicAdd(&den[best][0], (double)w0);
-                atomicAdd(&den[best][1], (double)w1);
-            }
-        }
-        __syncthreads();
-        if (!last) {
-            for (int e = tid; e < 2 * E; e += 1024) {
-                const double dn = (&den[0][0])[e];
-                if (dn > 0.0) (&cb[0][0])[e] = f16_bits_to_f32(f64_to_f16_bits((&num[0][0])[e] / dn));
+            if (last) continue;                       // the final pass only assigns
+            __syncthreads();
+            {
+                const uint32_t e = (uint32_t)(pair >> 1);
+                const int c = pair & 1;
+                for (int i = 0; i < kPer; ++i) {
+                    const int slot = seg * kRow + i;
+                    const bool mine = s_idx[slot] == e;
+                    const double w = (double)s_w[slot][c];
+                    // the product of two binary32 values is exact in binary64; vectors of other entries add +0
+                    sn += mine ? w * (double)s_m[slot][c] : 0.0;
+                    sd += mine ? w : 0.0;
+                }
             }
             __syncthreads();
         }
+        if (last) break;
+        num[pair][seg] = sn;
+        den[pair][seg] = sd;
+        __syncthreads();
+        for (int p = tid; p < 2 * E; p += 1024) {
+            double tn = 0.0, td = 0.0;
+#pragma unroll
+            for (int g = 0; g < S; ++g) { tn += num[p][g]; td += den[p][g]; }
+            if (td > 0.0) (&cb[0][0])[p] = f16_bits_to_f32(f64_to_f16_bits(tn / td));
+        }
+        __syncthreads();
     }
+    __syncthreads();
     for (int e = tid; e < 2 * E; e += 1024) t.cb[e] = f32_to_f16_bits((&cb[0][0])[e]);
 }
 
