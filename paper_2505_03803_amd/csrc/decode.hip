@@ -61,6 +61,18 @@ static_assert(kRT == 1, "the batch-1 tile loops hold one row tile per wavefront"
 #ifndef RWKVQ_DECODE_BATCH_RT
 #define RWKVQ_DECODE_BATCH_RT 2
 #endif
+#ifndef RWKVQ_BATCH_UB2
+#define RWKVQ_BATCH_UB2 0            // batch 2..16: 1 = read the activation fragments of both column halves of a tile up front
+#endif
+#ifndef RWKVQ_BATCH_DEPTH
+#define RWKVQ_BATCH_DEPTH 1          // batch 2..32: tiles in flight beyond the one being consumed
+#endif
+#ifndef RWKVQ_BATCH16_MINBLOCKS
+#define RWKVQ_BATCH16_MINBLOCKS 4    // workgroups per compute unit the compiler must leave registers for (batch 5..16)
+#endif
+#ifndef RWKVQ_BATCH4_MINBLOCKS
+#define RWKVQ_BATCH4_MINBLOCKS 4
+#endif
 // Batch 2..16: row tiles per wavefront.  Every wavefront reads the whole activation tile from LDS as
 // its A operands; with two row tiles those reads serve twice the weights (the batched path is bound
 // by LDS traffic: M = 16 gained 12-16 % per format over one row tile).
@@ -318,9 +330,25 @@ __device__ __forceinline__ float dpp_add(float v) {
 // end of the row the loads fetch the last tile again (cache hits, never used).
 template <int DEPTH, class Regs, class Load, class Compute>
 __device__ __forceinline__ void tile_pipeline(int KT, Load load, Compute compute) {
-    static_assert(DEPTH == 2 || DEPTH == 3, "pipeline depth");
+    static_assert(DEPTH == 1 || DEPTH == 2 || DEPTH == 3, "pipeline depth");
     const int last = KT - 1;
     auto c = [&](int T) { return T < KT ? T : last; };
+    if constexpr (DEPTH == 1) {                  // two register sets: the next tile in flight while one is consumed
+        Regs q0, q1;
+        auto issue1 = [&](Regs& r, int T) {
+            load(r, c(T));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        issue1(q0, 0);
+        for (int T = 0; T < KT; T += 2) {
+            issue1(q1, T + 1);
+            compute(q0, T);
+            issue1(q0, T + 2);
+            if (T + 1 < KT) compute(q1, T + 1);
+        }
+        return;
+    }
     Regs r0, r1, r2, r3;
     // The fences keep each tile's loads together and in program order, in the prologue too: the
     // wait the compiler derives for a tile then lets all younger tiles stay in flight.
@@ -404,7 +432,7 @@ struct WavePos {
 template <int MT, int DEPTH, bool XB>
 __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc,
                                        float4_t (&out)[groups_of(MT)][kBRT]) {
-    constexpr int G = groups_of(MT), UB = G == 1 ? 2 : 1;   // one group: the fragments of both column halves up front
+    constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;   // one group: the fragments of both column halves up front
     using Regs = SqRegs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
     const uint32_t* codes[kBRT];
@@ -493,7 +521,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
 template <int MT, int DEPTH, bool XB>
 __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
                                         float4_t (&out)[groups_of(MT)][kBRT]) {
-    constexpr int G = groups_of(MT), UB = G == 1 ? 2 : 1;
+    constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;
     using Regs = Vq6Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
     const uint32_t* codes[kBRT];
@@ -1007,8 +1035,8 @@ __device__ __forceinline__ void run_batched(const DecodeMat& mt, const WavePos& 
 // vector ALU (run_*_m1); the others on the matrix cores, whose D layout is: lane holds batch rows
 // 4*(lane/16) + i of output column lane%16.
 template <int MT>
-__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? 3 : MT == 16 ? 2 : 1) decode_kernel(DecodeArgs a) {
-    constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : 2;
+__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? RWKVQ_BATCH4_MINBLOCKS : MT == 16 ? RWKVQ_BATCH16_MINBLOCKS : 1) decode_kernel(DecodeArgs a) {
+    constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : RWKVQ_BATCH_DEPTH;
     // batch > 1: two activation tiles shared by the workgroup; codebook slots per wavefront
     __shared__ __attribute__((aligned(16))) half_t xs[MT == 1 ? 8 : 2 * MT * kXStride];
     __shared__ __attribute__((aligned(1024))) uint32_t cb_all[4][MT == 1 ? 256 : 512];
