@@ -41,10 +41,10 @@ __global__ void __launch_bounds__(256) sq_encode_kernel(const void* __restrict__
     const size_t e0 = (size_t)unit * kGroup + 8 * sub;   // groups are consecutive in a row-major matrix
     float v[8];
     if (wdt == DT_F32) {
-        const float4_t a = *(const float4_t*)((const float*)w + e0), b = *(const float4_t*)((const float*)w + e0 + 4);
+        const float4_t a = __builtin_nontemporal_load((const float4_t*)((const float*)w + e0)), b = __builtin_nontemporal_load((const float4_t*)((const float*)w + e0 + 4));   // the dense weights are read once
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
     } else {
-        const uint4_t p = *(const uint4_t*)((const uint16_t*)w + e0);
+        const uint4_t p = __builtin_nontemporal_load((const uint4_t*)((const uint16_t*)w + e0));
         const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {

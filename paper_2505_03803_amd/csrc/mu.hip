@@ -305,7 +305,9 @@ __global__ void __launch_bounds__(256) token_shift_mix_kernel(MixArgs a) {
             const float o1 = __fadd_rn(__fmul_rn(m1, t[2 * q + 1]), __fmul_rn(__fsub_rn(1.0f, m1), u[2 * q + 1]));
             ow[q] = MixElem<BF16>::narrow(o0, o1);
         }
-        ((uint4_t*)a.out[p])[(size_t)row * chunks + c] = uint4_t{ow[0], ow[1], ow[2], ow[3]};
+        // written once, read by a later launch: stored with the non-temporal hint, so that the outputs do not
+        // displace the rows of x (each read twice, as x_t and as x_{t-1}) from the L2
+        __builtin_nontemporal_store(uint4_t{ow[0], ow[1], ow[2], ow[3]}, (uint4_t*)a.out[p] + (size_t)row * chunks + c);
     }
 }
 

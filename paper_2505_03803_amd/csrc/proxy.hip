@@ -75,7 +75,7 @@ __global__ void __launch_bounds__(kSetThreads, 2) proxy_set_kernel(ProxyArgs a) 
     const uint4_t* src = (const uint4_t*)w;
     for (unsigned long long i = (unsigned long long)local * kSetThreads + tid; i < nvec;
          i += (unsigned long long)nwg * kSetThreads) {
-        const uint4_t v = src[i];
+        const uint4_t v = __builtin_nontemporal_load(src + i);      // read once
         const uint32_t a = v.x, b = v.y, c = v.z, d = v.w;
         flag[sort_key(a & 0xFFFFu)] = 1; flag[sort_key(a >> 16)] = 1;
         flag[sort_key(b & 0xFFFFu)] = 1; flag[sort_key(b >> 16)] = 1;
