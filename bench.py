@@ -47,7 +47,9 @@ DECODE_MATS_PER_LAUNCH = 256
 # are separate runs of this file (commands in the named summaries under profiles/); the figures are theirs, for the
 # default workload only, and are not re-measured by the run that prints them.
 TRAFFIC = {
-    "decode_config3": (2806.7e6, "profiles/decode_hbm_traffic_config3.txt"),
+    "decode_config3": (2909.0e6, "profiles/decode_hbm_traffic_config3_config5.txt"),
+    "decode_config5_M1": (7473.9e6 / 2, "profiles/decode_hbm_traffic_config3_config5.txt"),     # mean of the two launches of a step
+    "decode_config5_M16": (8028.6e6 / 2, "profiles/decode_hbm_traffic_config3_config5.txt"),
     "prefill_config4": (8.87e9, "profiles/prefill_and_mix_hbm_traffic.txt"),
     "proxy_8_layers": (3495.6e6, "profiles/proxy_kernel_trace_and_traffic_7b_layers.txt"),
     "mix_per_call": (75.7e6, "profiles/prefill_and_mix_hbm_traffic.txt"),
@@ -835,9 +837,11 @@ def main():
         rec = {"workload": "configs[4]: 14B-class stack, %d layers x 8 matrices, d=5120 ffn=17920, SQ 3-bit g128 / VQ d=2 "
                            "6-bit / VQ d=2 8-bit per matrix (seed 4), bf16 activations" % args.config5_layers,
                "weight_bytes_per_step": c5["wbytes"], "matrices": c5["n_mats"]}
-        rec["decode_M1"] = decode_leg(c5, 1, args.config5_steps, max(1, args.config5_steps * 3 // 10), DECODE_KERNEL, y_dtype=B.BF16)
+        rec["decode_M1"] = decode_leg(c5, 1, args.config5_steps, max(1, args.config5_steps * 3 // 10), DECODE_KERNEL, "decode_config5_M1",
+                                      args.config5_layers == 48, y_dtype=B.BF16)
         c16 = with_batch(c5, 16, B.BF16)
-        rec["decode_M16"] = decode_leg(c16, 16, max(1, args.config5_steps * 6 // 10), max(1, args.config5_steps * 2 // 10), DECODE16_KERNEL, y_dtype=B.BF16)
+        rec["decode_M16"] = decode_leg(c16, 16, max(1, args.config5_steps * 6 // 10), max(1, args.config5_steps * 2 // 10), DECODE16_KERNEL,
+                                       "decode_config5_M16", args.config5_layers == 48, y_dtype=B.BF16)
         del c16
         torch.cuda.empty_cache()
         c4k = with_batch(c5, 4096, B.BF16)
