@@ -68,7 +68,7 @@ static_assert(kRT == 1, "the batch-1 tile loops hold one row tile per wavefront"
 #define RWKVQ_BATCH_DEPTH 1          // batch 2..32: tiles in flight beyond the one being consumed
 #endif
 #ifndef RWKVQ_BATCH16_MINBLOCKS
-#define RWKVQ_BATCH16_MINBLOCKS 4    // workgroups per compute unit the compiler must leave registers for (batch 5..16)
+#define RWKVQ_BATCH16_MINBLOCKS 4    // wavefronts per SIMD the compiler must leave registers for (batch 5..16)
 #endif
 #ifndef RWKVQ_BATCH4_MINBLOCKS
 #define RWKVQ_BATCH4_MINBLOCKS 4
@@ -79,7 +79,17 @@ static_assert(kRT == 1, "the batch-1 tile loops hold one row tile per wavefront"
 constexpr int kBRT = RWKVQ_DECODE_BATCH_RT;
 static_assert(kBRT == 1 || kBRT == 2 || kBRT == 4, "row tiles of a wavefront share a 256-row codebook block");
 constexpr int rt_of(int MT) { return MT == 1 ? kRT : kBRT; }
-constexpr int wg_rows(int MT) { return 64 * rt_of(MT); }   // rows of W per workgroup of four wavefronts
+#ifndef RWKVQ_BATCH_WAVES
+#define RWKVQ_BATCH_WAVES 4
+#endif
+// Batch 2..32: wavefronts per workgroup (4 or 8).  They share the staged activation tile, so its reads from
+// the L2 (M x 512 bytes per column tile and workgroup) are spread over that many rows of W.  Measured on the
+// 14B-class shapes: eight wavefronts gain 1.5-3 % on single-format stacks at batch 16 and lose 2-8 % on the
+// mixed stack at batch 4 and 32 (longer tails of the larger workgroups): four is the default.
+constexpr int kBW = RWKVQ_BATCH_WAVES;
+static_assert(kBW == 4 || kBW == 8, "sixteen or thirty-two threads stage a batch row");
+constexpr int waves_of(int MT) { return MT == 1 ? 4 : kBW; }
+constexpr int wg_rows(int MT) { return 16 * waves_of(MT) * rt_of(MT); }   // rows of W per workgroup
 
 struct DecodeMat {
     const uint32_t* codes;
@@ -221,17 +231,18 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Batch 2..16: the activation tile [MT rows][256 columns] of a column tile is shared by the four
-// wavefronts of the workgroup.  Thread t fetches 16 columns of row t / 16 (rows beyond M repeat row
-// M - 1: every load is unconditional, see tile_pipeline) and later stores them, converted to fp16,
+// Batch 2..32: the activation tile [MT rows][256 columns] of a column tile is shared by the wavefronts of the
+// workgroup.  kRowThreads threads fetch a row of it, kRowCols columns each (rows beyond M repeat row
+// M - 1: every load is unconditional, see tile_pipeline) and later store them, converted to fp16,
 // into one of two LDS buffers.
-struct XShared { uint4_t a, b; };
+struct XShared { uint4_t a, b; };           // b: only with sixteen threads per row
+constexpr int kRowThreads = 4 * kBW, kRowCols = 256 / kRowThreads;
 
 __device__ __forceinline__ void x_load_wg(XShared& r, const uint16_t* x, int M, int K, int T, int tid, int g = 0) {
-    const int row = 16 * g + (tid >> 4) < M ? 16 * g + (tid >> 4) : M - 1;
-    const uint16_t* p = x + (size_t)row * K + 256 * T + 16 * (tid & 15);
+    const int row = 16 * g + tid / kRowThreads < M ? 16 * g + tid / kRowThreads : M - 1;
+    const uint16_t* p = x + (size_t)row * K + 256 * T + kRowCols * (tid % kRowThreads);
     r.a = *(const uint4_t*)p;
-    r.b = *(const uint4_t*)(p + 8);
+    if constexpr (kRowCols == 16) r.b = *(const uint4_t*)(p + 8);
 }
 
 // ---- bf16 activations -----------------------------------------------------------------------
@@ -280,27 +291,35 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v, int n) {
     return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
-// bf16: the sixteen threads that hold one batch row's 256 columns are one DPP row; they agree on the
-// row's scale for this tile, convert, and thread 0 of the row leaves the inverse scale in xsc[row].
+// bf16: the threads that hold one batch row's 256 columns are one or two DPP rows of sixteen lanes; they agree
+// on the row's scale for this tile, convert, and the first of them leaves the inverse scale in xsc[row].
 template <int MT>
 __device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, float* xsc, int tid, bool bf16, int g = 0) {
-    const int row = 16 * g + (tid >> 4);
+    const int row = 16 * g + tid / kRowThreads;
     uint4_t a = r.a, b = r.b;
     if (bf16) {
         const ushort2_t m01 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a.x & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, a.y & 0x7FFF7FFFu));
         const ushort2_t m23 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a.z & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, a.w & 0x7FFF7FFFu));
-        const ushort2_t m45 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, b.x & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, b.y & 0x7FFF7FFFu));
-        const ushort2_t m67 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, b.z & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, b.w & 0x7FFF7FFFu));
-        const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_elementwise_max(m01, m23), __builtin_elementwise_max(m45, m67)));
-        const int n = bf16_scale_exponent(dpp_row_max(max(w >> 16, w & 0xFFFFu)));
+        ushort2_t mm = __builtin_elementwise_max(m01, m23);
+        if constexpr (kRowCols == 16) {
+            const ushort2_t m45 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, b.x & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, b.y & 0x7FFF7FFFu));
+            const ushort2_t m67 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, b.z & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, b.w & 0x7FFF7FFFu));
+            mm = __builtin_elementwise_max(mm, __builtin_elementwise_max(m45, m67));
+        }
+        const uint32_t w = __builtin_bit_cast(uint32_t, mm);
+        uint32_t amax = dpp_row_max(max(w >> 16, w & 0xFFFFu));
+        if constexpr (kRowThreads == 32) amax = max(amax, (uint32_t)__shfl_xor((int)amax, 16, 64));   // the row's other sixteen lanes
+        const int n = bf16_scale_exponent(amax);
         a.x = bf16x2_to_f16x2(a.x, n); a.y = bf16x2_to_f16x2(a.y, n); a.z = bf16x2_to_f16x2(a.z, n); a.w = bf16x2_to_f16x2(a.w, n);
-        b.x = bf16x2_to_f16x2(b.x, n); b.y = bf16x2_to_f16x2(b.y, n); b.z = bf16x2_to_f16x2(b.z, n); b.w = bf16x2_to_f16x2(b.w, n);
-        if ((tid & 15) == 0) xsc[row] = ldexpf(1.0f, -n);      // rows beyond MT repeat row M - 1: written, never used
+        if constexpr (kRowCols == 16) {
+            b.x = bf16x2_to_f16x2(b.x, n); b.y = bf16x2_to_f16x2(b.y, n); b.z = bf16x2_to_f16x2(b.z, n); b.w = bf16x2_to_f16x2(b.w, n);
+        }
+        if (tid % kRowThreads == 0) xsc[row] = ldexpf(1.0f, -n);      // rows beyond MT repeat row M - 1: written, never used
     }
     if (row < MT) {
-        half_t* d = xs + row * kXStride + 16 * (tid & 15);
+        half_t* d = xs + row * kXStride + kRowCols * (tid % kRowThreads);
         *(uint4_t*)d = a;
-        *(uint4_t*)(d + 8) = b;
+        if constexpr (kRowCols == 16) *(uint4_t*)(d + 8) = b;
     }
 }
 
@@ -1037,15 +1056,22 @@ __device__ __forceinline__ void run_batched(const DecodeMat& mt, const WavePos& 
     }
 }
 
+// Workgroups per compute unit the compiler must leave registers for: the macros give wavefronts per SIMD.
+constexpr int min_blocks(int MT) {
+    if (MT == 1) return RWKVQ_DECODE_MINBLOCKS;
+    const int per_simd = MT == 4 ? RWKVQ_BATCH4_MINBLOCKS : MT == 16 ? RWKVQ_BATCH16_MINBLOCKS : 2;
+    return per_simd * 4 / kBW > 0 ? per_simd * 4 / kBW : 1;
+}
+
 // MT = number of activation rows carried (1, 4, 16 or 32 >= M).  MT = 1 runs every format on the
 // vector ALU (run_*_m1); the others on the matrix cores, whose D layout is: lane holds batch rows
 // 4*(lane/16) + i of output column lane%16.
 template <int MT>
-__global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 4 ? RWKVQ_BATCH4_MINBLOCKS : MT == 16 ? RWKVQ_BATCH16_MINBLOCKS : 1) decode_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kernel(DecodeArgs a) {
     constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : RWKVQ_BATCH_DEPTH;
     // batch > 1: two activation tiles shared by the workgroup; codebook slots per wavefront
     __shared__ __attribute__((aligned(16))) half_t xs[MT == 1 ? 8 : 2 * MT * kXStride];
-    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[4][MT == 1 ? 256 : 512];
+    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[waves_of(MT)][MT == 1 ? 256 : 512];
     __shared__ __attribute__((aligned(16))) float xsc[MT == 1 ? 4 : 2 * 16 * groups_of(MT)];   // bf16: inverse scales per tile and batch row
 
     // Which matrix does this workgroup belong to?  Lane i compares against the end of matrix i
@@ -1066,7 +1092,7 @@ __global__ void __launch_bounds__(256, MT == 1 ? RWKVQ_DECODE_MINBLOCKS : MT == 
     const int NR = mt.N >> 4;
     WavePos wp;
     constexpr int RT = rt_of(MT);
-    wp.R[0] = RT * (4 * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
+    wp.R[0] = RT * (waves_of(MT) * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
     const bool live = wp.R[0] < NR;                // rows beyond N (N not a multiple of the workgroup's rows)
     wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xbf16;
 
@@ -1348,9 +1374,9 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
         if (split) { hipError_t e = launch_splitk(split, wgs, a, s); if (e != hipSuccess) return e; }
         else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
-        else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
-        else if (M <= 16) hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(256), 0, s, a);
-        else hipLaunchKernelGGL(decode_kernel<32>, dim3(wgs), dim3(256), 0, s, a);
+        else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(64 * kBW), 0, s, a);
+        else if (M <= 16) hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(64 * kBW), 0, s, a);
+        else hipLaunchKernelGGL(decode_kernel<32>, dim3(wgs), dim3(64 * kBW), 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
