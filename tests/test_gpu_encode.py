@@ -61,6 +61,44 @@ def test_sq_encode_range_below_the_resolution_of_an_fp16_scale():
     assert np.array_equal(codes, E.pack_fields(want_q, 3))
 
 
+def quotient_stress(rng, N, K, dtype):
+    """Groups whose codes hang on the last bit of each quotient w / s: a group sits far from zero compared
+    with its range (so w / s and z are large and w / s + z lands on or beside a rounding tie), at scales
+    from 2^-20 to 2^12; plus groups that hold zeros of both signs, values far below the rest of the group,
+    and (binary32 only) values beyond 2^60."""
+    G = K // 128
+    scale = np.exp2(rng.integers(-20, 13, size=(N, G, 1)).astype(np.float64))
+    offset = rng.choice([0.0, 1.0, -3.0, 37.0, -500.0, 4000.0], size=(N, G, 1)) * scale
+    w = (offset + scale * rng.uniform(-1.0, 1.0, size=(N, G, 128))).reshape(N, K).astype(np.float32)
+    w[0, 0:8] = [0.0, -0.0, 1e-30, -1e-30, 2.0 ** -61, 2.0 ** -59, -(2.0 ** -60), 1e-38]
+    w[1, 128:132] = [0.0, -0.0, 1e-25, -3e-22]
+    if dtype == "f32":
+        w[2, 0:128] = rng.uniform(-1.0, 1.0, 128).astype(np.float32) * np.float32(2.0 ** 70)   # fp16 scale overflows
+        w[3, 5] = np.float32(2.0 ** 61)
+        return w, w
+    if dtype == "f16":
+        w = np.clip(w, -60000.0, 60000.0)
+        bits = w.astype(np.float16).view(np.uint16)
+        return bits, bits.view(np.float16).astype(np.float32)
+    u = w.view(np.uint32)
+    bits = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)       # binary32 -> bf16, nearest even
+    return bits, (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_sq_encode_quotients_to_the_last_bit(dtype):
+    from paper_2505_03803_amd import binding as B
+    print(f"sq_encode quotient stress {dtype}", flush=True)
+    rng = np.random.default_rng(4242)
+    w, wide = quotient_stress(rng, 600, 1024, dtype)
+    dm = B.sq_encode(dev(w, dtype), B.DTYPES[dtype])
+    with np.errstate(all="ignore"):
+        codes, s16, z16 = E.sq_encode_packed(wide)
+    assert np.array_equal(dm.scales.cpu().numpy().view(np.uint16), s16)
+    assert np.array_equal(dm.zeros.cpu().numpy().view(np.uint16), z16)
+    assert np.array_equal(dm.codes.cpu().numpy().view(np.uint32), codes)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("kbits,N,K", [(6, 256, 256), (6, 512, 768), (8, 256, 512)])
 def test_vq_assign_bit_exact(dtype, kbits, N, K):
