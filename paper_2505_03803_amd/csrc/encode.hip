@@ -49,7 +49,8 @@ __device__ __forceinline__ float half_row_max(float v) {
 // exactly.  Two steps yield the correctly rounded quotient whenever nothing over- or underflows
 // on the way (one makes q faithful, the second rounds it correctly: Markstein's theorem); for a
 // dividend that is a bf16 or fp16 value and a divisor that is an fp16 value one step does
-// (checked on the host over every such pair with the dividend zero or in [2^-60, 2^60]).
+// (checked on the host over every such pair with the dividend zero or in [2^-60, 2^60]:
+// tests/host/quotient_check.c).
 template <int STEPS>
 __device__ __forceinline__ float quotient(float v, float d, float r) {
     float q = __fmul_rn(v, r);
