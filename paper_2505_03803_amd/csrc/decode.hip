@@ -89,7 +89,17 @@ constexpr int rt_of(int MT) { return MT == 1 ? kRT : kBRT; }
 constexpr int kBW = RWKVQ_BATCH_WAVES;
 static_assert(kBW == 4 || kBW == 8, "sixteen or thirty-two threads stage a batch row");
 constexpr int waves_of(int MT) { return MT == 1 ? 4 : kBW; }
-constexpr int wg_rows(int MT) { return 16 * waves_of(MT) * rt_of(MT); }   // rows of W per workgroup
+#ifndef RWKVQ_BATCH_PASSES
+#define RWKVQ_BATCH_PASSES 2
+#endif
+// Batch 2..32: row passes of a workgroup per column tile (1 or 2).  With two, the staged activation tile (and,
+// for VQ, the tile's codebook) serves a second stretch of rows before the next tile is staged: half the
+// activation reads from the L2, half the staging work and half the barriers per weight.
+constexpr int kBP = RWKVQ_BATCH_PASSES;
+static_assert(kBP == 1 || kBP == 2, "row passes per column tile");
+static_assert(16 * kBW * kBRT * kBP <= 256, "the rows of a workgroup share a 256-row codebook block");
+constexpr int passes_of(int MT) { return MT == 1 ? 1 : kBP; }
+constexpr int wg_rows(int MT) { return 16 * waves_of(MT) * rt_of(MT) * passes_of(MT); }   // rows of W per workgroup
 
 struct DecodeMat {
     const uint32_t* codes;
@@ -406,6 +416,33 @@ __device__ __forceinline__ void tile_pipeline(int KT, Load load, Compute compute
     }
 }
 
+// Batch 2..32 with two row passes per column tile: the units of the pipeline are (tile, pass) pairs, one in
+// flight while one is consumed.  Pass 0 of a tile carries the activation tile (and the codebook) and stages
+// them; pass 1 streams only weights and reads what pass 0 staged.
+template <int J> struct PassTag { static constexpr int value = J; };
+template <class Regs, class Load, class Compute>
+__device__ __forceinline__ void tile_pipeline_two_pass(int KT, Load load, Compute compute) {
+    Regs q0, q1;
+    const int last = KT - 1;
+    __builtin_amdgcn_sched_barrier(0);
+    load(q0, 0, PassTag<0>{});
+    __builtin_amdgcn_sched_barrier(0);
+    for (int T = 0; T < KT; ++T) {
+        load(q1, T, PassTag<1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        compute(q0, T, PassTag<0>{});
+        load(q0, T < last ? T + 1 : last, PassTag<0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        compute(q1, T, PassTag<1>{});
+    }
+}
+template <int DEPTH, class Regs, class Load, class Compute>
+__device__ __forceinline__ void batched_pipeline(int KT, Load load, Compute compute) {
+    if constexpr (kBP == 2) tile_pipeline_two_pass<Regs>(KT, load, compute);
+    else tile_pipeline<DEPTH, Regs>(KT, [&](Regs& r, int T) { load(r, T, PassTag<0>{}); },
+                                    [&](const Regs& r, int T) { compute(r, T, PassTag<0>{}); });
+}
+
 template <int P>
 __device__ __forceinline__ uint32_t vq6_lds_addr(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t m, uint32_t base) {
     // LDS byte address of codebook entry P: (index * 4) | base, base aligned to 256 bytes
@@ -437,6 +474,7 @@ template <int G> struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; 
 // for the tiles past the end of the matrix: worked on again, not stored).
 struct WavePos {
     int R[4], M, lane, tid;
+    int Rn[4];           // batch > 1, second row pass: its row tiles (Rn[i] == R[0] past the end of the matrix)
     bool xbf16;
     int t0, ts, nt;      // split-K (batch 1): this wavefront's column tiles are t0, t0 + ts, ... (nt of them)
     // fused token-shift mix (batch 1): the previous token's activations, the mix weight's indices
@@ -456,16 +494,20 @@ struct WavePos {
 // leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
 template <int MT, int DEPTH, bool XB>
 __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc,
-                                       float4_t (&out)[groups_of(MT)][kBRT]) {
+                                       float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;   // one group: the fragments of both column halves up front
     using Regs = SqRegs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[kBRT];
+    const uint32_t* codes[kBP][kBRT];
+    const uint2_t* sz[kBP][kBRT];
 #pragma unroll
-    for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 384;
-    const uint2_t* sz[kBRT];
+    for (int j = 0; j < kBP; ++j)
 #pragma unroll
-    for (int rt = 0; rt < kBRT; ++rt) sz[rt] = (const uint2_t*)mt.aux + (size_t)wp.R[rt] * KT * 16;
+        for (int rt = 0; rt < kBRT; ++rt) {
+            const int R = j == 0 ? wp.R[rt] : wp.Rn[rt];
+            codes[j][rt] = mt.codes + (size_t)R * KT * 384;
+            sz[j][rt] = (const uint2_t*)mt.aux + (size_t)R * KT * 16;
+        }
     int xoff[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
@@ -476,23 +518,29 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
     const uint4_t ones4 = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
     const half8_t ones = __builtin_bit_cast(half8_t, ones4);
-    auto load = [&](Regs& r, int T) {
+    auto load = [&](Regs& r, int T, auto pass) {
+        constexpr int J = decltype(pass)::value;
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            const uint32_t* t = codes[J][rt] + (size_t)T * 384;
             r.a[rt] = stream_load((const uint4_t*)(t + 4 * lane));
             r.b[rt] = stream_load((const uint2_t*)(t + 256 + 2 * lane));
-            r.sz[rt] = stream_load(sz[rt] + (size_t)T * 16 + (lane & 15));
+            r.sz[rt] = stream_load(sz[J][rt] + (size_t)T * 16 + (lane & 15));
         }
+        if constexpr (J == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
+            for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
+        }
     };
-    auto compute = [&](const Regs& r, int T) {
+    auto compute = [&](const Regs& r, int T, auto pass) {
+        constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
+        if constexpr (J == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
-        __syncthreads();
+            for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
+            __syncthreads();
+        }
         float4_t sc[G];                              // bf16: inverse scale of this tile for the lane's batch rows
 #pragma unroll
         for (int g = 0; g < G; ++g) sc[g] = XB ? *(const float4_t*)(scb + 16 * g + 4 * (lane >> 4)) : float4_t{1, 1, 1, 1};
@@ -532,26 +580,28 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
                         acc = RWKVQ_MFMA(xa[uu][g][2], op2, acc);
                         acc = RWKVQ_MFMA(xa[uu][g][3], op3, acc);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(XB ? s * sc[g][i] : s, fmaf(-z8, X[g][i], acc[i]), out[g][rt][i]);
+                        for (int i = 0; i < 4; ++i) out[J][g][rt][i] = fmaf(XB ? s * sc[g][i] : s, fmaf(-z8, X[g][i], acc[i]), out[J][g][rt][i]);
                     }
                 }
             }
         }
     };
-    tile_pipeline<DEPTH, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, Regs>(KT, load, compute);
 }
 
 // 6-bit VQ: the codebook of a tile (64 entries, one per lane) goes through a wavefront-private LDS
 // slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
 template <int MT, int DEPTH, bool XB>
 __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
-                                        float4_t (&out)[groups_of(MT)][kBRT]) {
+                                        float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;
     using Regs = Vq6Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[kBRT];
+    const uint32_t* codes[kBP][kBRT];
 #pragma unroll
-    for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 384;
+    for (int j = 0; j < kBP; ++j)
+#pragma unroll
+        for (int rt = 0; rt < kBRT; ++rt) codes[j][rt] = mt.codes + (size_t)(j == 0 ? wp.R[rt] : wp.Rn[rt]) * KT * 384;
     const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
     int xoff[G];
 #pragma unroll
@@ -559,28 +609,34 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
     const uint32_t base0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
     uint32_t m;
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
-    auto load = [&](Regs& r, int T) {
+    auto load = [&](Regs& r, int T, auto pass) {
+        constexpr int J = decltype(pass)::value;
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 384;
+            const uint32_t* t = codes[J][rt] + (size_t)T * 384;
             r.a[rt] = stream_load((const uint4_t*)(t + 4 * lane));
             r.b[rt] = stream_load((const uint2_t*)(t + 256 + 2 * lane));
         }
-        r.cb = (cbs + (size_t)T * 64)[lane];
+        if constexpr (J == 0) {
+            r.cb = (cbs + (size_t)T * 64)[lane];
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
+            for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
+        }
     };
-    auto compute = [&](const Regs& r, int T) {
+    auto compute = [&](const Regs& r, int T, auto pass) {
+        constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
+        if constexpr (J == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
-        cb_lds[(T & 1) * 256 + lane] = r.cb;         // two slots, 1 KB apart (the gather address ORs the index in)
-        __syncthreads();
+            for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
+            cb_lds[(T & 1) * 256 + lane] = r.cb;     // two slots, 1 KB apart (the gather address ORs the index in)
+            __syncthreads();
+        }
         const uint32_t base = base0 + (T & 1) * 1024;
         // bf16: the tile's products are summed on their own and join the output through the rows' inverse scales
         float4_t part[G][kBRT];
-        float4_t (&acc)[G][kBRT] = *(XB ? &part : &out);
+        float4_t (&acc)[G][kBRT] = *(XB ? &part : &out[J]);
         if (XB) {
 #pragma unroll
             for (int g = 0; g < G; ++g)
@@ -624,49 +680,57 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
 #pragma unroll
                 for (int rt = 0; rt < kBRT; ++rt)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(part[g][rt][i], sc[i], out[g][rt][i]);
+                    for (int i = 0; i < 4; ++i) out[J][g][rt][i] = fmaf(part[g][rt][i], sc[i], out[J][g][rt][i]);
             }
         }
     };
-    tile_pipeline<DEPTH, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, Regs>(KT, load, compute);
 }
 
 // 8-bit VQ: the codebook of a tile (256 entries) goes through a wavefront-private LDS region; the
 // workgroup barrier that publishes the activations also orders that store before the gathers.
 template <int MT, int DEPTH, bool XB>
 __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
-                                        float4_t (&out)[groups_of(MT)][kBRT]) {
+                                        float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT);
     using Regs = Vq8Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[kBRT];
+    const uint32_t* codes[kBP][kBRT];
 #pragma unroll
-    for (int rt = 0; rt < kBRT; ++rt) codes[rt] = mt.codes + (size_t)wp.R[rt] * KT * 512;
+    for (int j = 0; j < kBP; ++j)
+#pragma unroll
+        for (int rt = 0; rt < kBRT; ++rt) codes[j][rt] = mt.codes + (size_t)(j == 0 ? wp.R[rt] : wp.Rn[rt]) * KT * 512;
     const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
     int xoff[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    auto load = [&](Regs& r, int T) {
+    auto load = [&](Regs& r, int T, auto pass) {
+        constexpr int J = decltype(pass)::value;
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
-            const uint32_t* t = codes[rt] + (size_t)T * 512;
+            const uint32_t* t = codes[J][rt] + (size_t)T * 512;
             r.a[rt] = stream_load((const uint4_t*)(t + 4 * lane));
             r.b[rt] = stream_load((const uint4_t*)(t + 256 + 4 * lane));
         }
-        r.cb = (cbs + (size_t)T * 64)[lane];
+        if constexpr (J == 0) {
+            r.cb = (cbs + (size_t)T * 64)[lane];
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
+            for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
+        }
     };
-    auto compute = [&](const Regs& r, int T) {
+    auto compute = [&](const Regs& r, int T, auto pass) {
+        constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
         uint32_t* cbuf = cb_lds + (T & 1) * 256;     // two codebook slots, like the activations
+        if constexpr (J == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
-        *(uint4_t*)(cbuf + 4 * lane) = r.cb;
-        __syncthreads();
+            for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
+            *(uint4_t*)(cbuf + 4 * lane) = r.cb;
+            __syncthreads();
+        }
         float4_t part[G][kBRT];                      // bf16: as in run_vq6
-        float4_t (&acc)[G][kBRT] = *(XB ? &part : &out);
+        float4_t (&acc)[G][kBRT] = *(XB ? &part : &out[J]);
         if (XB) {
 #pragma unroll
             for (int g = 0; g < G; ++g)
@@ -701,11 +765,11 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
 #pragma unroll
                 for (int rt = 0; rt < kBRT; ++rt)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) out[g][rt][i] = fmaf(part[g][rt][i], sc[i], out[g][rt][i]);
+                    for (int i = 0; i < 4; ++i) out[J][g][rt][i] = fmaf(part[g][rt][i], sc[i], out[J][g][rt][i]);
             }
         }
     };
-    tile_pipeline<DEPTH, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, Regs>(KT, load, compute);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1044,7 +1108,7 @@ __device__ __forceinline__ void run_m1(const DecodeMat& mt, const WavePos& wp, u
 // The same for batch 2..32.
 template <int MT, int DEPTH>
 __device__ __forceinline__ void run_batched(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
-                                            float4_t (&out)[groups_of(MT)][kBRT]) {
+                                            float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
     if (wp.xbf16) {
         if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, true>(mt, wp, xs, xsc, out);
         else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, true>(mt, wp, xs, xsc, cb_lds, out);
@@ -1092,7 +1156,7 @@ __global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kern
     const int NR = mt.N >> 4;
     WavePos wp;
     constexpr int RT = rt_of(MT);
-    wp.R[0] = RT * (waves_of(MT) * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
+    wp.R[0] = RT * (waves_of(MT) * passes_of(MT) * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
     const bool live = wp.R[0] < NR;                // rows beyond N (N not a multiple of the workgroup's rows)
     wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xbf16;
 
@@ -1116,27 +1180,38 @@ __global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kern
         if (!live) wp.R[0] = NR - 1;
 #pragma unroll
         for (int rt = 1; rt < 4; ++rt) wp.R[rt] = (rt < RT && wp.R[0] + rt < NR) ? wp.R[0] + rt : wp.R[0];
+        // second pass: the same positions one stretch of waves_of(MT) * RT row tiles further on
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            const int r2 = wp.R[0] + RT * waves_of(MT) + rt;
+            wp.Rn[rt] = (live && rt < RT && r2 < NR) ? r2 : wp.R[0];
+        }
         constexpr int G = groups_of(MT);
-        float4_t out[G][RT];
+        float4_t out[kBP][G][RT];
 #pragma unroll
-        for (int g = 0; g < G; ++g)
+        for (int j = 0; j < kBP; ++j)
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) out[g][rt] = float4_t{0, 0, 0, 0};
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) out[j][g][rt] = float4_t{0, 0, 0, 0};
         run_batched<MT, DEPTH>(mt, wp, xs, xsc, cb_all[wave], out);
         if (!live) return;
         // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 (of its group) of output column n
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            if (rt > 0 && wp.R[rt] == wp.R[0]) break;
-            const int n = 16 * wp.R[rt] + (lane & 15);
+        for (int j = 0; j < kBP; ++j)
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int rt = 0; rt < RT; ++rt) {
+                const int R = j == 0 ? wp.R[rt] : wp.Rn[rt];
+                if ((j > 0 || rt > 0) && R == wp.R[0]) continue;
+                const int n = 16 * R + (lane & 15);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int m = 16 * g + 4 * (lane >> 4) + i;
-                    if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, out[g][rt][i]);
-                }
-        }
+                for (int g = 0; g < G; ++g)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int m = 16 * g + 4 * (lane >> 4) + i;
+                        if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, out[j][g][rt][i]);
+                    }
+            }
     }
 }
 

@@ -81,6 +81,22 @@ def test_decode_small(fmt, N, K, M, xdt):
     G.check_outputs(y, mat, x, xdt, fed=None, tight=2e-5)
 
 
+@pytest.mark.parametrize("fmt,N,K", [("sq", 176, 512), ("sq", 272, 768), ("sq", 400, 256), ("vq6", 768, 512), ("vq8", 768, 768)])
+@pytest.mark.parametrize("M", [2, 16, 32])
+@pytest.mark.parametrize("xdt", ["f16", "bf16"])
+def test_decode_batched_row_stretches(fmt, N, K, M, xdt, options):
+    """Batch 2..32: a workgroup covers 256 rows of W as two stretches of 128 that share each staged activation
+    tile.  Row counts that end inside the first stretch, inside the second, and one row tile into the next
+    workgroup (SQ rows come in sixteens; VQ in blocks of 256, here three blocks).  The streaming kernels are
+    forced (left alone the dispatcher may send M = 32 to the matrix cores, which round the weights)."""
+    print(f"decode row stretches {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+    options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_STREAM)
+    mat = make(fmt, N, K, 12)
+    x = acts(M, K, xdt, N + M)
+    y = G.gpu_gemm(B.upload(mat, native=True), x, xdt)
+    G.check_outputs(y, mat, x, xdt, fed=None, tight=2e-5)
+
+
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
 @pytest.mark.parametrize("N,K", [(256, 256), (256, 3584), (4096, 512), (4096, 1792), (8192, 256), (8192, 1280), (16384, 512), (65536, 256)])
 def test_decode_batch1_launch_shapes(fmt, N, K):
