@@ -104,10 +104,14 @@ const char* rwkvq_status_string(int status);
  *   RWKVQ_OPT_STREAM_WIDE_MIN_US  least duration of such a pass in microseconds (24)
  *   RWKVQ_OPT_STREAM_NARROW_MIN_US  (12)
  *   RWKVQ_OPT_MFMA_KSTEP_NS       one 64-column step of a 128-row matrix-core workgroup in nanoseconds (1500)
+ *   RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS  batch 2..32 on the streaming kernels: a workgroup covers 256 rows of W
+ *                                 (two stretches that share each staged activation tile) when the launch
+ *                                 still has at least this many workgroups that way, and 128 rows otherwise
+ *                                 (2048; 1 = always 256 rows, 1000000 = never)
  * Errors: RWKVQ_ERR_UNSUPPORTED (unknown option, value out of range), RWKVQ_ERR_NULL. */
 enum { RWKVQ_OPT_SMALL_BATCH_PATH = 0, RWKVQ_OPT_PREFILL_TILE_ROWS = 1, RWKVQ_OPT_STREAM_WIDE_GBPS = 2,
        RWKVQ_OPT_STREAM_NARROW_GBPS = 3, RWKVQ_OPT_STREAM_WIDE_MIN_US = 4, RWKVQ_OPT_STREAM_NARROW_MIN_US = 5,
-       RWKVQ_OPT_MFMA_KSTEP_NS = 6 };
+       RWKVQ_OPT_MFMA_KSTEP_NS = 6, RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS = 7 };
 enum { RWKVQ_SMALL_BATCH_AUTO = 0, RWKVQ_SMALL_BATCH_STREAM = 1, RWKVQ_SMALL_BATCH_MATRIX_CORES = 2 };
 int rwkvq_set_option(int option, int value);
 int rwkvq_get_option(int option, int* value /* host */);

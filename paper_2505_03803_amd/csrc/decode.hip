@@ -35,6 +35,7 @@
 //   * bf16 activations are converted to fp16 on load, group by group under an exact power-of-two
 //     scale (see "bf16 activations" below), so their whole range is accepted.
 #include "common.h"
+#include "../../include/rwkvq.h"
 #include <algorithm>
 
 namespace rwkvq {
@@ -89,17 +90,15 @@ constexpr int rt_of(int MT) { return MT == 1 ? kRT : kBRT; }
 constexpr int kBW = RWKVQ_BATCH_WAVES;
 static_assert(kBW == 4 || kBW == 8, "sixteen or thirty-two threads stage a batch row");
 constexpr int waves_of(int MT) { return MT == 1 ? 4 : kBW; }
-#ifndef RWKVQ_BATCH_PASSES
-#define RWKVQ_BATCH_PASSES 2
-#endif
-// Batch 2..32: row passes of a workgroup per column tile (1 or 2).  With two, the staged activation tile (and,
-// for VQ, the tile's codebook) serves a second stretch of rows before the next tile is staged: half the
-// activation reads from the L2, half the staging work and half the barriers per weight.
-constexpr int kBP = RWKVQ_BATCH_PASSES;
-static_assert(kBP == 1 || kBP == 2, "row passes per column tile");
-static_assert(16 * kBW * kBRT * kBP <= 256, "the rows of a workgroup share a 256-row codebook block");
-constexpr int passes_of(int MT) { return MT == 1 ? 1 : kBP; }
-constexpr int wg_rows(int MT) { return 16 * waves_of(MT) * rt_of(MT) * passes_of(MT); }   // rows of W per workgroup
+// Batch 2..32: row passes of a workgroup per column tile (1 or 2, a template parameter of the kernel).  With two,
+// the staged activation tile (and, for VQ, the tile's codebook) serves a second stretch of rows before the
+// next tile is staged: half the activation reads from the L2, half the staging work and half the barriers
+// per weight (configuration 5 at batch 16: 4.44 -> 4.79 TB/s).  The launcher takes two passes when the launch
+// still has RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS workgroups that way (2048 unless set), and one otherwise: a single
+// 4096 x 4096 matrix is 32 workgroups of 128 rows, and halving that count costs more than the staging saves
+// (25 -> 40 us at 17..32 rows).
+constexpr bool kTwoPassFits = 16 * kBW * kBRT * 2 <= 256;   // the rows of a workgroup share a 256-row codebook block
+constexpr int wg_rows(int MT, int P = 1) { return 16 * waves_of(MT) * rt_of(MT) * (MT == 1 ? 1 : P); }   // rows of W per workgroup
 
 struct DecodeMat {
     const uint32_t* codes;
@@ -436,9 +435,10 @@ __device__ __forceinline__ void tile_pipeline_two_pass(int KT, Load load, Comput
         compute(q1, T, PassTag<1>{});
     }
 }
-template <int DEPTH, class Regs, class Load, class Compute>
+template <int DEPTH, int P, class Regs, class Load, class Compute>
 __device__ __forceinline__ void batched_pipeline(int KT, Load load, Compute compute) {
-    if constexpr (kBP == 2) tile_pipeline_two_pass<Regs>(KT, load, compute);
+    static_assert(P == 1 || P == 2, "row passes per column tile");
+    if constexpr (P == 2) tile_pipeline_two_pass<Regs>(KT, load, compute);
     else tile_pipeline<DEPTH, Regs>(KT, [&](Regs& r, int T) { load(r, T, PassTag<0>{}); },
                                     [&](const Regs& r, int T) { compute(r, T, PassTag<0>{}); });
 }
@@ -492,16 +492,16 @@ struct WavePos {
 // SQ: the codes enter as 8 + q (one shift and one and-or per pair).  The group sums of the
 // activations come from the matrix cores too: one more MFMA per k-step with an all-ones B operand
 // leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
-template <int MT, int DEPTH, bool XB>
+template <int MT, int DEPTH, bool XB, int P>
 __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc,
-                                       float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
+                                       float4_t (&out)[P][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;   // one group: the fragments of both column halves up front
     using Regs = SqRegs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[kBP][kBRT];
-    const uint2_t* sz[kBP][kBRT];
+    const uint32_t* codes[P][kBRT];
+    const uint2_t* sz[P][kBRT];
 #pragma unroll
-    for (int j = 0; j < kBP; ++j)
+    for (int j = 0; j < P; ++j)
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const int R = j == 0 ? wp.R[rt] : wp.Rn[rt];
@@ -586,20 +586,20 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
             }
         }
     };
-    batched_pipeline<DEPTH, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, P, Regs>(KT, load, compute);
 }
 
 // 6-bit VQ: the codebook of a tile (64 entries, one per lane) goes through a wavefront-private LDS
 // slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
-template <int MT, int DEPTH, bool XB>
+template <int MT, int DEPTH, bool XB, int P>
 __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
-                                        float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
+                                        float4_t (&out)[P][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;
     using Regs = Vq6Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[kBP][kBRT];
+    const uint32_t* codes[P][kBRT];
 #pragma unroll
-    for (int j = 0; j < kBP; ++j)
+    for (int j = 0; j < P; ++j)
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) codes[j][rt] = mt.codes + (size_t)(j == 0 ? wp.R[rt] : wp.Rn[rt]) * KT * 384;
     const uint32_t* cbs = (const uint32_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
@@ -684,20 +684,20 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
             }
         }
     };
-    batched_pipeline<DEPTH, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, P, Regs>(KT, load, compute);
 }
 
 // 8-bit VQ: the codebook of a tile (256 entries) goes through a wavefront-private LDS region; the
 // workgroup barrier that publishes the activations also orders that store before the gathers.
-template <int MT, int DEPTH, bool XB>
+template <int MT, int DEPTH, bool XB, int P>
 __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
-                                        float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
+                                        float4_t (&out)[P][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT);
     using Regs = Vq8Regs<G>;
     const int KT = mt.K >> 8, lane = wp.lane, M = wp.M;
-    const uint32_t* codes[kBP][kBRT];
+    const uint32_t* codes[P][kBRT];
 #pragma unroll
-    for (int j = 0; j < kBP; ++j)
+    for (int j = 0; j < P; ++j)
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) codes[j][rt] = mt.codes + (size_t)(j == 0 ? wp.R[rt] : wp.Rn[rt]) * KT * 512;
     const uint4_t* cbs = (const uint4_t*)mt.aux + (size_t)(wp.R[0] >> 4) * KT * 64;
@@ -769,7 +769,7 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
             }
         }
     };
-    batched_pipeline<DEPTH, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, P, Regs>(KT, load, compute);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1106,17 +1106,17 @@ __device__ __forceinline__ void run_m1(const DecodeMat& mt, const WavePos& wp, u
     }
 }
 // The same for batch 2..32.
-template <int MT, int DEPTH>
+template <int MT, int DEPTH, int P>
 __device__ __forceinline__ void run_batched(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
-                                            float4_t (&out)[kBP][groups_of(MT)][kBRT]) {
+                                            float4_t (&out)[P][groups_of(MT)][kBRT]) {
     if (wp.xbf16) {
-        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, true>(mt, wp, xs, xsc, out);
-        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, true>(mt, wp, xs, xsc, cb_lds, out);
-        else run_vq8<MT, DEPTH, true>(mt, wp, xs, xsc, cb_lds, out);
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, true, P>(mt, wp, xs, xsc, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, true, P>(mt, wp, xs, xsc, cb_lds, out);
+        else run_vq8<MT, DEPTH, true, P>(mt, wp, xs, xsc, cb_lds, out);
     } else {
-        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, false>(mt, wp, xs, xsc, out);
-        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, false>(mt, wp, xs, xsc, cb_lds, out);
-        else run_vq8<MT, DEPTH, false>(mt, wp, xs, xsc, cb_lds, out);
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, false, P>(mt, wp, xs, xsc, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, false, P>(mt, wp, xs, xsc, cb_lds, out);
+        else run_vq8<MT, DEPTH, false, P>(mt, wp, xs, xsc, cb_lds, out);
     }
 }
 
@@ -1130,8 +1130,9 @@ constexpr int min_blocks(int MT) {
 // MT = number of activation rows carried (1, 4, 16 or 32 >= M).  MT = 1 runs every format on the
 // vector ALU (run_*_m1); the others on the matrix cores, whose D layout is: lane holds batch rows
 // 4*(lane/16) + i of output column lane%16.
-template <int MT>
+template <int MT, int P = 1>
 __global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kernel(DecodeArgs a) {
+    static_assert(MT > 1 || P == 1, "batch 1 has no staged activation tile to share");
     constexpr int DEPTH = MT == 1 ? RWKVQ_DECODE_DEPTH : RWKVQ_BATCH_DEPTH;
     // batch > 1: two activation tiles shared by the workgroup; codebook slots per wavefront
     __shared__ __attribute__((aligned(16))) half_t xs[MT == 1 ? 8 : 2 * MT * kXStride];
@@ -1156,7 +1157,7 @@ __global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kern
     const int NR = mt.N >> 4;
     WavePos wp;
     constexpr int RT = rt_of(MT);
-    wp.R[0] = RT * (waves_of(MT) * passes_of(MT) * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
+    wp.R[0] = RT * (waves_of(MT) * P * (wg - (mi ? a.wg_end[mi - 1] : 0)) + wave);
     const bool live = wp.R[0] < NR;                // rows beyond N (N not a multiple of the workgroup's rows)
     wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xbf16;
 
@@ -1187,18 +1188,18 @@ __global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kern
             wp.Rn[rt] = (live && rt < RT && r2 < NR) ? r2 : wp.R[0];
         }
         constexpr int G = groups_of(MT);
-        float4_t out[kBP][G][RT];
+        float4_t out[P][G][RT];
 #pragma unroll
-        for (int j = 0; j < kBP; ++j)
+        for (int j = 0; j < P; ++j)
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) out[j][g][rt] = float4_t{0, 0, 0, 0};
-        run_batched<MT, DEPTH>(mt, wp, xs, xsc, cb_all[wave], out);
+        run_batched<MT, DEPTH, P>(mt, wp, xs, xsc, cb_all[wave], out);
         if (!live) return;
         // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 (of its group) of output column n
 #pragma unroll
-        for (int j = 0; j < kBP; ++j)
+        for (int j = 0; j < P; ++j)
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 const int R = j == 0 ? wp.R[rt] : wp.Rn[rt];
@@ -1434,10 +1435,18 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         for (int i = 0; i < cnt; ++i) tiles += (mats[order[i]].N + 15) / 16;
         int split = 0;
         if (M == 1 && tiles < kSplitTarget) split = pick_split(tiles);
+        // batch > 1: two row passes per workgroup if the launch keeps enough workgroups that way
+        int passes = 1;
+        if (M > 1) {
+            long long wgs2 = 0;
+            for (int i = 0; i < cnt; ++i) wgs2 += (mats[order[i]].N + wg_rows(M, 2) - 1) / wg_rows(M, 2);
+            if (kTwoPassFits && wgs2 >= option(RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS)) passes = 2;
+        }
+        const int rows = wg_rows(M, passes);
         int wgs = 0;
         for (int i = 0; i < cnt; ++i) {
             const MatDev& m = mats[order[i]];
-            wgs += split ? (m.N + 15) / 16 : (m.N + wg_rows(M) - 1) / wg_rows(M);
+            wgs += split ? (m.N + 15) / 16 : (m.N + rows - 1) / rows;
             a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, posts ? posts[order[i]].op : POST_NONE,
                                posts ? posts[order[i]].gate : nullptr};
             a.wg_end[i] = wgs;
@@ -1447,11 +1456,15 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
             a.wg_end[i] = 0x7FFFFFFF;
         }
         a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
+        const dim3 grid(wgs), wide(64 * kBW);
         if (split) { hipError_t e = launch_splitk(split, wgs, a, s); if (e != hipSuccess) return e; }
-        else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, dim3(wgs), dim3(256), 0, s, a);
-        else if (M <= 4) hipLaunchKernelGGL(decode_kernel<4>, dim3(wgs), dim3(64 * kBW), 0, s, a);
-        else if (M <= 16) hipLaunchKernelGGL(decode_kernel<16>, dim3(wgs), dim3(64 * kBW), 0, s, a);
-        else hipLaunchKernelGGL(decode_kernel<32>, dim3(wgs), dim3(64 * kBW), 0, s, a);
+        else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, grid, dim3(256), 0, s, a);
+        else if (M <= 4 && passes == 1) hipLaunchKernelGGL((decode_kernel<4, 1>), grid, wide, 0, s, a);
+        else if (M <= 4) hipLaunchKernelGGL((decode_kernel<4, 2>), grid, wide, 0, s, a);
+        else if (M <= 16 && passes == 1) hipLaunchKernelGGL((decode_kernel<16, 1>), grid, wide, 0, s, a);
+        else if (M <= 16) hipLaunchKernelGGL((decode_kernel<16, 2>), grid, wide, 0, s, a);
+        else if (passes == 1) hipLaunchKernelGGL((decode_kernel<32, 1>), grid, wide, 0, s, a);
+        else hipLaunchKernelGGL((decode_kernel<32, 2>), grid, wide, 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

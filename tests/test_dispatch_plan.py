@@ -99,6 +99,8 @@ def test_option_rejects():
     assert B.rwkvq_set_option(B.OPT_SMALL_BATCH_PATH, 3, check=False) == B.ERR_UNSUPPORTED
     assert B.rwkvq_set_option(B.OPT_PREFILL_TILE_ROWS, 64, check=False) == B.ERR_UNSUPPORTED
     assert B.rwkvq_set_option(B.OPT_STREAM_WIDE_GBPS, -5, check=False) == B.ERR_UNSUPPORTED
+    assert B.rwkvq_set_option(B.OPT_STREAM_TWO_PASS_MIN_WGS, 1000001, check=False) == B.ERR_UNSUPPORTED
+    assert B.rwkvq_get_option(B.OPT_STREAM_TWO_PASS_MIN_WGS) == 2048
     assert B.lib().rwkvq_get_option(0, None) == B.ERR_NULL
 
 

@@ -26,6 +26,17 @@ def acts(M, K, dtype, seed):
 
 FORCE = {None: B.SMALL_BATCH_AUTO, "stream": B.SMALL_BATCH_STREAM, "mfma": B.SMALL_BATCH_MATRIX_CORES}
 
+
+
+@pytest.fixture(params=[1, 1000000], ids=["256-row-workgroups", "128-row-workgroups"])
+def stretches(request, options):
+    """Batch 2..32 on the streaming kernels: a workgroup covers two row stretches of 128 per staged activation
+    tile when the launch is large enough (RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS workgroups), else one.  The test
+    shapes are small launches, so both instances are forced in turn."""
+    options(B.OPT_STREAM_TWO_PASS_MIN_WGS, request.param)
+    return request.param
+
+
 SMALL = [("sq", 48, 768), ("sq", 256, 256), ("vq6", 256, 768), ("vq6", 512, 256), ("vq8", 256, 768),
          ("vq8", 512, 512)]
 
@@ -73,8 +84,8 @@ def test_dequant_rounding_order_cases(golden_dir):
 @pytest.mark.parametrize("fmt,N,K", SMALL)
 @pytest.mark.parametrize("M", [1, 3, 4, 7, 16])
 @pytest.mark.parametrize("xdt", ["f16", "bf16"])
-def test_decode_small(fmt, N, K, M, xdt):
-    print(f"decode {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+def test_decode_small(fmt, N, K, M, xdt, stretches):
+    print(f"decode {fmt} N={N} K={K} M={M} x={xdt} two-pass threshold {stretches}", flush=True)
     mat = make(fmt, N, K, 2)
     x = acts(M, K, xdt, M)
     y = G.gpu_gemm(B.upload(mat, native=True), x, xdt)
@@ -84,12 +95,12 @@ def test_decode_small(fmt, N, K, M, xdt):
 @pytest.mark.parametrize("fmt,N,K", [("sq", 176, 512), ("sq", 272, 768), ("sq", 400, 256), ("vq6", 768, 512), ("vq8", 768, 768)])
 @pytest.mark.parametrize("M", [2, 16, 32])
 @pytest.mark.parametrize("xdt", ["f16", "bf16"])
-def test_decode_batched_row_stretches(fmt, N, K, M, xdt, options):
+def test_decode_batched_row_stretches(fmt, N, K, M, xdt, options, stretches):
     """Batch 2..32: a workgroup covers 256 rows of W as two stretches of 128 that share each staged activation
     tile.  Row counts that end inside the first stretch, inside the second, and one row tile into the next
     workgroup (SQ rows come in sixteens; VQ in blocks of 256, here three blocks).  The streaming kernels are
     forced (left alone the dispatcher may send M = 32 to the matrix cores, which round the weights)."""
-    print(f"decode row stretches {fmt} N={N} K={K} M={M} x={xdt}", flush=True)
+    print(f"decode row stretches {fmt} N={N} K={K} M={M} x={xdt} two-pass threshold {stretches}", flush=True)
     options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_STREAM)
     mat = make(fmt, N, K, 12)
     x = acts(M, K, xdt, N + M)
@@ -375,7 +386,7 @@ def rowwise_g2(y, ref):
 
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
 @pytest.mark.parametrize("M", [1, 6, 16, 32, 48])
-def test_bf16_activations_of_any_magnitude(fmt, M, options):
+def test_bf16_activations_of_any_magnitude(fmt, M, options, stretches):
     """Every finite bf16 activation is in contract.  The streaming kernels multiply fp16 operands: they
     must bring the activations into fp16's range with exact scales, so that a row of tiny values, a
     row of huge ones and rows that mix both all come out as the oracle computes them - row by row,
