@@ -80,9 +80,17 @@ __global__ void __launch_bounds__(kSortThreads) sort_hist_kernel(const uint32_t*
         uint32_t k = valid ? in[i] : 0u;
         if (FIRST) k = f32_key(k);
         const uint32_t d = (k >> shift) & 255u;
-        const unsigned long long m = same_digit_lanes(d, valid);
-        // one addition per digit value and wavefront: the first lane of each group adds the group's size
-        if (valid && (m & lanes_below(lane)) == 0ull) atomicAdd(&h[d], (uint32_t)__builtin_popcountll(m));
+        // Counting needs no order: one LDS addition per key, except that a wavefront whose valid lanes all hold
+        // the same digit (the low bytes of binary32 patterns that came from 16-bit values, a run of equal
+        // weights) adds once - 64 additions to one address would be served one after the other.
+        const unsigned long long live = __builtin_amdgcn_ballot_w64(valid);
+        const uint32_t d0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)d);      // digit of the first valid lane
+        const unsigned long long same = __builtin_amdgcn_ballot_w64(valid && d == d0);
+        if (same == live) {
+            if (valid && (live & lanes_below(lane)) == 0ull) atomicAdd(&h[d], (uint32_t)__builtin_popcountll(live));
+        } else if (valid) {
+            atomicAdd(&h[d], 1u);
+        }
     }
     __syncthreads();
     counts[(size_t)tid * n_tiles + blockIdx.x] = h[tid];
