@@ -318,7 +318,7 @@ hipError_t launch_proxy_f32(const void* const* ws, const int* Ns, const int* Ks,
     double* partial = (double*)(base + L.partial);
     for (int i = 0; i < n_mats; ++i) {
         const uint32_t count = (uint32_t)((unsigned long long)Ns[i] * (unsigned long long)Ks[i]);
-        const uint32_t tiles = (count + kSortTile - 1) / kSortTile;
+        const uint32_t tiles = (uint32_t)(((unsigned long long)count + kSortTile - 1) / kSortTile);   // count may be 2^32 - 1
         const uint32_t* src = (const uint32_t*)ws[i];
         for (int pass = 0; pass < 4; ++pass) {
             uint32_t* dst = buf[pass & 1];
@@ -332,7 +332,7 @@ hipError_t launch_proxy_f32(const void* const* ws, const int* Ns, const int* Ks,
             if (e != hipSuccess) return e;
             src = dst;
         }
-        const uint32_t gap_tiles = (count - 1u + kGapTile - 1) / kGapTile;
+        const uint32_t gap_tiles = (uint32_t)(((unsigned long long)count - 1 + kGapTile - 1) / kGapTile);
         hipLaunchKernelGGL(gap_sum_kernel, dim3(gap_tiles), dim3(kGapThreads), 0, s, src, count, terms, partial);
         hipLaunchKernelGGL(gap_final_kernel, dim3(1), dim3(256), 0, s, src, count, terms, partial, gap_tiles, tau_c, tau_f,
                            out + 2 * i, phi + i);
