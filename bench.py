@@ -8,7 +8,8 @@ by a seeded coin flip) through rwkvq_linear_dispatch:
     exactly --steps timed steps after --warmup untimed ones; metric = packed weight bytes read per second
     (GB/s) and the fraction of the 8 TB/s HBM peak.  `steady_state` holds the same step timed over a long
     region of its own (run first: the device leaves the clock transient that follows idle there);
-  * `decode_batched`: the same matrices at batch 4, 16, 32, 64; `sequential_step`: in data-flow order;
+  * `decode_batched`: the same matrices at batch 4, 16, 32, 64, and at batch 4 and 16 as the 128 stage-sized launches a
+    model would make (`M*_stage_ordered`); `sequential_step`: batch 1 in data-flow order;
   * `config1`, `config2`: the single-matrix configurations, cache-hot, HBM-cold (rotated copies) and grouped;
   * `prefill`: the same matrix recipe at M = 2048 tokens, bf16 activations, bf16 MFMA with binary32
     accumulate; metric = 2*M*N*K FLOP per second and the fraction of the 2.5 PFLOP/s dense bf16 peak;
@@ -444,6 +445,33 @@ def batched_decode(dec):
         res[f"M{M}"] = {"ms_per_step": ms, "weight_GBps": dec["wbytes"] / (ms * 1e-3) / 1e9, "tokens_per_s": M * 1e3 / ms}
         del xs, ys, table
     res["note"] = "same 256 matrices, one rwkvq_linear_dispatch call per step; weight_GBps counts the packed weights once per step"
+    # The same matrices as the launches a model would make: per layer {r, k, v, g}, then o, then {k', r'}, then v'
+    # (4 dispatches per layer, each waiting for the one before; no element-wise operators in between), replayed
+    # from one HIP graph.  These are small launches: the streaming kernels take their column-split form.
+    n_layers = len(dec["descs"]) // 8
+    for M in (4, 16):
+        tables = []
+        for layer in range(n_layers):
+            for ids in ((0, 1, 2, 3), (4,), (5, 7), (6,)):
+                ds = [dec["descs"][8 * layer + i] for i in ids]
+                xs = [torch.randn((M, int(d.K)), device="cuda", generator=gen).to(torch.float16).view(torch.int16) for d in ds]
+                ys = [torch.empty((M, int(d.N)), dtype=torch.int16, device="cuda") for d in ds]
+                tables.append((B.DispatchTable(ds, xs, ys), xs, ys))
+
+        def step():
+            for t, _, _ in tables:
+                B.rwkvq_linear_dispatch(t, M, B.F16, B.F16)
+
+        step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        total, _, _ = time_steps(graph.replay, 300, 100)
+        ms = total / 300
+        res[f"M{M}_stage_ordered"] = {"ms_per_step": ms, "weight_GBps": dec["wbytes"] / (ms * 1e-3) / 1e9, "tokens_per_s": M * 1e3 / ms,
+                                      "launches_per_step": len(tables)}
+        del tables, graph
     return res
 
 

@@ -338,6 +338,34 @@ __device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, float* 
 template <class T>
 __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
 
+// Batch 2..16, small launches (decode_splitk_batched_kernel): a wavefront takes its A operands straight from global
+// memory in the layout the MFMA wants - lane (m, kg) = (lane % 16, lane / 16) holds, for column half u and k-step t of
+// a 256-column tile, the eight consecutive activations 128 u + 32 t + 8 kg ... of batch row m (rows beyond M repeat
+// row M - 1) - so nothing is staged in LDS and no workgroup barrier is needed: f[4 u + t].
+struct XFrags { uint4_t f[8]; };
+__device__ __forceinline__ void x_load_frags(XFrags& r, const uint16_t* x, int M, int K, int T, int lane) {
+    const int m = (lane & 15) < M ? (lane & 15) : M - 1;
+    const uint16_t* p = x + (size_t)m * K + 256 * T + 8 * (lane >> 4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r.f[i] = *(const uint4_t*)(p + 128 * (i >> 2) + 32 * (i & 3));
+}
+// bf16 fragments -> fp16, scaled by the power of two of the batch row's largest magnitude in this tile (the four lanes
+// that hold a row agree through two exchanges); lane m < 16 leaves the row's inverse scale in scw[m].
+__device__ __forceinline__ void x_frags_to_f16(XFrags& r, float* scw, int lane) {
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = max(amax, max(bf16x2_absmax(r.f[i].x, r.f[i].y), bf16x2_absmax(r.f[i].z, r.f[i].w)));
+    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 16, 64));
+    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32, 64));
+    const int n = bf16_scale_exponent(amax);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        r.f[i].x = bf16x2_to_f16x2(r.f[i].x, n); r.f[i].y = bf16x2_to_f16x2(r.f[i].y, n);
+        r.f[i].z = bf16x2_to_f16x2(r.f[i].z, n); r.f[i].w = bf16x2_to_f16x2(r.f[i].w, n);
+    }
+    if (lane < 16) scw[lane] = ldexpf(1.0f, -n);
+}
+
 // v_dot2_f32_f16 on two packed fp16 pairs.
 __device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {   // two fp16 pairs, scalars in
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
@@ -466,9 +494,9 @@ __device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_
 
 // G = groups of 16 batch rows (1 for batch <= 16, 2 for batch 17..32)
 constexpr int groups_of(int MT) { return MT <= 16 ? 1 : MT / 16; }
-template <int G> struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x[G]; };
-template <int G> struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x[G]; };
-template <int G> struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x[G]; };
+template <int G> struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x[G]; XFrags xf; };
+template <int G> struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x[G]; XFrags xf; };
+template <int G> struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x[G]; XFrags xf; };
 
 // Everything a tile loop needs about its wavefront's position; R[i] are its row tiles (R[i] == R[0]
 // for the tiles past the end of the matrix: worked on again, not stored).
@@ -492,7 +520,7 @@ struct WavePos {
 // SQ: the codes enter as 8 + q (one shift and one and-or per pair).  The group sums of the
 // activations come from the matrix cores too: one more MFMA per k-step with an all-ones B operand
 // leaves X_g[m] in the accumulator layout of the products, and y += s (acc - (8 + z) X_g).
-template <int MT, int DEPTH, bool XB, int P>
+template <int MT, int DEPTH, bool XB, int P, bool DIRECT = false>
 __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc,
                                        float4_t (&out)[P][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;   // one group: the fragments of both column halves up front
@@ -518,8 +546,10 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
     const uint4_t ones4 = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
     const half8_t ones = __builtin_bit_cast(half8_t, ones4);
+    static_assert(!DIRECT || (G == 1 && P == 1), "fragments from global memory: one group of batch rows, one row pass");
     auto load = [&](Regs& r, int T, auto pass) {
         constexpr int J = decltype(pass)::value;
+        if constexpr (DIRECT) T = wp.t0 + T * wp.ts;     // this wavefront's column tiles
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[J][rt] + (size_t)T * 384;
@@ -527,7 +557,9 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
             r.b[rt] = stream_load((const uint2_t*)(t + 256 + 2 * lane));
             r.sz[rt] = stream_load(sz[J][rt] + (size_t)T * 16 + (lane & 15));
         }
-        if constexpr (J == 0) {
+        if constexpr (DIRECT) {
+            x_load_frags(r.xf, (const uint16_t*)mt.x, M, mt.K, T, lane);
+        } else if constexpr (J == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
         }
@@ -536,7 +568,11 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
         constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
-        if constexpr (J == 0) {
+        XFrags xf;
+        if constexpr (DIRECT) {
+            xf = r.xf;
+            if (XB) { x_frags_to_f16(xf, scb, lane); wave_lds_sync(); }
+        } else if constexpr (J == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
             __syncthreads();
@@ -552,7 +588,8 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
 #pragma unroll
                 for (int g = 0; g < G; ++g)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) xa[uu][g][t] = *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
+                    for (int t = 0; t < 4; ++t)
+                        xa[uu][g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf.f[4 * (ub + uu) + t]) : *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
 #pragma unroll
             for (int uu = 0; uu < UB; ++uu) {
                 const int u = ub + uu;
@@ -586,12 +623,12 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
             }
         }
     };
-    batched_pipeline<DEPTH, P, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, P, Regs>(DIRECT ? wp.nt : KT, load, compute);
 }
 
 // 6-bit VQ: the codebook of a tile (64 entries, one per lane) goes through a wavefront-private LDS
 // slot and every weight pair is one ds_read_b32 gather (cheaper on this part than ds_bpermute).
-template <int MT, int DEPTH, bool XB, int P>
+template <int MT, int DEPTH, bool XB, int P, bool DIRECT = false>
 __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
                                         float4_t (&out)[P][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT), UB = (G == 1 && RWKVQ_BATCH_UB2) ? 2 : 1;
@@ -609,15 +646,20 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
     const uint32_t base0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
     uint32_t m;
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
+    static_assert(!DIRECT || (G == 1 && P == 1), "fragments from global memory: one group of batch rows, one row pass");
     auto load = [&](Regs& r, int T, auto pass) {
         constexpr int J = decltype(pass)::value;
+        if constexpr (DIRECT) T = wp.t0 + T * wp.ts;     // this wavefront's column tiles
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[J][rt] + (size_t)T * 384;
             r.a[rt] = stream_load((const uint4_t*)(t + 4 * lane));
             r.b[rt] = stream_load((const uint2_t*)(t + 256 + 2 * lane));
         }
-        if constexpr (J == 0) {
+        if constexpr (DIRECT) {
+            r.cb = (cbs + (size_t)T * 64)[lane];
+            x_load_frags(r.xf, (const uint16_t*)mt.x, M, mt.K, T, lane);
+        } else if constexpr (J == 0) {
             r.cb = (cbs + (size_t)T * 64)[lane];
 #pragma unroll
             for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
@@ -627,7 +669,13 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
         constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
-        if constexpr (J == 0) {
+        XFrags xf;
+        if constexpr (DIRECT) {
+            xf = r.xf;
+            if (XB) x_frags_to_f16(xf, scb, lane);
+            cb_lds[(T & 1) * 256 + lane] = r.cb;
+            wave_lds_sync();
+        } else if constexpr (J == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
             cb_lds[(T & 1) * 256 + lane] = r.cb;     // two slots, 1 KB apart (the gather address ORs the index in)
@@ -651,7 +699,8 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
 #pragma unroll
                 for (int g = 0; g < G; ++g)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) xa[uu][g][t] = *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
+                    for (int t = 0; t < 4; ++t)
+                        xa[uu][g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf.f[4 * (ub + uu) + t]) : *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
 #pragma unroll
             for (int uu = 0; uu < UB; ++uu) {
                 const int u = ub + uu;
@@ -684,12 +733,12 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
             }
         }
     };
-    batched_pipeline<DEPTH, P, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, P, Regs>(DIRECT ? wp.nt : KT, load, compute);
 }
 
 // 8-bit VQ: the codebook of a tile (256 entries) goes through a wavefront-private LDS region; the
 // workgroup barrier that publishes the activations also orders that store before the gathers.
-template <int MT, int DEPTH, bool XB, int P>
+template <int MT, int DEPTH, bool XB, int P, bool DIRECT = false>
 __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
                                         float4_t (&out)[P][groups_of(MT)][kBRT]) {
     constexpr int G = groups_of(MT);
@@ -704,15 +753,20 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
     int xoff[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
+    static_assert(!DIRECT || (G == 1 && P == 1), "fragments from global memory: one group of batch rows, one row pass");
     auto load = [&](Regs& r, int T, auto pass) {
         constexpr int J = decltype(pass)::value;
+        if constexpr (DIRECT) T = wp.t0 + T * wp.ts;     // this wavefront's column tiles
 #pragma unroll
         for (int rt = 0; rt < kBRT; ++rt) {
             const uint32_t* t = codes[J][rt] + (size_t)T * 512;
             r.a[rt] = stream_load((const uint4_t*)(t + 4 * lane));
             r.b[rt] = stream_load((const uint4_t*)(t + 256 + 4 * lane));
         }
-        if constexpr (J == 0) {
+        if constexpr (DIRECT) {
+            r.cb = (cbs + (size_t)T * 64)[lane];
+            x_load_frags(r.xf, (const uint16_t*)mt.x, M, mt.K, T, lane);
+        } else if constexpr (J == 0) {
             r.cb = (cbs + (size_t)T * 64)[lane];
 #pragma unroll
             for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
@@ -723,7 +777,13 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
         uint32_t* cbuf = cb_lds + (T & 1) * 256;     // two codebook slots, like the activations
-        if constexpr (J == 0) {
+        XFrags xf;
+        if constexpr (DIRECT) {
+            xf = r.xf;
+            if (XB) x_frags_to_f16(xf, scb, lane);
+            *(uint4_t*)(cbuf + 4 * lane) = r.cb;
+            wave_lds_sync();
+        } else if constexpr (J == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
             *(uint4_t*)(cbuf + 4 * lane) = r.cb;
@@ -743,7 +803,8 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) xa[g][t] = *(const half8_t*)(buf + xoff[g] + 128 * u + 32 * t);
+                for (int t = 0; t < 4; ++t)
+                    xa[g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf.f[4 * u + t]) : *(const half8_t*)(buf + xoff[g] + 128 * u + 32 * t);
 #pragma unroll
             for (int rt = 0; rt < kBRT; ++rt) {
                 const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
@@ -769,7 +830,7 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
             }
         }
     };
-    batched_pipeline<DEPTH, P, Regs>(KT, load, compute);
+    batched_pipeline<DEPTH, P, Regs>(DIRECT ? wp.nt : KT, load, compute);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1105,18 +1166,18 @@ __device__ __forceinline__ void run_m1(const DecodeMat& mt, const WavePos& wp, u
         else run_vq8_m1<DEPTH, SPLIT, MIXED, false>(mt, wp, cb_lds, part);
     }
 }
-// The same for batch 2..32.
-template <int MT, int DEPTH, int P>
+// The same for batch 2..32.  DIRECT: the split-K form (activation fragments from global memory, see XFrags).
+template <int MT, int DEPTH, int P, bool DIRECT = false>
 __device__ __forceinline__ void run_batched(const DecodeMat& mt, const WavePos& wp, half_t* xs, float* xsc, uint32_t* cb_lds,
                                             float4_t (&out)[P][groups_of(MT)][kBRT]) {
     if (wp.xbf16) {
-        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, true, P>(mt, wp, xs, xsc, out);
-        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, true, P>(mt, wp, xs, xsc, cb_lds, out);
-        else run_vq8<MT, DEPTH, true, P>(mt, wp, xs, xsc, cb_lds, out);
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, true, P, DIRECT>(mt, wp, xs, xsc, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, true, P, DIRECT>(mt, wp, xs, xsc, cb_lds, out);
+        else run_vq8<MT, DEPTH, true, P, DIRECT>(mt, wp, xs, xsc, cb_lds, out);
     } else {
-        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, false, P>(mt, wp, xs, xsc, out);
-        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, false, P>(mt, wp, xs, xsc, cb_lds, out);
-        else run_vq8<MT, DEPTH, false, P>(mt, wp, xs, xsc, cb_lds, out);
+        if (mt.fmt == FMT_SQ3) run_sq<MT, DEPTH, false, P, DIRECT>(mt, wp, xs, xsc, out);
+        else if (mt.fmt == FMT_VQ6) run_vq6<MT, DEPTH, false, P, DIRECT>(mt, wp, xs, xsc, cb_lds, out);
+        else run_vq8<MT, DEPTH, false, P, DIRECT>(mt, wp, xs, xsc, cb_lds, out);
     }
 }
 
@@ -1266,6 +1327,61 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
         for (int s = 1; s < S; ++s) t += red[s][lane];
         if constexpr (Args::kPostMix) store_post_mix(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t, pre);
         else store_post(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+    }
+}
+
+// Batch 2..16 when a launch holds too few rows to fill the device with the kernel above (a single projection, the
+// matrices of one stage of a block): one workgroup per 32 rows of W (two 16-row tiles, which share every activation
+// fragment), its S wavefronts take the column tiles s, s + S, ...; each fetches its activation fragments itself
+// (from the L2: every workgroup reads all of x, which is why this form is for small launches only), nothing is
+// staged for the workgroup and no barrier sits in the tile loop; the partial sums meet in LDS in a fixed order.
+template <int S>
+__global__ void __launch_bounds__(64 * S, 1) decode_splitk_batched_kernel(DecodeArgs a) {
+    constexpr int MT = 16;
+    __shared__ __attribute__((aligned(1024))) uint32_t cb_all[S][512];
+    __shared__ __attribute__((aligned(16))) float xsc[S][32];
+    __shared__ __attribute__((aligned(16))) float red[S][kBRT][256];
+    const int wg = blockIdx.x;
+    int mi = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxGroupMats; j += 64)
+        mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
+    const DecodeMat mt = a.m[mi];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KT = mt.K >> 8, NR = mt.N >> 4, M = a.M;
+    WavePos wp;
+    wp.R[0] = kBRT * (wg - (mi ? a.wg_end[mi - 1] : 0));           // here wg_end counts stretches of kBRT row tiles
+#pragma unroll
+    for (int rt = 1; rt < 4; ++rt) wp.R[rt] = (rt < kBRT && wp.R[0] + rt < NR) ? wp.R[0] + rt : wp.R[0];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) wp.Rn[rt] = wp.R[0];
+    wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
+    wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
+    float4_t out[1][1][kBRT];
+#pragma unroll
+    for (int rt = 0; rt < kBRT; ++rt) out[0][0][rt] = float4_t{0, 0, 0, 0};
+    if (wp.nt > 0) run_batched<MT, 1, 1, true>(mt, wp, nullptr, xsc[wave], cb_all[wave], out);
+#pragma unroll
+    for (int rt = 0; rt < kBRT; ++rt) *(float4_t*)&red[wave][rt][4 * lane] = out[0][0][rt];
+    __syncthreads();
+    // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 of output column n; wavefront rt sums tile rt
+    static_assert(kBRT <= 2, "the wavefront that sums row tile rt is picked with a select, not an index");
+    const int Rw = wave == 0 ? wp.R[0] : wp.R[1];
+    if (wave < kBRT && (wave == 0 || Rw != wp.R[0])) {
+        float4_t t = *(const float4_t*)&red[0][wave][4 * lane];
+#pragma unroll
+        for (int s = 1; s < S; ++s) {
+            const float4_t v = *(const float4_t*)&red[s][wave][4 * lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[i] += v[i];
+        }
+        const int n = 16 * Rw + (lane & 15);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = 4 * (lane >> 4) + i;
+            if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, t[i]);
+        }
     }
 }
 
@@ -1435,6 +1551,33 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         for (int i = 0; i < cnt; ++i) tiles += (mats[order[i]].N + 15) / 16;
         int split = 0;
         if (M == 1 && tiles < kSplitTarget) split = pick_split(tiles);
+        // batch 2..16 with few rows in the launch: one workgroup per 32 rows, S wavefronts over its column tiles
+        if (M > 1 && M <= 16) {
+            long long stretches = 0;
+            for (int i = 0; i < cnt; ++i) stretches += (mats[order[i]].N + 16 * kBRT - 1) / (16 * kBRT);
+            // measured on the RWKV-6-7B shapes: the form wins up to about 2000 stretches at batch 16 and 3500 at batch <= 8
+            // (what it pays is every workgroup's own read of x, which grows with the batch)
+            if (stretches * (16 + M) <= option(RWKVQ_OPT_STREAM_SPLIT_MAX_WORK)) {
+                const int S = stretches * 8 >= kSplitTarget ? 4 : 8;      // sixteen wavefronts would leave 128 registers each
+                int wgs = 0;
+                for (int i = 0; i < cnt; ++i) {
+                    const MatDev& m = mats[order[i]];
+                    wgs += (m.N + 16 * kBRT - 1) / (16 * kBRT);
+                    a.m[i] = DecodeMat{m.codes, m.aux, m.x, m.y, m.N, m.K, m.fmt, POST_NONE, nullptr};
+                    a.wg_end[i] = wgs;
+                }
+                for (int i = cnt; i < kMaxGroupMats; ++i) {
+                    a.m[i] = DecodeMat{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, POST_NONE, nullptr};
+                    a.wg_end[i] = 0x7FFFFFFF;
+                }
+                a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
+                if (S == 4) hipLaunchKernelGGL(decode_splitk_batched_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
+                else hipLaunchKernelGGL(decode_splitk_batched_kernel<8>, dim3(wgs), dim3(512), 0, s, a);
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                continue;
+            }
+        }
         // batch > 1: two row passes per workgroup if the launch keeps enough workgroups that way
         int passes = 1;
         if (M > 1) {

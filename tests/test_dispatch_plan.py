@@ -101,6 +101,7 @@ def test_option_rejects():
     assert B.rwkvq_set_option(B.OPT_STREAM_WIDE_GBPS, -5, check=False) == B.ERR_UNSUPPORTED
     assert B.rwkvq_set_option(B.OPT_STREAM_TWO_PASS_MIN_WGS, 1000001, check=False) == B.ERR_UNSUPPORTED
     assert B.rwkvq_get_option(B.OPT_STREAM_TWO_PASS_MIN_WGS) == 2048
+    assert B.rwkvq_get_option(B.OPT_STREAM_SPLIT_MAX_WORK) == 65536
     assert B.lib().rwkvq_get_option(0, None) == B.ERR_NULL
 
 

@@ -28,13 +28,17 @@ FORCE = {None: B.SMALL_BATCH_AUTO, "stream": B.SMALL_BATCH_STREAM, "mfma": B.SMA
 
 
 
-@pytest.fixture(params=[1, 1000000], ids=["256-row-workgroups", "128-row-workgroups"])
+@pytest.fixture(params=["columns-split", "256-row-workgroups", "128-row-workgroups"])
 def stretches(request, options):
-    """Batch 2..32 on the streaming kernels: a workgroup covers two row stretches of 128 per staged activation
-    tile when the launch is large enough (RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS workgroups), else one.  The test
-    shapes are small launches, so both instances are forced in turn."""
-    options(B.OPT_STREAM_TWO_PASS_MIN_WGS, request.param)
-    return request.param
+    """Batch 2..32 on the streaming kernels has three forms, chosen by the size of the launch: one workgroup per 32
+    rows whose wavefronts split the columns and fetch their activation fragments themselves (small launches, batch
+    <= 16: RWKVQ_OPT_STREAM_SPLIT_MAX_WORK), workgroups of 128 rows that share a staged activation tile, and
+    workgroups of two such stretches (large launches: RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS).  The test shapes are small
+    launches, so each form is forced in turn (the first applies up to batch 16; above it the second runs)."""
+    form = request.param
+    options(B.OPT_STREAM_SPLIT_MAX_WORK, 1000000 if form == "columns-split" else 1)
+    options(B.OPT_STREAM_TWO_PASS_MIN_WGS, 1 if form == "256-row-workgroups" else 1000000)
+    return form
 
 
 SMALL = [("sq", 48, 768), ("sq", 256, 256), ("vq6", 256, 768), ("vq6", 512, 256), ("vq8", 256, 768),
