@@ -428,7 +428,7 @@ def sequential_step(dec, n_layers):
                     "operators of the block between the stages"}
 
 
-def batched_decode(dec):
+def batched_decode(dec, stage_ordered=True):
     """The decode stack at batches 4, 16 (streaming kernels, 2..16 rows), 32 (their 17..32-row instance) and
     64 (two passes of it, or the matrix cores: whichever the dispatcher estimates cheaper)."""
     import torch
@@ -449,7 +449,7 @@ def batched_decode(dec):
     # (4 dispatches per layer, each waiting for the one before; no element-wise operators in between), replayed
     # from one HIP graph.  These are small launches: the streaming kernels take their column-split form.
     n_layers = len(dec["descs"]) // 8
-    for M in (4, 16):
+    for M in ((4, 16) if stage_ordered else ()):
         tables = []
         for layer in range(n_layers):
             for ids in ((0, 1, 2, 3), (4,), (5, 7), (6,)):
@@ -750,7 +750,7 @@ def main():
     ap.add_argument("--skip-encode", action="store_true")
     ap.add_argument("--skip-mu", action="store_true", help="skip the element-wise multiplication leg")
     ap.add_argument("--skip-batched", action="store_true", help="skip the small-batch decode figures")
-    ap.add_argument("--skip-sequential", action="store_true", help="skip the dependency-ordered token step")
+    ap.add_argument("--skip-sequential", action="store_true", help="skip the legs replayed from a HIP graph: the dependency-ordered token step and the stage-ordered batched steps")
     ap.add_argument("--proxy-layers", type=int, default=8, help="layers of dense bf16 weights the proxy leg scans per call")
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -812,7 +812,7 @@ def main():
         out["steady_state"] = steady
     # ---------------- the same matrices at small batches (one grouped call per step)
     if not args.skip_batched:
-        out["decode_batched"] = batched_decode(dec)
+        out["decode_batched"] = batched_decode(dec, stage_ordered=not args.skip_sequential)   # the graph legs go together
     # ---------------- the same matrices in data-flow order, one HIP graph per token step
     if not args.skip_sequential:
         unit_gain(dec, 1)
