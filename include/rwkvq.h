@@ -108,10 +108,11 @@ const char* rwkvq_status_string(int status);
  *                                 (two stretches that share each staged activation tile) when the launch
  *                                 still has at least this many workgroups that way, and 128 rows otherwise
  *                                 (2048; 1 = always 256 rows, 1000000 = never)
- *   RWKVQ_OPT_STREAM_SPLIT_MAX_WORK    batch 2..16 on the streaming kernels: a launch takes the small-launch form (one
+ *   RWKVQ_OPT_STREAM_SPLIT_MAX_WORK    batch 2..32 on the streaming kernels: a launch takes the small-launch form (one
  *                                 workgroup per 32 rows of W, its wavefronts split the columns, every workgroup
  *                                 reads all of x) when (rows of all its matrices / 32) x (16 + M) is at most this
- *                                 (65536: one RWKV-6-7B layer at any such M, two layers up to M = 8; 1 = never)
+ *                                 (65536: one RWKV-6-7B layer at any M <= 16, two layers up to M = 8; 1 = never;
+ *                                 at M = 17..32 a third of the value is the limit unless it is 1000000 or more)
  * Errors: RWKVQ_ERR_UNSUPPORTED (unknown option, value out of range), RWKVQ_ERR_NULL. */
 enum { RWKVQ_OPT_SMALL_BATCH_PATH = 0, RWKVQ_OPT_PREFILL_TILE_ROWS = 1, RWKVQ_OPT_STREAM_WIDE_GBPS = 2,
        RWKVQ_OPT_STREAM_NARROW_GBPS = 3, RWKVQ_OPT_STREAM_WIDE_MIN_US = 4, RWKVQ_OPT_STREAM_NARROW_MIN_US = 5,

@@ -343,8 +343,8 @@ __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontempo
 // a 256-column tile, the eight consecutive activations 128 u + 32 t + 8 kg ... of batch row m (rows beyond M repeat
 // row M - 1) - so nothing is staged in LDS and no workgroup barrier is needed: f[4 u + t].
 struct XFrags { uint4_t f[8]; };
-__device__ __forceinline__ void x_load_frags(XFrags& r, const uint16_t* x, int M, int K, int T, int lane) {
-    const int m = (lane & 15) < M ? (lane & 15) : M - 1;
+__device__ __forceinline__ void x_load_frags(XFrags& r, const uint16_t* x, int M, int K, int T, int lane, int g = 0) {
+    const int m = 16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1;     // g: group of 16 batch rows
     const uint16_t* p = x + (size_t)m * K + 256 * T + 8 * (lane >> 4);
 #pragma unroll
     for (int i = 0; i < 8; ++i) r.f[i] = *(const uint4_t*)(p + 128 * (i >> 2) + 32 * (i & 3));
@@ -494,9 +494,9 @@ __device__ __forceinline__ uint4_t vq6_gather4(uint32_t w0, uint32_t w1, uint32_
 
 // G = groups of 16 batch rows (1 for batch <= 16, 2 for batch 17..32)
 constexpr int groups_of(int MT) { return MT <= 16 ? 1 : MT / 16; }
-template <int G> struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x[G]; XFrags xf; };
-template <int G> struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x[G]; XFrags xf; };
-template <int G> struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x[G]; XFrags xf; };
+template <int G> struct SqRegs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint2_t sz[kBRT]; XShared x[G]; XFrags xf[G]; };
+template <int G> struct Vq6Regs { uint4_t a[kBRT]; uint2_t b[kBRT]; uint32_t cb; XShared x[G]; XFrags xf[G]; };
+template <int G> struct Vq8Regs { uint4_t a[kBRT]; uint4_t b[kBRT]; uint4_t cb; XShared x[G]; XFrags xf[G]; };
 
 // Everything a tile loop needs about its wavefront's position; R[i] are its row tiles (R[i] == R[0]
 // for the tiles past the end of the matrix: worked on again, not stored).
@@ -546,7 +546,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
     asm("s_mov_b32 %0, 0x48004800" : "=s"(magic));
     const uint4_t ones4 = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
     const half8_t ones = __builtin_bit_cast(half8_t, ones4);
-    static_assert(!DIRECT || (G == 1 && P == 1), "fragments from global memory: one group of batch rows, one row pass");
+    static_assert(!DIRECT || P == 1, "fragments from global memory: one row pass");
     auto load = [&](Regs& r, int T, auto pass) {
         constexpr int J = decltype(pass)::value;
         if constexpr (DIRECT) T = wp.t0 + T * wp.ts;     // this wavefront's column tiles
@@ -558,7 +558,8 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
             r.sz[rt] = stream_load(sz[J][rt] + (size_t)T * 16 + (lane & 15));
         }
         if constexpr (DIRECT) {
-            x_load_frags(r.xf, (const uint16_t*)mt.x, M, mt.K, T, lane);
+#pragma unroll
+            for (int g = 0; g < G; ++g) x_load_frags(r.xf[g], (const uint16_t*)mt.x, M, mt.K, T, lane, g);
         } else if constexpr (J == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) x_load_wg(r.x[g], (const uint16_t*)mt.x, M, mt.K, T, wp.tid, g);
@@ -568,10 +569,14 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
         constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
-        XFrags xf;
+        XFrags xf[G];
         if constexpr (DIRECT) {
-            xf = r.xf;
-            if (XB) { x_frags_to_f16(xf, scb, lane); wave_lds_sync(); }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                xf[g] = r.xf[g];
+                if (XB) x_frags_to_f16(xf[g], scb + 16 * g, lane);
+            }
+            if (XB) wave_lds_sync();
         } else if constexpr (J == 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) x_store_wg<MT>(r.x[g], buf, scb, wp.tid, XB, g);
@@ -589,7 +594,7 @@ __device__ __forceinline__ void run_sq(const DecodeMat& mt, const WavePos& wp, h
                 for (int g = 0; g < G; ++g)
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
-                        xa[uu][g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf.f[4 * (ub + uu) + t]) : *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
+                        xa[uu][g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf[g].f[4 * (ub + uu) + t]) : *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
 #pragma unroll
             for (int uu = 0; uu < UB; ++uu) {
                 const int u = ub + uu;
@@ -646,7 +651,7 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
     const uint32_t base0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)cb_lds;
     uint32_t m;
     asm("v_mov_b32 %0, 0xfc" : "=v"(m));
-    static_assert(!DIRECT || (G == 1 && P == 1), "fragments from global memory: one group of batch rows, one row pass");
+    static_assert(!DIRECT || P == 1, "fragments from global memory: one row pass");
     auto load = [&](Regs& r, int T, auto pass) {
         constexpr int J = decltype(pass)::value;
         if constexpr (DIRECT) T = wp.t0 + T * wp.ts;     // this wavefront's column tiles
@@ -658,7 +663,8 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
         }
         if constexpr (DIRECT) {
             r.cb = (cbs + (size_t)T * 64)[lane];
-            x_load_frags(r.xf, (const uint16_t*)mt.x, M, mt.K, T, lane);
+#pragma unroll
+            for (int g = 0; g < G; ++g) x_load_frags(r.xf[g], (const uint16_t*)mt.x, M, mt.K, T, lane, g);
         } else if constexpr (J == 0) {
             r.cb = (cbs + (size_t)T * 64)[lane];
 #pragma unroll
@@ -669,10 +675,13 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
         constexpr int J = decltype(pass)::value;
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
-        XFrags xf;
+        XFrags xf[G];
         if constexpr (DIRECT) {
-            xf = r.xf;
-            if (XB) x_frags_to_f16(xf, scb, lane);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                xf[g] = r.xf[g];
+                if (XB) x_frags_to_f16(xf[g], scb + 16 * g, lane);
+            }
             cb_lds[(T & 1) * 256 + lane] = r.cb;
             wave_lds_sync();
         } else if constexpr (J == 0) {
@@ -700,7 +709,7 @@ __device__ __forceinline__ void run_vq6(const DecodeMat& mt, const WavePos& wp, 
                 for (int g = 0; g < G; ++g)
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
-                        xa[uu][g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf.f[4 * (ub + uu) + t]) : *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
+                        xa[uu][g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf[g].f[4 * (ub + uu) + t]) : *(const half8_t*)(buf + xoff[g] + 128 * (ub + uu) + 32 * t);
 #pragma unroll
             for (int uu = 0; uu < UB; ++uu) {
                 const int u = ub + uu;
@@ -753,7 +762,7 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
     int xoff[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) xoff[g] = (16 * g + (lane & 15) < M ? 16 * g + (lane & 15) : M - 1) * kXStride + 8 * (lane >> 4);
-    static_assert(!DIRECT || (G == 1 && P == 1), "fragments from global memory: one group of batch rows, one row pass");
+    static_assert(!DIRECT || P == 1, "fragments from global memory: one row pass");
     auto load = [&](Regs& r, int T, auto pass) {
         constexpr int J = decltype(pass)::value;
         if constexpr (DIRECT) T = wp.t0 + T * wp.ts;     // this wavefront's column tiles
@@ -765,7 +774,8 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
         }
         if constexpr (DIRECT) {
             r.cb = (cbs + (size_t)T * 64)[lane];
-            x_load_frags(r.xf, (const uint16_t*)mt.x, M, mt.K, T, lane);
+#pragma unroll
+            for (int g = 0; g < G; ++g) x_load_frags(r.xf[g], (const uint16_t*)mt.x, M, mt.K, T, lane, g);
         } else if constexpr (J == 0) {
             r.cb = (cbs + (size_t)T * 64)[lane];
 #pragma unroll
@@ -777,10 +787,13 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
         half_t* buf = xs + (T & 1) * (MT * kXStride);
         float* scb = xsc + (T & 1) * (16 * G);
         uint32_t* cbuf = cb_lds + (T & 1) * 256;     // two codebook slots, like the activations
-        XFrags xf;
+        XFrags xf[G];
         if constexpr (DIRECT) {
-            xf = r.xf;
-            if (XB) x_frags_to_f16(xf, scb, lane);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                xf[g] = r.xf[g];
+                if (XB) x_frags_to_f16(xf[g], scb + 16 * g, lane);
+            }
             *(uint4_t*)(cbuf + 4 * lane) = r.cb;
             wave_lds_sync();
         } else if constexpr (J == 0) {
@@ -804,7 +817,7 @@ __device__ __forceinline__ void run_vq8(const DecodeMat& mt, const WavePos& wp, 
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    xa[g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf.f[4 * u + t]) : *(const half8_t*)(buf + xoff[g] + 128 * u + 32 * t);
+                    xa[g][t] = DIRECT ? __builtin_bit_cast(half8_t, xf[g].f[4 * u + t]) : *(const half8_t*)(buf + xoff[g] + 128 * u + 32 * t);
 #pragma unroll
             for (int rt = 0; rt < kBRT; ++rt) {
                 const uint4_t w = u == 0 ? r.a[rt] : r.b[rt];
@@ -1335,12 +1348,13 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
 // fragment), its S wavefronts take the column tiles s, s + S, ...; each fetches its activation fragments itself
 // (from the L2: every workgroup reads all of x, which is why this form is for small launches only), nothing is
 // staged for the workgroup and no barrier sits in the tile loop; the partial sums meet in LDS in a fixed order.
-template <int S>
+template <int MT, int S>
 __global__ void __launch_bounds__(64 * S, 1) decode_splitk_batched_kernel(DecodeArgs a) {
-    constexpr int MT = 16;
+    static_assert(MT == 16 || MT == 32, "one or two groups of sixteen batch rows");
+    constexpr int G = groups_of(MT);
     __shared__ __attribute__((aligned(1024))) uint32_t cb_all[S][512];
-    __shared__ __attribute__((aligned(16))) float xsc[S][32];
-    __shared__ __attribute__((aligned(16))) float red[S][kBRT][256];
+    __shared__ __attribute__((aligned(16))) float xsc[S][2 * 16 * G];
+    __shared__ __attribute__((aligned(16))) float red[S][G][kBRT][256];
     const int wg = blockIdx.x;
     int mi = 0;
 #pragma unroll
@@ -1358,32 +1372,41 @@ __global__ void __launch_bounds__(64 * S, 1) decode_splitk_batched_kernel(Decode
     for (int rt = 0; rt < 4; ++rt) wp.Rn[rt] = wp.R[0];
     wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
     wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
-    float4_t out[1][1][kBRT];
+    float4_t out[1][G][kBRT];
 #pragma unroll
-    for (int rt = 0; rt < kBRT; ++rt) out[0][0][rt] = float4_t{0, 0, 0, 0};
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int rt = 0; rt < kBRT; ++rt) out[0][g][rt] = float4_t{0, 0, 0, 0};
     if (wp.nt > 0) run_batched<MT, 1, 1, true>(mt, wp, nullptr, xsc[wave], cb_all[wave], out);
 #pragma unroll
-    for (int rt = 0; rt < kBRT; ++rt) *(float4_t*)&red[wave][rt][4 * lane] = out[0][0][rt];
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int rt = 0; rt < kBRT; ++rt) *(float4_t*)&red[wave][g][rt][4 * lane] = out[0][g][rt];
     __syncthreads();
-    // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 of output column n; wavefront rt sums tile rt
+    // D layout of the MFMA: lane (n, mg) holds batch rows 4 mg .. 4 mg + 3 (of its group) of output column n;
+    // wavefront rt sums row tile rt
     static_assert(kBRT <= 2, "the wavefront that sums row tile rt is picked with a select, not an index");
     const int Rw = wave == 0 ? wp.R[0] : wp.R[1];
     if (wave < kBRT && (wave == 0 || Rw != wp.R[0])) {
-        float4_t t = *(const float4_t*)&red[0][wave][4 * lane];
-#pragma unroll
-        for (int s = 1; s < S; ++s) {
-            const float4_t v = *(const float4_t*)&red[s][wave][4 * lane];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) t[i] += v[i];
-        }
         const int n = 16 * Rw + (lane & 15);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = 4 * (lane >> 4) + i;
-            if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, t[i]);
+        for (int g = 0; g < G; ++g) {
+            float4_t t = *(const float4_t*)&red[0][g][wave & 1][4 * lane];
+#pragma unroll
+            for (int s = 1; s < S; ++s) {
+                const float4_t v = *(const float4_t*)&red[s][g][wave & 1][4 * lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] += v[i];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = 16 * g + 4 * (lane >> 4) + i;
+                if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, t[i]);
+            }
         }
     }
 }
+
 
 // Time mixing's r, k, v and the wkv step in one launch.  The recurrence is per channel, and channel c
 // needs r[c], k[c], v[c]: output row c of three matrices.  A workgroup of 12 wavefronts takes row tile R
@@ -1551,13 +1574,16 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         for (int i = 0; i < cnt; ++i) tiles += (mats[order[i]].N + 15) / 16;
         int split = 0;
         if (M == 1 && tiles < kSplitTarget) split = pick_split(tiles);
-        // batch 2..16 with few rows in the launch: one workgroup per 32 rows, S wavefronts over its column tiles
-        if (M > 1 && M <= 16) {
+        // batch 2..32 with few rows in the launch: one workgroup per 32 rows, S wavefronts over its column tiles
+        if (M > 1 && M <= 32) {
             long long stretches = 0;
             for (int i = 0; i < cnt; ++i) stretches += (mats[order[i]].N + 16 * kBRT - 1) / (16 * kBRT);
             // measured on the RWKV-6-7B shapes: the form wins up to about 2000 stretches at batch 16 and 3500 at batch <= 8
             // (what it pays is every workgroup's own read of x, which grows with the batch)
-            if (stretches * (16 + M) <= option(RWKVQ_OPT_STREAM_SPLIT_MAX_WORK)) {
+            // (above batch 16 a workgroup carries two groups of fragments and the row-workgroup form catches up at a
+            // third of that: one 4096-row matrix still gains 25-35 %, the two 14336-row matrices of channel mixing lose)
+            const long long max_work = option(RWKVQ_OPT_STREAM_SPLIT_MAX_WORK);
+            if (stretches * (16 + M) <= (M <= 16 || max_work >= 1000000 ? max_work : max_work / 3)) {
                 const int S = stretches * 8 >= kSplitTarget ? 4 : 8;      // sixteen wavefronts would leave 128 registers each
                 int wgs = 0;
                 for (int i = 0; i < cnt; ++i) {
@@ -1571,8 +1597,10 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
                     a.wg_end[i] = 0x7FFFFFFF;
                 }
                 a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
-                if (S == 4) hipLaunchKernelGGL(decode_splitk_batched_kernel<4>, dim3(wgs), dim3(256), 0, s, a);
-                else hipLaunchKernelGGL(decode_splitk_batched_kernel<8>, dim3(wgs), dim3(512), 0, s, a);
+                if (M <= 16 && S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 4>), dim3(wgs), dim3(256), 0, s, a);
+                else if (M <= 16) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 8>), dim3(wgs), dim3(512), 0, s, a);
+                else if (S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 4>), dim3(wgs), dim3(256), 0, s, a);
+                else hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 8>), dim3(wgs), dim3(512), 0, s, a);
                 hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return e;
                 continue;

@@ -34,7 +34,7 @@ def stretches(request, options):
     rows whose wavefronts split the columns and fetch their activation fragments themselves (small launches, batch
     <= 16: RWKVQ_OPT_STREAM_SPLIT_MAX_WORK), workgroups of 128 rows that share a staged activation tile, and
     workgroups of two such stretches (large launches: RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS).  The test shapes are small
-    launches, so each form is forced in turn (the first applies up to batch 16; above it the second runs)."""
+    launches, so each form is forced in turn."""
     form = request.param
     options(B.OPT_STREAM_SPLIT_MAX_WORK, 1000000 if form == "columns-split" else 1)
     options(B.OPT_STREAM_TWO_PASS_MIN_WGS, 1 if form == "256-row-workgroups" else 1000000)
