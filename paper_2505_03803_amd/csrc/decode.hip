@@ -338,7 +338,7 @@ __device__ __forceinline__ void x_store_wg(const XShared& r, half_t* xs, float* 
 template <class T>
 __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
 
-// Batch 2..16, small launches (decode_splitk_batched_kernel): a wavefront takes its A operands straight from global
+// Batch 2..32, small launches (decode_splitk_batched_kernel): a wavefront takes its A operands straight from global
 // memory in the layout the MFMA wants - lane (m, kg) = (lane % 16, lane / 16) holds, for column half u and k-step t of
 // a 256-column tile, the eight consecutive activations 128 u + 32 t + 8 kg ... of batch row m (rows beyond M repeat
 // row M - 1) - so nothing is staged in LDS and no workgroup barrier is needed: f[4 u + t].
