@@ -97,13 +97,14 @@ def test_decode_small(fmt, N, K, M, xdt, stretches):
 
 
 @pytest.mark.parametrize("fmt,N,K", [("sq", 176, 512), ("sq", 272, 768), ("sq", 400, 256), ("vq6", 768, 512), ("vq8", 768, 768)])
-@pytest.mark.parametrize("M", [2, 16, 32])
+@pytest.mark.parametrize("M", [2, 16, 17, 24, 32])
 @pytest.mark.parametrize("xdt", ["f16", "bf16"])
 def test_decode_batched_row_stretches(fmt, N, K, M, xdt, options, stretches):
     """Batch 2..32: a workgroup covers 256 rows of W as two stretches of 128 that share each staged activation
     tile.  Row counts that end inside the first stretch, inside the second, and one row tile into the next
-    workgroup (SQ rows come in sixteens; VQ in blocks of 256, here three blocks).  The streaming kernels are
-    forced (left alone the dispatcher may send M = 32 to the matrix cores, which round the weights)."""
+    workgroup (SQ rows come in sixteens; VQ in blocks of 256, here three blocks).  M = 17 and 24 leave the second
+    group of sixteen batch rows of the 32-row instances partly filled.  The streaming kernels are
+    forced (left alone the dispatcher may send M > 16 to the matrix cores, which round the weights)."""
     print(f"decode row stretches {fmt} N={N} K={K} M={M} x={xdt} two-pass threshold {stretches}", flush=True)
     options(B.OPT_SMALL_BATCH_PATH, B.SMALL_BATCH_STREAM)
     mat = make(fmt, N, K, 12)
