@@ -113,10 +113,14 @@ const char* rwkvq_status_string(int status);
  *                                 reads all of x) when (rows of all its matrices / 32) x (16 + M) is at most this
  *                                 (65536: one RWKV-6-7B layer at any M <= 16, two layers up to M = 8; 1 = never;
  *                                 at M = 17..32 a third of the value is the limit unless it is 1000000 or more)
+ *   RWKVQ_OPT_SPLIT_GRID_2D       batch 1, launches of at most eight matrices with few rows (the stages of a block): 1 = a
+ *                                 workgroup takes its matrix and row tile from a two-dimensional grid, 2 = from the
+ *                                 table of first-workgroup indices that larger launches use (1; same output bits)
  * Errors: RWKVQ_ERR_UNSUPPORTED (unknown option, value out of range), RWKVQ_ERR_NULL. */
 enum { RWKVQ_OPT_SMALL_BATCH_PATH = 0, RWKVQ_OPT_PREFILL_TILE_ROWS = 1, RWKVQ_OPT_STREAM_WIDE_GBPS = 2,
        RWKVQ_OPT_STREAM_NARROW_GBPS = 3, RWKVQ_OPT_STREAM_WIDE_MIN_US = 4, RWKVQ_OPT_STREAM_NARROW_MIN_US = 5,
-       RWKVQ_OPT_MFMA_KSTEP_NS = 6, RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS = 7, RWKVQ_OPT_STREAM_SPLIT_MAX_WORK = 8 };
+       RWKVQ_OPT_MFMA_KSTEP_NS = 6, RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS = 7, RWKVQ_OPT_STREAM_SPLIT_MAX_WORK = 8,
+       RWKVQ_OPT_SPLIT_GRID_2D = 9 };
 enum { RWKVQ_SMALL_BATCH_AUTO = 0, RWKVQ_SMALL_BATCH_STREAM = 1, RWKVQ_SMALL_BATCH_MATRIX_CORES = 2 };
 int rwkvq_set_option(int option, int value);
 int rwkvq_get_option(int option, int* value /* host */);

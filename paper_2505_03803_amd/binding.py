@@ -143,7 +143,8 @@ def lib() -> ctypes.CDLL:
 
 
 (OPT_SMALL_BATCH_PATH, OPT_PREFILL_TILE_ROWS, OPT_STREAM_WIDE_GBPS, OPT_STREAM_NARROW_GBPS, OPT_STREAM_WIDE_MIN_US,
- OPT_STREAM_NARROW_MIN_US, OPT_MFMA_KSTEP_NS, OPT_STREAM_TWO_PASS_MIN_WGS, OPT_STREAM_SPLIT_MAX_WORK) = range(9)
+ OPT_STREAM_NARROW_MIN_US, OPT_MFMA_KSTEP_NS, OPT_STREAM_TWO_PASS_MIN_WGS, OPT_STREAM_SPLIT_MAX_WORK,
+ OPT_SPLIT_GRID_2D) = range(10)
 SMALL_BATCH_AUTO, SMALL_BATCH_STREAM, SMALL_BATCH_MATRIX_CORES = 0, 1, 2
 
 

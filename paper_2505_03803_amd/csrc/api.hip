@@ -124,8 +124,8 @@ void plan_paths(const std::vector<MatDev>& devs, int M, std::vector<int>* path) 
 }  // namespace
 
 namespace rwkvq {
-static const int kOptionDefault[kOptionCount] = {RWKVQ_SMALL_BATCH_AUTO, 0, 2800, 4100, 24, 12, 1500, 2048, 65536};
-static std::atomic<int> g_option[kOptionCount] = {{RWKVQ_SMALL_BATCH_AUTO}, {0}, {2800}, {4100}, {24}, {12}, {1500}, {2048}, {65536}};
+static const int kOptionDefault[kOptionCount] = {RWKVQ_SMALL_BATCH_AUTO, 0, 2800, 4100, 24, 12, 1500, 2048, 65536, 1};
+static std::atomic<int> g_option[kOptionCount] = {{RWKVQ_SMALL_BATCH_AUTO}, {0}, {2800}, {4100}, {24}, {12}, {1500}, {2048}, {65536}, {1}};
 int option(int which) { return g_option[which].load(std::memory_order_relaxed); }
 }  // namespace rwkvq
 

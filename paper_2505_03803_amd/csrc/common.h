@@ -203,7 +203,7 @@ hipError_t launch_wkv(const void* r, const void* k, const void* v, int dt, int M
 hipError_t launch_pointwise(int op, const void* x, const void* y, int dt, long long n, void* out, hipStream_t s);
 
 // Process-wide settings behind rwkvq_set_option (values of RWKVQ_OPT_* in rwkvq.h); option() is an atomic load.
-constexpr int kOptionCount = 9;
+constexpr int kOptionCount = 10;
 int option(int which);
 
 constexpr int kDecodeMaxM = 16;    // native layout: M <= this goes to the streaming kernels

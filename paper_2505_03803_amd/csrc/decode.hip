@@ -117,6 +117,7 @@ struct MixedMat : DecodeMat {
     int mix_E, pad2;
 };
 constexpr int kMaxMixedMats = 64;
+constexpr int kGrid2DMaxMats = 8;     // split-K kernels: launches of at most this many matrices are two-dimensional grids (matrix, row tile)
 // A matrix whose output also leaves as the token-shift mixes of the stage that follows (up to four
 // projections): out_p[n] = mu_p[n] y[n] + (1 - mu_p[n]) xprev[n].
 struct PostMix { const uint8_t* idx; const uint32_t* cb; void* out; };
@@ -155,7 +156,18 @@ struct DecodeArgs {                   // 15 KB of kernel arguments
 // have read it from memory, then max(y, 0)^2 (Eq. "channel mixing o", input of W'_v) or
 // sigma(gate) * y (the gates of Eq. "time mixing o" / "channel mixing o") in binary32, then rounded
 // for the store: the same bits as the projection followed by rwkvq_relu2 / rwkvq_sigmoid_gate.
-__device__ __forceinline__ float store_post(const DecodeMat& mt, size_t i, int ydt, float v) {
+// A value of the given type as its bits, and back: what the lanes that store a row tile ask memory for at the start of
+// a split-K kernel (gate, previous token, mix indices) stays bits until the end, so that nothing in front of the
+// multiply waits for it (converted at once, each load is a trip to memory that the wavefront sits out).
+__device__ __forceinline__ uint32_t load_bits(const void* p, size_t i, int dt) {
+    return dt == DT_F32 ? ((const uint32_t*)p)[i] : (uint32_t)((const uint16_t*)p)[i];
+}
+__device__ __forceinline__ float bits_to_f32(uint32_t b, int dt) {
+    return dt == DT_F16 ? f16_bits_to_f32((uint16_t)b) : dt == DT_BF16 ? bf16_bits_to_f32((uint16_t)b) : __uint_as_float(b);
+}
+// gate_bits: the gate's bits if the caller fetched them ahead (have_gate), else it is loaded here
+__device__ __forceinline__ float store_post(const DecodeMat& mt, size_t i, int ydt, float v, bool have_gate = false,
+                                            uint32_t gate_bits = 0) {
     if (mt.post != POST_NONE) {
         if (ydt == DT_F16) v = f16_bits_to_f32(f32_to_f16_bits(v));
         else if (ydt == DT_BF16) v = bf16_bits_to_f32(f32_to_bf16_bits(v));
@@ -163,7 +175,7 @@ __device__ __forceinline__ float store_post(const DecodeMat& mt, size_t i, int y
             const float m = fmaxf(v, 0.0f);
             v = m * m;
         } else {
-            v = gate_f32(load_as_f32(mt.gate, i, ydt), v);
+            v = gate_f32(have_gate ? bits_to_f32(gate_bits, ydt) : load_as_f32(mt.gate, i, ydt), v);
         }
     }
     store_from_f32(mt.y, i, ydt, v);
@@ -177,24 +189,31 @@ __device__ __forceinline__ float store_post(const DecodeMat& mt, size_t i, int y
 // The previous token's value and the indices are fetched by post_mix_prefetch at the start of the kernel
 // (their latency hides behind the GEMV); the codebook entries, which depend on the indices, here, in one
 // batch of loads.
-struct PostMixPre { float xp; uint32_t ix[4]; };
+struct PostMixPre { uint32_t xp, ix[4], gate; };        // as bits (see load_bits)
 __device__ __forceinline__ void post_mix_prefetch(PostMixPre& pre, const PostMixMat& mt, size_t i, int ydt) {
-    pre.xp = load_as_f32(mt.xprev, i, ydt);
+    if (mt.post == POST_SIGMOID_GATE) pre.gate = load_bits(mt.gate, i, ydt);
+    if (mt.n_mix > 0) {
+        pre.xp = load_bits(mt.xprev, i, ydt);
+        // every load unconditional (a mix that is not there reads the first one's index): no branch, no wait between them;
+        // the aligned word that holds the index byte (a byte load is widened on the spot, which waits for it; the index
+        // arrays are 16-byte aligned and N / 2 is a multiple of 8); static indices: mt stays in registers
 #pragma unroll
-    for (int p = 0; p < 4; ++p) pre.ix[p] = p < mt.n_mix ? mt.mix[p].idx[i >> 1] : 0u;   // static indices: mt stays in registers
+        for (int p = 0; p < 4; ++p) pre.ix[p] = ((const uint32_t*)(p < mt.n_mix ? mt.mix[p].idx : mt.mix[0].idx))[i >> 3];
+    }
 }
 __device__ __forceinline__ void store_post_mix(const PostMixMat& mt, size_t i, int ydt, float v, const PostMixPre& pre) {
-    v = store_post(mt, i, ydt, v);
+    v = store_post(mt, i, ydt, v, true, pre.gate);
     if (mt.n_mix > 0) {
         const float xt = ydt == DT_F16 ? f16_bits_to_f32(f32_to_f16_bits(v)) : bf16_bits_to_f32(f32_to_bf16_bits(v));
+        const float xp = bits_to_f32(pre.xp, ydt);
         uint32_t e[4];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) e[p] = p < mt.n_mix ? mt.mix[p].cb[pre.ix[p]] : 0u;
+        for (int p = 0; p < 4; ++p) e[p] = p < mt.n_mix ? mt.mix[p].cb[(pre.ix[p] >> (8 * ((i >> 1) & 3))) & 255u] : 0u;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             if (p < mt.n_mix) {
                 const float m = f16_bits_to_f32((uint16_t)((i & 1) ? e[p] >> 16 : e[p] & 0xFFFFu));
-                const float o = __fadd_rn(__fmul_rn(m, xt), __fmul_rn(__fsub_rn(1.0f, m), pre.xp));
+                const float o = __fadd_rn(__fmul_rn(m, xt), __fmul_rn(__fsub_rn(1.0f, m), xp));
                 store_from_f32(mt.mix[p].out, i, ydt, o);
             }
         }
@@ -1295,7 +1314,7 @@ __global__ void __launch_bounds__(64 * waves_of(MT), min_blocks(MT)) decode_kern
 // column tiles s, s + S, s + 2S, ... and their partial sums meet in LDS in a fixed order.  The
 // grouped kernel above gives one wavefront a whole row tile, which keeps 4096 x 4096 on a quarter
 // of the SIMDs.
-template <int S, class Args>
+template <int S, class Args, bool GRID2D>
 __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     constexpr int DEPTH = RWKVQ_DECODE_DEPTH;
     constexpr bool MIXED = Args::kMixed;
@@ -1303,18 +1322,31 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     __shared__ __attribute__((aligned(1024))) uint32_t cb_all[S][256];
     __shared__ uint32_t cb_mix[MIXED ? S : 1][256];
     __shared__ float red[S][16];
-    const int wg = blockIdx.x;
-    int mi = 0;
+    // Which matrix, which row tile?  A launch of a few matrices (a stage of a block) is a two-dimensional grid,
+    // blockIdx.y the matrix and blockIdx.x the row tile (workgroups past a shorter matrix's last tile leave at once):
+    // the descriptor is then one load away.  The table of first-workgroup indices of the other form costs a load of
+    // its own in front of it, and these launches last three or four trips to memory in all.
+    int mi = 0, tile;
+    if constexpr (GRID2D) {
+        mi = blockIdx.y;
+        tile = blockIdx.x;
+    } else {
+        const int wg = blockIdx.x;
 #pragma unroll
-    for (int j = 0; j < Args::kMats; j += 64)
-        mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
+        for (int j = 0; j < Args::kMats; j += 64)
+            mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
+        tile = wg - (mi ? a.wg_end[mi - 1] : 0);                                   // here wg_end counts row tiles
+    }
+    const int xdt = a.xdt, ydt = a.ydt;    // the end of the argument block: asked for together with the descriptor
     const auto mt = a.m[mi];
+    asm volatile("" :: "s"(xdt), "s"(ydt), "s"(mt.N));
+    if (GRID2D && tile >= ((mt.N + 15) >> 4)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int KT = mt.K >> 8;
     WavePos wp;
-    wp.R[0] = wp.R[1] = wp.R[2] = wp.R[3] = wg - (mi ? a.wg_end[mi - 1] : 0);      // here wg_end counts row tiles
-    wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
+    wp.R[0] = wp.R[1] = wp.R[2] = wp.R[3] = tile;
+    wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xdt == DT_BF16;
     wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
     if constexpr (MIXED) {
         for (int e = lane; e < mt.mix_E; e += 64) cb_mix[wave][e] = mt.mix_cb[e];
@@ -1323,7 +1355,9 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
     }
     PostMixPre pre{};
     if constexpr (Args::kPostMix) {
-        if (wave == 0 && lane < 16 && mt.n_mix > 0) post_mix_prefetch(pre, mt, (size_t)16 * wp.R[0] + lane, a.ydt);
+        if (wave == 0 && lane < 16) post_mix_prefetch(pre, mt, (size_t)16 * wp.R[0] + lane, ydt);
+    } else {
+        if (wave == 0 && lane < 16 && mt.post == POST_SIGMOID_GATE) pre.gate = load_bits(mt.gate, (size_t)16 * wp.R[0] + lane, ydt);
     }
     float part[kRT] = {0.f};
     if (wp.nt > 0) {
@@ -1338,8 +1372,8 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
         float t = red[0][lane];
 #pragma unroll
         for (int s = 1; s < S; ++s) t += red[s][lane];
-        if constexpr (Args::kPostMix) store_post_mix(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t, pre);
-        else store_post(mt, (size_t)16 * wp.R[0] + lane, a.ydt, t);
+        if constexpr (Args::kPostMix) store_post_mix(mt, (size_t)16 * wp.R[0] + lane, ydt, t, pre);
+        else store_post(mt, (size_t)16 * wp.R[0] + lane, ydt, t, true, pre.gate);
     }
 }
 
@@ -1481,11 +1515,23 @@ hipError_t launch_decode_rkv_wkv(const MatDev* rkv, const WkvDev& wkv, int x_dty
 // Smallest S of 4, 8, 16 that brings `tiles` row tiles to kSplitTarget wavefronts.
 static int pick_split(int tiles) { return tiles * 4 >= kSplitTarget ? 4 : tiles * 8 >= kSplitTarget ? 8 : 16; }
 
+// n_mats <= kGrid2DMaxMats: grid (longest matrix's row tiles, matrices); else one row of `wgs` workgroups and the table
 template <class Args>
-static hipError_t launch_splitk(int split, int wgs, const Args& a, hipStream_t s) {
-    if (split == 4) hipLaunchKernelGGL((decode_splitk_kernel<4, Args>), dim3(wgs), dim3(256), 0, s, a);
-    else if (split == 8) hipLaunchKernelGGL((decode_splitk_kernel<8, Args>), dim3(wgs), dim3(512), 0, s, a);
-    else hipLaunchKernelGGL((decode_splitk_kernel<16, Args>), dim3(wgs), dim3(1024), 0, s, a);
+static hipError_t launch_splitk(int split, int wgs, Args& a, int n_mats, hipStream_t s) {
+    a.pad = 0;
+    if (n_mats <= kGrid2DMaxMats && option(RWKVQ_OPT_SPLIT_GRID_2D) == 1) {
+        int longest = 0;
+        for (int i = 0; i < n_mats; ++i) longest = std::max(longest, a.wg_end[i] - (i ? a.wg_end[i - 1] : 0));
+        const dim3 grid(longest, n_mats);
+        if (split == 4) hipLaunchKernelGGL((decode_splitk_kernel<4, Args, true>), grid, dim3(256), 0, s, a);
+        else if (split == 8) hipLaunchKernelGGL((decode_splitk_kernel<8, Args, true>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((decode_splitk_kernel<16, Args, true>), grid, dim3(1024), 0, s, a);
+        return hipGetLastError();
+    }
+    const dim3 grid(wgs);
+    if (split == 4) hipLaunchKernelGGL((decode_splitk_kernel<4, Args, false>), grid, dim3(256), 0, s, a);
+    else if (split == 8) hipLaunchKernelGGL((decode_splitk_kernel<8, Args, false>), grid, dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((decode_splitk_kernel<16, Args, false>), grid, dim3(1024), 0, s, a);
     return hipGetLastError();
 }
 
@@ -1516,7 +1562,7 @@ hipError_t launch_decode_mixed(const MatDev* mats, const MixDev* mixes, int n_ma
             }
         }
         a.M = 1; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
-        hipError_t e = launch_splitk(pick_split(tiles), wgs, a, s);
+        hipError_t e = launch_splitk(pick_split(tiles), wgs, a, cnt, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -1550,7 +1596,7 @@ hipError_t launch_decode_postmix(const MatDev* mats, const PostDev* posts, const
             a.m[i] = mm;
         }
         a.M = 1; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
-        hipError_t e = launch_splitk(pick_split(tiles), wgs, a, s);
+        hipError_t e = launch_splitk(pick_split(tiles), wgs, a, cnt, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -1628,7 +1674,7 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
         }
         a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
         const dim3 grid(wgs), wide(64 * kBW);
-        if (split) { hipError_t e = launch_splitk(split, wgs, a, s); if (e != hipSuccess) return e; }
+        if (split) { hipError_t e = launch_splitk(split, wgs, a, cnt, s); if (e != hipSuccess) return e; }
         else if (M == 1) hipLaunchKernelGGL(decode_kernel<1>, grid, dim3(256), 0, s, a);
         else if (M <= 4 && passes == 1) hipLaunchKernelGGL((decode_kernel<4, 1>), grid, wide, 0, s, a);
         else if (M <= 4) hipLaunchKernelGGL((decode_kernel<4, 2>), grid, wide, 0, s, a);

@@ -294,12 +294,16 @@ def test_block_tokens_through_quantized_projections():
 @pytest.mark.parametrize("shapes", [[(256, 512), (512, 256), (48, 768)], [(4096, 512)], [(8192, 256), (256, 3584)],
                                     [(16384, 256), (16384, 512), (4096, 256)]])
 @pytest.mark.parametrize("with_mix", [False, True])
-def test_post_operator_equals_separate_pass(dt, shapes, with_mix):
+@pytest.mark.parametrize("grid", [1, 2])
+def test_post_operator_equals_separate_pass(dt, shapes, with_mix, grid, options):
     """rwkvq_linear_dispatch_post against the same projections followed by rwkvq_relu2 /
     rwkvq_sigmoid_gate: bit for bit (same matrices per call, hence the same kernel shape and order of
     summation; the operator is applied to the rounded output).  The shapes take 4, 8 and 16
     wavefronts per row tile and, the last, the grouped kernel (with the mix in front, which always
-    splits the columns, four wavefronts per row tile on 2304 row tiles); matrix j gets operator j mod 3."""
+    splits the columns, four wavefronts per row tile on 2304 row tiles); matrix j gets operator j mod 3.
+    grid: how a workgroup of the split-K kernels finds its matrix and row tile (RWKVQ_OPT_SPLIT_GRID_2D: 1 = from a
+    two-dimensional grid, 2 = from the table of first workgroups)."""
+    options(B.OPT_SPLIT_GRID_2D, grid)
     torch = G.torch_()
     rng = np.random.default_rng(9500 + len(shapes) + shapes[0][0])
     mats = []

@@ -115,12 +115,15 @@ def test_decode_batched_row_stretches(fmt, N, K, M, xdt, options, stretches):
 
 @pytest.mark.parametrize("fmt", ["sq", "vq6", "vq8"])
 @pytest.mark.parametrize("N,K", [(256, 256), (256, 3584), (4096, 512), (4096, 1792), (8192, 256), (8192, 1280), (16384, 512), (65536, 256)])
-def test_decode_batch1_launch_shapes(fmt, N, K):
+@pytest.mark.parametrize("grid", ["matrix-by-row-tile grid", "table of first workgroups"])
+def test_decode_batch1_launch_shapes(fmt, N, K, grid, options):
     """Batch 1 picks its kernel by the number of 16-row tiles in the launch: 16, 8 or 4 wavefronts
     per tile with the column tiles dealt round-robin (small launches), or one wavefront per tile
     (2048 tiles and more).  Rows with fewer column tiles than wavefronts, and
-    tile counts that do not divide, are part of the sweep."""
-    print(f"decode shapes {fmt} N={N} K={K}", flush=True)
+    tile counts that do not divide, are part of the sweep.  A small launch of few matrices finds its matrix
+    and row tile in a two-dimensional grid; the table that launches of more than eight matrices use is forced too."""
+    print(f"decode shapes {fmt} N={N} K={K} {grid}", flush=True)
+    options(B.OPT_SPLIT_GRID_2D, 1 if grid.startswith("matrix") else 2)
     mat = make(fmt, N, K, 8)
     x = acts(1, K, "f16", N + K)
     y = G.gpu_gemm(B.upload(mat, native=True), x, "f16")
