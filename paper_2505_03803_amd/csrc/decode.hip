@@ -1382,29 +1382,40 @@ __global__ void __launch_bounds__(64 * S) decode_splitk_kernel(Args a) {
 // fragment), its S wavefronts take the column tiles s, s + S, ...; each fetches its activation fragments itself
 // (from the L2: every workgroup reads all of x, which is why this form is for small launches only), nothing is
 // staged for the workgroup and no barrier sits in the tile loop; the partial sums meet in LDS in a fixed order.
-template <int MT, int S>
+template <int MT, int S, bool GRID2D>
 __global__ void __launch_bounds__(64 * S, 1) decode_splitk_batched_kernel(DecodeArgs a) {
     static_assert(MT == 16 || MT == 32, "one or two groups of sixteen batch rows");
     constexpr int G = groups_of(MT);
     __shared__ __attribute__((aligned(1024))) uint32_t cb_all[S][512];
     __shared__ __attribute__((aligned(16))) float xsc[S][2 * 16 * G];
     __shared__ __attribute__((aligned(16))) float red[S][G][kBRT][256];
-    const int wg = blockIdx.x;
-    int mi = 0;
+    // matrix and stretch of rows: from a two-dimensional grid (launches of at most kGrid2DMaxMats matrices, see
+    // decode_splitk_kernel) or from the table of first workgroups
+    int mi = 0, stretch;
+    if constexpr (GRID2D) {
+        mi = blockIdx.y;
+        stretch = blockIdx.x;
+    } else {
+        const int wg = blockIdx.x;
 #pragma unroll
-    for (int j = 0; j < kMaxGroupMats; j += 64)
-        mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
+        for (int j = 0; j < kMaxGroupMats; j += 64)
+            mi += __builtin_popcountll(__builtin_amdgcn_ballot_w64(wg >= a.wg_end[j + (threadIdx.x & 63)]));
+        stretch = wg - (mi ? a.wg_end[mi - 1] : 0);                // here wg_end counts stretches of kBRT row tiles
+    }
+    const int M = a.M, xdt = a.xdt, ydt = a.ydt;                   // the end of the argument block: asked for with the descriptor
     const DecodeMat mt = a.m[mi];
+    asm volatile("" :: "s"(M), "s"(xdt), "s"(ydt), "s"(mt.N));
+    if (GRID2D && stretch >= (mt.N + 16 * kBRT - 1) / (16 * kBRT)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int KT = mt.K >> 8, NR = mt.N >> 4, M = a.M;
+    const int KT = mt.K >> 8, NR = mt.N >> 4;
     WavePos wp;
-    wp.R[0] = kBRT * (wg - (mi ? a.wg_end[mi - 1] : 0));           // here wg_end counts stretches of kBRT row tiles
+    wp.R[0] = kBRT * stretch;
 #pragma unroll
     for (int rt = 1; rt < 4; ++rt) wp.R[rt] = (rt < kBRT && wp.R[0] + rt < NR) ? wp.R[0] + rt : wp.R[0];
 #pragma unroll
     for (int rt = 0; rt < 4; ++rt) wp.Rn[rt] = wp.R[0];
-    wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
+    wp.M = M; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xdt == DT_BF16;
     wp.t0 = wave; wp.ts = S; wp.nt = wave < KT ? (KT - wave + S - 1) / S : 0;
     float4_t out[1][G][kBRT];
 #pragma unroll
@@ -1435,7 +1446,7 @@ __global__ void __launch_bounds__(64 * S, 1) decode_splitk_batched_kernel(Decode
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int m = 16 * g + 4 * (lane >> 4) + i;
-                if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, a.ydt, t[i]);
+                if (m < M) store_from_f32(mt.y, (size_t)m * mt.N + n, ydt, t[i]);
             }
         }
     }
@@ -1464,10 +1475,14 @@ __global__ void __launch_bounds__(768) decode_rkv_wkv_kernel(WkvFuseArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int mi = wave >> 2, s = wave & 3;
     const DecodeMat mt = mi == 0 ? a.m[0] : mi == 1 ? a.m[1] : a.m[2];
+    const int xdt = a.xdt;
+    // the descriptor, the types and the recurrence's pointers sit in four cache lines of the argument block: all asked
+    // for before the first wait (one after the other each is a trip of its own at the start of a kernel that lasts 8 us)
+    asm volatile("" :: "s"(mt.codes), "s"(mt.K), "s"(xdt), "s"(a.state), "s"(a.d));
     const int KT = mt.K >> 8;
     WavePos wp;
     wp.R[0] = wp.R[1] = wp.R[2] = wp.R[3] = blockIdx.x;
-    wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = a.xdt == DT_BF16;
+    wp.M = 1; wp.lane = lane; wp.tid = threadIdx.x; wp.xbf16 = xdt == DT_BF16;
     wp.t0 = s; wp.ts = S; wp.nt = s < KT ? (KT - s + S - 1) / S : 0;
     wp.xprev = nullptr; wp.mix_idx = nullptr; wp.mix_cb = nullptr;
     // the recurrence's operands for this tile's channels: fetched now, used after the GEMV
@@ -1643,10 +1658,18 @@ hipError_t launch_decode(const MatDev* mats, int n_mats, int M, int x_dtype, int
                     a.wg_end[i] = 0x7FFFFFFF;
                 }
                 a.M = M; a.xdt = x_dtype; a.ydt = y_dtype; a.pad = 0;
-                if (M <= 16 && S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 4>), dim3(wgs), dim3(256), 0, s, a);
-                else if (M <= 16) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 8>), dim3(wgs), dim3(512), 0, s, a);
-                else if (S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 4>), dim3(wgs), dim3(256), 0, s, a);
-                else hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 8>), dim3(wgs), dim3(512), 0, s, a);
+                if (cnt <= kGrid2DMaxMats && option(RWKVQ_OPT_SPLIT_GRID_2D) == 1) {
+                    int longest = 0;
+                    for (int i = 0; i < cnt; ++i) longest = std::max(longest, a.wg_end[i] - (i ? a.wg_end[i - 1] : 0));
+                    const dim3 grid(longest, cnt);
+                    if (M <= 16 && S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 4, true>), grid, dim3(256), 0, s, a);
+                    else if (M <= 16) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 8, true>), grid, dim3(512), 0, s, a);
+                    else if (S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 4, true>), grid, dim3(256), 0, s, a);
+                    else hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 8, true>), grid, dim3(512), 0, s, a);
+                } else if (M <= 16 && S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 4, false>), dim3(wgs), dim3(256), 0, s, a);
+                else if (M <= 16) hipLaunchKernelGGL((decode_splitk_batched_kernel<16, 8, false>), dim3(wgs), dim3(512), 0, s, a);
+                else if (S == 4) hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 4, false>), dim3(wgs), dim3(256), 0, s, a);
+                else hipLaunchKernelGGL((decode_splitk_batched_kernel<32, 8, false>), dim3(wgs), dim3(512), 0, s, a);
                 hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return e;
                 continue;
