@@ -28,15 +28,17 @@ FORCE = {None: B.SMALL_BATCH_AUTO, "stream": B.SMALL_BATCH_STREAM, "mfma": B.SMA
 
 
 
-@pytest.fixture(params=["columns-split", "256-row-workgroups", "128-row-workgroups"])
+@pytest.fixture(params=["columns-split", "columns-split, table of first workgroups", "256-row-workgroups", "128-row-workgroups"])
 def stretches(request, options):
     """Batch 2..32 on the streaming kernels has three forms, chosen by the size of the launch: one workgroup per 32
     rows whose wavefronts split the columns and fetch their activation fragments themselves (small launches, batch
     <= 16: RWKVQ_OPT_STREAM_SPLIT_MAX_WORK), workgroups of 128 rows that share a staged activation tile, and
     workgroups of two such stretches (large launches: RWKVQ_OPT_STREAM_TWO_PASS_MIN_WGS).  The test shapes are small
-    launches, so each form is forced in turn."""
+    launches, so each form is forced in turn.  The column-split form finds matrix and stretch in a two-dimensional grid
+    when the launch holds at most eight matrices, and in the table of first workgroups otherwise: both are forced."""
     form = request.param
-    options(B.OPT_STREAM_SPLIT_MAX_WORK, 1000000 if form == "columns-split" else 1)
+    options(B.OPT_STREAM_SPLIT_MAX_WORK, 1000000 if form.startswith("columns-split") else 1)
+    options(B.OPT_SPLIT_GRID_2D, 2 if form.endswith("table of first workgroups") else 1)
     options(B.OPT_STREAM_TWO_PASS_MIN_WGS, 1 if form == "256-row-workgroups" else 1000000)
     return form
 
