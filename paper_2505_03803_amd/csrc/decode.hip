@@ -40,11 +40,16 @@
 
 namespace rwkvq {
 
+// Batch 1: column tiles in flight beyond the one being consumed, and the wavefronts per SIMD the compiler must leave
+// registers for.  One tile ahead keeps the grouped kernel at 64 registers, eight wavefronts per SIMD; two tiles ahead
+// (79 registers, six per SIMD) put more bytes in flight per compute unit (72 against 48 KB) and were slower once the
+// weight loads carried the non-temporal hint: 7B stack 5.79 -> 5.96 TB/s, 14B-class stack 5.65 -> 5.75 TB/s, the token
+// step of the 7B blocks (split-K kernels, 65 registers instead of 79-106) 1.008 -> 0.935 ms, same box, alternating.
 #ifndef RWKVQ_DECODE_MINBLOCKS
-#define RWKVQ_DECODE_MINBLOCKS 5
+#define RWKVQ_DECODE_MINBLOCKS 8
 #endif
 #ifndef RWKVQ_DECODE_DEPTH
-#define RWKVQ_DECODE_DEPTH 2
+#define RWKVQ_DECODE_DEPTH 1
 #endif
 constexpr int kMaxGroupMats = 256;    // matrices per grouped launch (descriptor table in kernarg: a whole
                                       // 32-layer stack is one launch, one ramp-up and one tail)
