@@ -48,8 +48,8 @@ DECODE_MATS_PER_LAUNCH = 256
 # are separate runs of this file (commands in the named summaries under profiles/); the figures are theirs, for the
 # default workload only, and are not re-measured by the run that prints them.
 TRAFFIC = {
-    "decode_config3": (2908.5e6, "profiles/decode_hbm_traffic_config3_config5.txt"),
-    "decode_config5_M1": (7473.9e6 / 2, "profiles/decode_hbm_traffic_config3_config5.txt"),     # mean of the two launches of a step
+    "decode_config3": (2844.3e6, "profiles/decode_hbm_traffic_config3_config5.txt"),
+    "decode_config5_M1": (7309.3e6 / 2, "profiles/decode_hbm_traffic_config3_config5.txt"),     # mean of the two launches of a step
     "decode_config5_M16": (7885.2e6 / 2, "profiles/decode_hbm_traffic_config3_config5.txt"),
     "prefill_config4": (8.87e9, "profiles/prefill_and_mix_hbm_traffic.txt"),
     "proxy_8_layers": (3495.6e6, "profiles/proxy_kernel_trace_and_traffic_7b_layers.txt"),
